@@ -1,0 +1,217 @@
+/*
+ * seed_verify.h -- C ABI of the MI355X (gfx950) library for the batched target-model verification
+ * step of scheduled speculative decoding on a reasoning tree.
+ *
+ * What one verify step computes (paper Section 3.1 "Speculative Decoding", Section 3.4 Algorithm 1,
+ * verification process, and Appendix "Batch Inference": one verified draft sequence per batch entry):
+ *   for each of N draft branches, the target model scores the branch's gamma draft tokens in a single
+ *   forward pass over (shared prefix + branch-private context + pending token + drafts), then every
+ *   draft token is accepted with probability min(1, p_t/p_d) from left to right, and on the first
+ *   rejection one replacement token is drawn from the normalised max(0, p_t - p_d).
+ *
+ * Conventions common to every entry point
+ *   - All array arguments are DEVICE pointers owned by the caller (any allocator, e.g. a PyTorch
+ *     tensor's data_ptr) unless the comment says "host".  Scalars and the argument structs themselves
+ *     live on the host and are read before the call returns.
+ *   - Calls only enqueue work on the HIP stream given at init (or passed explicitly); they never
+ *     synchronise the device.  Outputs are valid once the caller has synchronised that stream.
+ *   - Return value: SEED_OK (0) or a negative SEED_E_* code; seed_last_error() gives a thread-local
+ *     human-readable message for the last failing call.  Argument errors are detected before any
+ *     kernel is launched.  Nothing throws or aborts across this boundary.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
+ *   - Matrices are row-major [out][in].  dtype 0: float32 weights and KV cache; dtype 1: bfloat16
+ *     weights and KV cache.  Logits, probabilities and uniforms are always float32; token ids and
+ *     lengths are int32.
+ */
+#ifndef SEED_VERIFY_H
+#define SEED_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SEED_OK 0
+#define SEED_E_INVALID_ARG (-1)
+#define SEED_E_SHAPE (-2)
+#define SEED_E_CAPACITY (-3)
+#define SEED_E_NULL_PTR (-4)
+#define SEED_E_UNSUPPORTED_DTYPE (-5)
+#define SEED_E_NOT_INIT (-6)
+#define SEED_E_HIP (-7)
+
+#define SEED_DTYPE_F32 0
+#define SEED_DTYPE_BF16 1
+
+/* seed_accept_args.probs_kind */
+#define SEED_KIND_LOGITS 0 /* p_or_logits holds raw logits; the kernel applies softmax(logits / temperature) */
+#define SEED_KIND_PROBS 1  /* p_or_logits already holds the target probabilities p                          */
+
+/* seed_step_args.flags / seed_draft_args.flags */
+#define SEED_STEP_PREFILL_SHARED 1 /* rows are prefix tokens appended to the shared KV cache (n_branches = 1) */
+#define SEED_STEP_GREEDY 2         /* temperature-0 verification: accept iff draft == argmax                  */
+#define SEED_STEP_COMMIT_ALL 4     /* no accept step: every fed row becomes private context (private prefill) */
+
+typedef struct seed_ctx seed_ctx; /* opaque; one per model instance */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
+    int32_t dtype;      /* SEED_DTYPE_F32 or SEED_DTYPE_BF16 */
+    float rms_eps;      /* RMSNorm epsilon                    */
+    float rope_theta;   /* rotary base; rotate-half pairing (i, i + head_dim/2) */
+    int32_t max_branches;        /* largest N of any step                                  */
+    int32_t max_rows_per_branch; /* largest T (= gamma, or gamma+1 with a bonus row)        */
+    int32_t max_shared;          /* capacity of the shared-prefix KV cache, tokens          */
+    int32_t max_private;         /* capacity of each branch's private context, tokens       */
+} seed_model_cfg;
+
+typedef struct {
+    const void *wq, *wk, *wv, *wo;      /* [H*dh][d], [H*dh][d], [H*dh][d], [d][H*dh] */
+    const void *wgate, *wup, *wdown;    /* [F][d], [F][d], [d][F]                     */
+    const void *norm_attn, *norm_ffn;   /* [d] RMSNorm gains                          */
+} seed_layer_w;
+
+typedef struct {
+    const void *tok_emb;        /* [V][d]                                    */
+    const void *norm_final;     /* [d]                                       */
+    const void *lm_head;        /* [V][d] (untied)                           */
+    const seed_layer_w *layers; /* HOST array of n_layers entries            */
+} seed_weights;
+
+/*
+ * Accept / reject / resample (paper Section 3.1; Algorithm 1, inner loop of the verification process).
+ *   Row j of branch b holds the target distribution that verifies draft token draft_tok[b][j].
+ *   accept iff  fl32(u_acc[b][j] * q[b][j][x]) < p[b][j][x]  (x = draft_tok[b][j]; one float32
+ *   multiply, strict comparison), left to right; a_b = number accepted.  At the first rejection one
+ *   token is drawn from norm(max(0, p - q)) of that row with u_res[b], using an integer fixed-point
+ *   inverse CDF (weights truncated to multiples of 2^-38, so the result does not depend on scan order).
+ *   With n_target_rows == gamma + 1 and every draft accepted, a bonus token is drawn from row gamma.
+ *   Uniforms must lie on the grid m * 2^-24, 0 <= m < 2^24.
+ *   greedy != 0: accept iff x == argmax of the row (lowest index on ties), otherwise emit the argmax;
+ *   q, u_acc, u_res and temperature are ignored and may be NULL; p_or_logits must hold logits.
+ * Outputs: accept_len[b] = a_b; out_tok[b][0..gamma] = the a_b accepted drafts, then the new token if
+ *   any, then -1 padding; n_out[b] = number of valid entries (a_b + 1, or gamma when all gamma drafts
+ *   were accepted without a bonus row); p_tok[b][j] = p(draft_tok[b][j]) as used in the test (optional).
+ *   private_len (optional, in/out): Algorithm 1's validated-length bookkeeping in cache terms,
+ *   private_len[b] += min(a_b + 1, n_target_rows).
+ */
+typedef struct {
+    int32_t n_branches;    /* N >= 0                                             */
+    int32_t gamma;         /* draft tokens per branch (the paper's k), >= 1      */
+    int32_t n_target_rows; /* gamma or gamma + 1                                 */
+    int32_t vocab;         /* V >= 1                                             */
+    int32_t probs_kind;    /* SEED_KIND_LOGITS or SEED_KIND_PROBS                */
+    int32_t greedy;        /* 0 / 1                                              */
+    float temperature;     /* > 0 unless greedy (LOGITS kind only)               */
+    const float *p_or_logits; /* [N][n_target_rows][V]                           */
+    const float *q;           /* [N][gamma][V]                                   */
+    const int32_t *draft_tok; /* [N][gamma], each in [0, V)                      */
+    const float *u_acc;       /* [N][gamma]                                      */
+    const float *u_res;       /* [N]                                             */
+    int32_t *accept_len;      /* [N]            out                              */
+    int32_t *out_tok;         /* [N][gamma + 1] out                              */
+    int32_t *n_out;           /* [N]            out                              */
+    float *p_tok;             /* [N][gamma]     out, may be NULL                 */
+    int32_t *private_len;     /* [N]            in/out, may be NULL              */
+} seed_accept_args;
+
+/*
+ * One target forward over N x T rows (paper Section 3.1: the drafts "along with c are passed to M_t to
+ * obtain their output distribution ... in parallel"), optionally followed by accept / resample.
+ *   row_tok[b][0] is the branch's pending token (validated, KV not yet cached); row_tok[b][j], j >= 1,
+ *   is draft token j.  Row j sits at position shared_len + private_len[b] + j and attends to the shared
+ *   prefix (read once for all branches), to the branch's private context and causally to rows 0..j of
+ *   its own branch.  logits[b][j] is the distribution that verifies draft token j+1.  The K/V of the
+ *   fed rows are appended after the branch's private context ("in flight"); committing a row is just
+ *   the private_len update done by the accept step.
+ *   flags: SEED_STEP_PREFILL_SHARED (n_branches must be 1; rows are appended to the shared cache at
+ *   position shared_len; private_len is ignored), SEED_STEP_GREEDY, SEED_STEP_COMMIT_ALL.
+ *   accept (optional): its p_or_logits / probs_kind / n_target_rows / n_branches / vocab fields are
+ *   filled in by the library from this step's logits; the remaining fields are the caller's.
+ * Errors: SEED_E_CAPACITY if N, T or shared_len + T exceed what the context was created for.  A branch
+ *   whose private_len would overflow max_private + max_rows_per_branch is detected on the device:
+ *   its out-of-range rows are dropped and bit 0 of the status word is set (seed_verify_status).
+ */
+typedef struct {
+    int32_t n_branches;       /* N                                                */
+    int32_t rows_per_branch;  /* T                                                */
+    int32_t flags;
+    int32_t shared_len;       /* S: valid tokens in the shared cache (host value) */
+    const int32_t *row_tok;   /* [N][T]                                           */
+    int32_t *private_len;     /* [N] in (out if accept / COMMIT_ALL)              */
+    float *logits_out;        /* [N][T][V] out, may be NULL                       */
+    const seed_accept_args *accept; /* host pointer, may be NULL                  */
+} seed_step_args;
+
+/*
+ * One autoregressive draft token for each of N branches (paper Section 3.1: drafts are sampled
+ * autoregressively from p_d; Algorithm 1, drafting process).  Runs the same forward with one row per
+ * branch (the pending token), writes q = softmax(logits / temperature) and draws the next token from
+ * q with u[b] by the fixed-point inverse CDF; private_len[b] += 1.  GREEDY: token = argmax, q is
+ * still written (with temperature 1).
+ *   q_out row b starts at q_out + b * q_stride; tok_out entry b at tok_out + b * tok_stride, so the
+ *   call can fill column j of q[N][gamma][V] and draft_tok[N][gamma] directly.
+ */
+typedef struct {
+    int32_t n_branches;
+    int32_t flags;
+    int32_t shared_len;
+    float temperature;
+    const int32_t *row_tok; /* [N] pending tokens                 */
+    int32_t *private_len;   /* [N] in/out                          */
+    const float *u;         /* [N]                                 */
+    float *q_out;           /* N rows of V, stride q_stride floats */
+    int64_t q_stride;
+    int32_t *tok_out;       /* N entries, stride tok_stride        */
+    int64_t tok_stride;
+    float *logits_out;      /* [N][V] out, may be NULL             */
+} seed_draft_args;
+
+/* Bytes of device workspace a context needs: repacked weights + KV caches + activations. 0 on error. */
+size_t seed_verify_workspace_bytes(const seed_model_cfg *cfg);
+
+/*
+ * Create a context.  Validates cfg, carves `workspace` (device memory, 256-byte aligned, at least
+ * seed_verify_workspace_bytes(cfg)), repacks the weights into it (the caller's weight tensors may be
+ * freed once the stream has been synchronised) and zeroes the KV caches.  hip_stream is a hipStream_t
+ * (NULL = the default stream) used by every later call on this context.
+ */
+int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weights *weights,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+int seed_verify_step(seed_ctx *ctx, const seed_step_args *args);
+int seed_draft_step(seed_ctx *ctx, const seed_draft_args *args);
+
+/* Stateless, model-free accept / resample on `hip_stream`; see seed_accept_args. */
+int seed_accept_resample(const seed_accept_args *args, void *hip_stream);
+
+/*
+ * Stateless draw x ~ probs rows by the fixed-point inverse CDF (the draft-side sampler of Section 3.1).
+ * probs: n_rows rows of V floats, row i at probs + i * row_stride; u: [n_rows]; tok_out: [n_rows].
+ */
+int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
+                      int32_t n_rows, int32_t vocab, void *hip_stream);
+
+/*
+ * Import externally produced KV for one layer (synthetic-KV protocol): k_shared / v_shared
+ * [H][shared_len][dh] (keys already rotated), k_private / v_private [n_branches][H][private_len][dh],
+ * all in the context's dtype, device pointers; private pointers may be NULL when private_len == 0.
+ */
+int seed_kv_load(seed_ctx *ctx, int32_t layer, const void *k_shared, const void *v_shared,
+                 int32_t shared_len, const void *k_private, const void *v_private,
+                 int32_t n_branches, int32_t private_len);
+
+/* Synchronises the context's stream and returns the device status word (0 = clean; bit 0 = a branch
+ * overflowed its private capacity) in *host_status, then clears it. */
+int seed_verify_status(seed_ctx *ctx, int32_t *host_status);
+
+void seed_verify_destroy(seed_ctx *ctx);
+
+const char *seed_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEED_VERIFY_H */

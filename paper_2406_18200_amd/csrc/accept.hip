@@ -1,0 +1,293 @@
+// Fused accept / reject / resample and the draft-side softmax + draw.
+//
+// Rule (paper Section 3.1; Algorithm 1, inner loop of the verification process): draft token x_j is
+// accepted with probability min(1, p_t(x_j)/p_d(x_j)), checked left to right; the first rejection ends
+// the check and one replacement token is returned by the target model.  The replacement is drawn from
+// norm(max(0, p_t - p_d)), the distribution that keeps the output law equal to the target's.
+//
+// One workgroup (16 wavefronts) per branch.  Softmax statistics are wavefront-shuffle reductions; the
+// draw is an integer fixed-point inverse CDF: weights are truncated to multiples of 2^-38 and summed
+// as 64-bit integers, so the parallel scan gives the same token as a serial one.
+#include "seed_internal.h"
+
+namespace seedv {
+namespace {
+
+constexpr int kBlock = 1024;
+constexpr int kWaves = kBlock / 64;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+struct Shared {
+    float red[kWaves];
+    unsigned long long tot[kWaves];
+    int idx[kWaves];
+    int tok;
+};
+
+__device__ float block_max(float v, Shared &sm) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm.red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm.red[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) r = fmaxf(r, sm.red[i]);
+    return r;
+}
+__device__ float block_sum(float v, Shared &sm) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm.red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm.red[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) r += sm.red[i];   // fixed order: deterministic
+    return r;
+}
+
+// argmax with the lowest index on ties
+__device__ int block_argmax(const float *row, int V, Shared &sm) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += kBlock) {
+        float x = row[v];
+        if (x > bv) { bv = x; bi = v; }               // strided ascending: first max kept
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(bv, off);
+        int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sm.red[threadIdx.x >> 6] = bv; sm.idx[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    float rv = sm.red[0];
+    int ri = sm.idx[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) {
+        float ov = sm.red[i];
+        int oi = sm.idx[i];
+        if (ov > rv || (ov == rv && oi < ri)) { rv = ov; ri = oi; }
+    }
+    return ri;
+}
+
+// A row of target probabilities, either given or defined by softmax(logits / temperature).
+struct TargetRow {
+    const float *src;
+    int is_logits;
+    float mx, sum, temp;
+    __device__ __forceinline__ float p(int v) const {
+        if (!is_logits) return src[v];
+        return __fdiv_rn(expf(__fdiv_rn(src[v] - mx, temp)), sum);
+    }
+};
+
+__device__ TargetRow make_row(const float *src, int is_logits, float temp, int V, Shared &sm) {
+    TargetRow r{src, is_logits, 0.f, 1.f, temp};
+    if (!is_logits) return r;
+    float m = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += kBlock) m = fmaxf(m, src[v]);
+    r.mx = block_max(m, sm);
+    float s = 0.f;
+    for (int v = threadIdx.x; v < V; v += kBlock) s += expf(__fdiv_rn(src[v] - r.mx, temp));
+    r.sum = block_sum(s, sm);
+    return r;
+}
+
+__device__ __forceinline__ unsigned long long to_fixed(float w) {
+    // w in [0, 1]: scaling by 2^38 is exact, the conversion truncates
+    return (unsigned long long)(__fmul_rn(w, 274877906944.0f));
+}
+
+// weight of token v: residual max(0, p - q) (one float32 subtraction) or p itself
+template <int RESIDUAL>
+__device__ __forceinline__ unsigned long long weight_fixed(const TargetRow &row, const float *q, int v) {
+    float p = row.p(v);
+    if (RESIDUAL) {
+        float r = __fsub_rn(p, q[v]);
+        return r > 0.f ? to_fixed(r) : 0ull;
+    }
+    return to_fixed(p);
+}
+
+// Fixed-point inverse CDF over [0, V): token = min{v : sum_{w<=v} k_w > (m * Z) >> 24}, u = m 2^-24.
+// Returns -1 if every weight truncates to zero.  Uniform control flow: every thread of the block calls.
+template <int RESIDUAL>
+__device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, Shared &sm) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int per = (((V + kWaves - 1) / kWaves) + 63) & ~63;
+    const int base = wave * per;
+    const int end = min(V, base + per);
+    unsigned long long local = 0;
+    for (int v = base + lane; v < end; v += 64) local += weight_fixed<RESIDUAL>(row, q, v);
+    local = wave_sum_u64(local);
+    __syncthreads();
+    if (lane == 0) sm.tot[wave] = local;
+    if (threadIdx.x == 0) sm.tok = -1;
+    __syncthreads();
+    unsigned long long Z = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) Z += sm.tot[i];
+    if (Z == 0) return -1;
+    const unsigned long long m24 = (unsigned long long)(__fmul_rn(u, 16777216.0f));
+    const unsigned long long t = (m24 * Z) >> 24;
+    unsigned long long run = 0;
+    int target = 0;
+    for (int i = 0; i < kWaves; ++i) {
+        unsigned long long nx = run + sm.tot[i];
+        if (t < nx) { target = i; break; }
+        run = nx;
+    }
+    if (wave == target) {
+        for (int i = base; i < end; i += 64) {
+            int v = i + lane;
+            unsigned long long k = v < end ? weight_fixed<RESIDUAL>(row, q, v) : 0ull;
+            unsigned long long incl = k;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                unsigned long long o = __shfl_up(incl, off);
+                if (lane >= off) incl += o;
+            }
+            unsigned long long hit = __ballot(run + incl > t);
+            if (hit) {
+                if (lane == 0) sm.tok = i + (__ffsll((long long)hit) - 1);
+                break;
+            }
+            run += __shfl(incl, 63);
+        }
+    }
+    __syncthreads();
+    return sm.tok;
+}
+
+__global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a) {
+    __shared__ Shared sm;
+    const int b = blockIdx.x;
+    const int G = a.gamma, Tp = a.n_target_rows, V = a.vocab;
+    const int is_logits = a.probs_kind == SEED_KIND_LOGITS;
+    int acc = 0, new_tok = -1;
+    bool rejected = false;
+    for (int j = 0; j < G; ++j) {
+        if (rejected && (a.p_tok == nullptr || a.greedy)) break;
+        const float *src = a.p_or_logits + ((size_t)b * Tp + j) * V;
+        const int x = a.draft_tok[b * G + j];
+        bool ok;
+        int best = -1;
+        TargetRow row{src, 0, 0.f, 1.f, 1.f};
+        if (a.greedy) {
+            best = block_argmax(src, V, sm);
+            ok = (x == best);
+        } else {
+            row = make_row(src, is_logits, a.temperature, V, sm);
+            const float pj = row.p(x);
+            if (a.p_tok != nullptr && threadIdx.x == 0) a.p_tok[b * G + j] = pj;
+            const float qj = a.q[((size_t)b * G + j) * V + x];
+            ok = __fmul_rn(a.u_acc[b * G + j], qj) < pj;
+        }
+        if (rejected) continue;
+        if (ok) { ++acc; continue; }
+        rejected = true;
+        if (a.greedy) {
+            new_tok = best;
+        } else {
+            const float *q = a.q + ((size_t)b * G + j) * V;
+            new_tok = draw_fixed<1>(row, q, a.u_res[b], V, sm);
+            if (new_tok < 0) new_tok = draw_fixed<0>(row, q, a.u_res[b], V, sm);
+        }
+    }
+    if (!rejected && Tp == G + 1) {
+        const float *src = a.p_or_logits + ((size_t)b * Tp + G) * V;
+        if (a.greedy) {
+            new_tok = block_argmax(src, V, sm);
+        } else {
+            TargetRow row = make_row(src, is_logits, a.temperature, V, sm);
+            new_tok = draw_fixed<0>(row, nullptr, a.u_res[b], V, sm);
+        }
+    }
+    if (a.greedy && a.p_tok != nullptr && threadIdx.x < G) a.p_tok[b * G + threadIdx.x] = 0.f;
+    if (threadIdx.x <= G) {
+        const int j = threadIdx.x;
+        int t = -1;
+        if (j < acc) t = a.draft_tok[b * G + j];
+        else if (j == acc) t = new_tok;
+        a.out_tok[b * (G + 1) + j] = t;
+    }
+    if (threadIdx.x == 0) {
+        a.accept_len[b] = acc;
+        a.n_out[b] = acc + (new_tok >= 0 ? 1 : 0);
+        if (a.private_len != nullptr) a.private_len[b] += min(acc + 1, Tp);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
+        const float *logits, int64_t logits_stride, float temperature, int greedy, const float *u,
+        float *q_out, int64_t q_stride, int32_t *tok_out, int64_t tok_stride, int32_t *private_len, int V) {
+    __shared__ Shared sm;
+    const int b = blockIdx.x;
+    const float *src = logits + (size_t)b * logits_stride;
+    TargetRow row = make_row(src, 1, temperature, V, sm);
+    if (q_out != nullptr) {
+        float *dst = q_out + (size_t)b * q_stride;
+        for (int v = threadIdx.x; v < V; v += kBlock) dst[v] = row.p(v);
+    }
+    int tok;
+    if (greedy) tok = block_argmax(src, V, sm);
+    else tok = draw_fixed<0>(row, nullptr, u[b], V, sm);
+    if (threadIdx.x == 0) {
+        tok_out[(size_t)b * tok_stride] = tok;
+        if (private_len != nullptr) private_len[b] += 1;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void sample_probs_kernel(const float *probs, int64_t row_stride,
+                                                              const float *u, int32_t *tok_out, int V) {
+    __shared__ Shared sm;
+    const int b = blockIdx.x;
+    TargetRow row{probs + (size_t)b * row_stride, 0, 0.f, 1.f, 1.f};
+    int tok = draw_fixed<0>(row, nullptr, u[b], V, sm);
+    if (threadIdx.x == 0) tok_out[b] = tok;
+}
+
+}  // namespace
+
+int launch_accept(const seed_accept_args &a, hipStream_t st) {
+    if (a.n_branches == 0) return SEED_OK;
+    hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a);
+    return hip_fail(hipGetLastError(), "accept_resample launch");
+}
+
+int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
+                          const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
+                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, hipStream_t st) {
+    if (n_rows == 0) return SEED_OK;
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_rows), dim3(kBlock), 0, st, logits, logits_stride,
+                       temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, vocab);
+    return hip_fail(hipGetLastError(), "softmax_sample launch");
+}
+
+int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
+                        int n_rows, int vocab, hipStream_t st) {
+    if (n_rows == 0) return SEED_OK;
+    hipLaunchKernelGGL(sample_probs_kernel, dim3(n_rows), dim3(kBlock), 0, st, probs, row_stride, u,
+                       tok_out, vocab);
+    return hip_fail(hipGetLastError(), "sample_probs launch");
+}
+
+}  // namespace seedv

@@ -1,0 +1,35 @@
+// Small device-side helpers for gfx950 kernels (wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace seedv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// float -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// Offset (in elements) of activation element (row r, column c) in the MFMA-fragment-packed layout
+// [m-tile][k-tile][lane][8]: 16 rows x 32 columns per 1 KiB tile, lane = (r % 16) + 16 * ((c % 32) / 8).
+__device__ __host__ __forceinline__ size_t packed_offset(int r, int c, int KT) {
+    return ((((size_t)(r >> 4) * KT + (c >> 5)) * 64) + (r & 15) + 16 * ((c & 31) >> 3)) * 8 + (c & 7);
+}
+
+__device__ __forceinline__ float wave_reduce_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+}  // namespace seedv

@@ -1,0 +1,283 @@
+// Row-wise stages between the projections: embedding gather, split-K reduction + residual add +
+// RMSNorm, rotary embedding + KV append, SwiGLU.  All are O(M x d) work on at most 128 rows; they exist
+// to hand the next projection its activation tile in MFMA B-fragment order (bf16 path) and to keep the
+// residual stream and the normalisation statistics in fp32.
+#include "seed_internal.h"
+#include "device_utils.h"
+
+namespace seedv {
+namespace {
+
+template <bool BF16>
+__device__ __forceinline__ float load_w(const void *p, size_t i) {
+    if (BF16) return bf2f(reinterpret_cast<const uint16_t *>(p)[i]);
+    return reinterpret_cast<const float *>(p)[i];
+}
+
+// store 8 consecutive activation columns c..c+7 (c % 8 == 0) of row r
+template <bool BF16>
+__device__ __forceinline__ void store_act8(void *base, int r, int c, int K, const float *v) {
+    if (BF16) {
+        u32x4 w = {pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7])};
+        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(base) + packed_offset(r, c, K >> 5)) = w;
+    } else {
+        float *d = reinterpret_cast<float *>(base) + (size_t)r * K + c;
+        *reinterpret_cast<f32x4 *>(d) = (f32x4){v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f32x4 *>(d + 4) = (f32x4){v[4], v[5], v[6], v[7]};
+    }
+}
+
+__device__ float block_sum_256(float v) {
+    __shared__ float red[4];
+    v = wave_reduce_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// x[r] = (tok ? emb[tok[r]] : x[r]) + sum_sk part[sk][r];  act[r] = rmsnorm(x[r]) * gain
+template <bool BF16>
+__global__ __launch_bounds__(256) void rownorm_kernel(float *__restrict__ x, const float *__restrict__ part,
+                                                      int SK, int64_t split_stride,
+                                                      const int32_t *__restrict__ tok, const void *emb, int vocab,
+                                                      const void *gain, float eps, void *act, int M, int d) {
+    const int r = blockIdx.x;
+    const int n8 = d >> 3;
+    if (r >= M) {
+        const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int c8 = threadIdx.x; c8 < n8; c8 += 256) store_act8<BF16>(act, r, c8 * 8, d, z);
+        return;
+    }
+    int t = 0;
+    if (tok != nullptr) t = min(max(tok[r], 0), vocab - 1);
+    float ss = 0.f;
+    for (int c8 = threadIdx.x; c8 < n8; c8 += 256) {
+        const int c = c8 * 8;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            v[i] = tok != nullptr ? load_w<BF16>(emb, (size_t)t * d + c + i) : x[(size_t)r * d + c + i];
+        for (int s = 0; s < SK; ++s) {
+            const float *p = part + (size_t)s * split_stride + (size_t)r * d + c;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] += p[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            x[(size_t)r * d + c + i] = v[i];
+            ss += v[i] * v[i];
+        }
+    }
+    ss = block_sum_256(ss);
+    const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c8 = threadIdx.x; c8 < n8; c8 += 256) {
+        const int c = c8 * 8;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = x[(size_t)r * d + c + i] * rinv * load_w<BF16>(gain, c + i);
+        store_act8<BF16>(act, r, c, d, v);
+    }
+}
+
+// h[r][f] = silu(gate) * up from the (split-K partial) gate/up projection; INTERLEAVED: gate and up
+// alternate in 16-column tiles (bf16 packed weights), otherwise gate columns [0,F) then up [F,2F).
+template <bool BF16, bool INTERLEAVED>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ part, int SK, int64_t split_stride,
+                                                     void *act, int M, int F) {
+    const int r = blockIdx.y;
+    const int f = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (f >= F) return;
+    float h[8];
+    if (r >= M) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) h[i] = 0.f;
+    } else {
+        const int gcol = INTERLEAVED ? 32 * (f >> 4) + (f & 15) : f;
+        const int ucol = INTERLEAVED ? gcol + 16 : F + f;
+        float g[8], u[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) g[i] = u[i] = 0.f;
+        for (int s = 0; s < SK; ++s) {
+            const float *p = part + (size_t)s * split_stride + (size_t)r * 2 * F;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                g[i] += p[gcol + i];
+                u[i] += p[ucol + i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) h[i] = g[i] / (1.0f + expf(-g[i])) * u[i];
+    }
+    store_act8<BF16>(act, r, f, F, h);
+}
+
+// Reduce the QKV partials, rotate q and k (pair (i, i + dh/2), angle pos * theta^(-2i/dh)), store q for the
+// attention kernel and append k, v to the KV cache.
+//   bf16: K cache [H][cap][dh], V cache transposed [H][dh][cap] (the attention kernel reads V^T fragments)
+//   fp32: K and V caches [H][cap][dh]
+template <bool BF16>
+__global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ part, int SK, int64_t split_stride,
+                                                      void *q_out, void *k_shared, void *v_shared,
+                                                      void *k_priv, void *v_priv, const int32_t *private_len,
+                                                      int M, int T, int H, int dh, int S, int prefill_shared,
+                                                      int cap_shared, int cap_priv, int max_private,
+                                                      float theta, int32_t *status) {
+    const int r = blockIdx.x;
+    const int HD = H * dh, half = dh >> 1;
+    if (r >= M) {   // padding rows of the q tile: zeros
+        for (int c = threadIdx.x; c < HD; c += 256) {
+            if (BF16) reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c] = 0;
+            else reinterpret_cast<float *>(q_out)[(size_t)r * HD + c] = 0.f;
+        }
+        return;
+    }
+    const int b = r / T, j = r - b * T;
+    int pos, idx, cap;
+    bool store_kv = true;
+    if (prefill_shared) {
+        pos = S + j;
+        idx = pos;
+        cap = cap_shared;
+    } else {
+        int pl = private_len[b];
+        if (pl < 0 || pl > max_private) {          // capacity overflow: drop the append, flag it
+            if (threadIdx.x == 0) atomicOr(status, 1);
+            pl = min(max(pl, 0), max_private);
+            store_kv = false;
+        }
+        pos = S + pl + j;
+        idx = pl + j;
+        cap = cap_priv;
+    }
+    const float *row = part + (size_t)r * 3 * HD;
+    for (int p = threadIdx.x; p < H * half; p += 256) {
+        const int h = p / half, i = p - h * half;
+        float q1 = 0.f, q2 = 0.f, k1 = 0.f, k2 = 0.f, v1 = 0.f, v2 = 0.f;
+        for (int s = 0; s < SK; ++s) {
+            const float *pr = row + (size_t)s * split_stride + h * dh + i;
+            q1 += pr[0];
+            q2 += pr[half];
+            k1 += pr[HD];
+            k2 += pr[HD + half];
+            v1 += pr[2 * HD];
+            v2 += pr[2 * HD + half];
+        }
+        const double inv_freq = pow((double)theta, -2.0 * (double)i / (double)dh);
+        double sn, cs;
+        sincos((double)pos * inv_freq, &sn, &cs);
+        const float c = (float)cs, s_ = (float)sn;
+        const float qa = q1 * c - q2 * s_, qb = q2 * c + q1 * s_;
+        const float ka = k1 * c - k2 * s_, kb = k2 * c + k1 * s_;
+        const size_t qo = (size_t)r * HD + h * dh + i;
+        if (BF16) {
+            uint16_t *q16 = reinterpret_cast<uint16_t *>(q_out);
+            q16[qo] = f2bf(qa);
+            q16[qo + half] = f2bf(qb);
+            if (store_kv) {
+                uint16_t *kc = reinterpret_cast<uint16_t *>(prefill_shared ? k_shared : k_priv);
+                uint16_t *vc = reinterpret_cast<uint16_t *>(prefill_shared ? v_shared : v_priv);
+                const size_t head = prefill_shared ? (size_t)h : ((size_t)b * H + h);
+                kc[(head * cap + idx) * dh + i] = f2bf(ka);
+                kc[(head * cap + idx) * dh + i + half] = f2bf(kb);
+                vc[(head * dh + i) * cap + idx] = f2bf(v1);
+                vc[(head * dh + i + half) * cap + idx] = f2bf(v2);
+            }
+        } else {
+            float *q32 = reinterpret_cast<float *>(q_out);
+            q32[qo] = qa;
+            q32[qo + half] = qb;
+            if (store_kv) {
+                float *kc = reinterpret_cast<float *>(prefill_shared ? k_shared : k_priv);
+                float *vc = reinterpret_cast<float *>(prefill_shared ? v_shared : v_priv);
+                const size_t head = prefill_shared ? (size_t)h : ((size_t)b * H + h);
+                kc[(head * cap + idx) * dh + i] = ka;
+                kc[(head * cap + idx) * dh + i + half] = kb;
+                vc[(head * cap + idx) * dh + i] = v1;
+                vc[(head * cap + idx) * dh + i + half] = v2;
+            }
+        }
+    }
+}
+
+// Import of externally produced KV: src [heads][len][dh] -> K cache [heads][cap][dh] and, for bf16,
+// V cache transposed [heads][dh][cap].
+template <bool BF16, bool TRANSPOSE>
+__global__ void kv_import_kernel(const void *src, void *dst, int heads, int len, int dh, int cap) {
+    const size_t n = (size_t)heads * len * dh;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const int i = e % dh;
+        const size_t t = e / dh;
+        const int tokn = t % len;
+        const size_t h = t / len;
+        const size_t o = TRANSPOSE ? (h * dh + i) * cap + tokn : (h * cap + tokn) * dh + i;
+        if (BF16) reinterpret_cast<uint16_t *>(dst)[o] = reinterpret_cast<const uint16_t *>(src)[e];
+        else reinterpret_cast<float *>(dst)[o] = reinterpret_cast<const float *>(src)[e];
+    }
+}
+
+__global__ void add_len_kernel(int32_t *len, int n, int delta) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) len[i] += delta;
+}
+
+}  // namespace
+
+int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,
+                   const void *emb, int vocab, const void *gain, float eps, void *act, int M, int Mp, int d,
+                   hipStream_t st) {
+    if (bf16)
+        hipLaunchKernelGGL(rownorm_kernel<true>, dim3(Mp), dim3(256), 0, st, x, part, SK, split_stride, tok, emb,
+                           vocab, gain, eps, act, M, d);
+    else
+        hipLaunchKernelGGL(rownorm_kernel<false>, dim3(Mp), dim3(256), 0, st, x, part, SK, split_stride, tok, emb,
+                           vocab, gain, eps, act, M, d);
+    return hip_fail(hipGetLastError(), "rownorm launch");
+}
+
+int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, void *act, int M, int Mp, int F,
+                  hipStream_t st) {
+    dim3 grid((F / 8 + 255) / 256, Mp);
+    if (bf16)
+        hipLaunchKernelGGL((swiglu_kernel<true, true>), grid, dim3(256), 0, st, part, SK, split_stride, act, M, F);
+    else
+        hipLaunchKernelGGL((swiglu_kernel<false, false>), grid, dim3(256), 0, st, part, SK, split_stride, act, M, F);
+    return hip_fail(hipGetLastError(), "swiglu launch");
+}
+
+int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, void *k_shared,
+                   void *v_shared, void *k_priv, void *v_priv, const int32_t *private_len, int M, int Mq,
+                   int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
+                   int max_private, float theta, int32_t *status, hipStream_t st) {
+    if (bf16)
+        hipLaunchKernelGGL(rope_kv_kernel<true>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
+                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S, prefill_shared,
+                           cap_shared, cap_priv, max_private, theta, status);
+    else
+        hipLaunchKernelGGL(rope_kv_kernel<false>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
+                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S, prefill_shared,
+                           cap_shared, cap_priv, max_private, theta, status);
+    return hip_fail(hipGetLastError(), "rope_kv launch");
+}
+
+int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
+                     hipStream_t st) {
+    const size_t n = (size_t)heads * len * dh;
+    if (n == 0) return SEED_OK;
+    const unsigned blocks = (unsigned)((n + 255) / 256 > 65535 ? 65535 : (n + 255) / 256);
+    if (bf16 && transpose)
+        hipLaunchKernelGGL((kv_import_kernel<true, true>), dim3(blocks), dim3(256), 0, st, src, dst, heads, len, dh, cap);
+    else if (bf16)
+        hipLaunchKernelGGL((kv_import_kernel<true, false>), dim3(blocks), dim3(256), 0, st, src, dst, heads, len, dh, cap);
+    else
+        hipLaunchKernelGGL((kv_import_kernel<false, false>), dim3(blocks), dim3(256), 0, st, src, dst, heads, len, dh, cap);
+    return hip_fail(hipGetLastError(), "kv_import launch");
+}
+
+int launch_add_len(int32_t *len, int n, int delta, hipStream_t st) {
+    if (n == 0) return SEED_OK;
+    hipLaunchKernelGGL(add_len_kernel, dim3((n + 63) / 64), dim3(64), 0, st, len, n, delta);
+    return hip_fail(hipGetLastError(), "add_len launch");
+}
+
+}  // namespace seedv

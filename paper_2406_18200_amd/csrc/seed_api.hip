@@ -1,0 +1,525 @@
+// C-ABI entry points: argument validation, workspace layout, weight repacking and the per-step
+// sequence of kernel launches.  Every entry point validates on the host first and only then touches HIP.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "seed_internal.h"
+
+namespace seedv {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    if (e == hipSuccess) return SEED_OK;
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return SEED_E_HIP;
+}
+
+namespace {
+
+constexpr int kMaxSplitK = 16;
+constexpr int kMaxAttnSlots = 128;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    size_t es;                    // bytes per weight / KV element
+    int HD, M_cap, Mp_cap, Mq_cap, cap_s, cap_p;
+    // weights
+    size_t w_qkv, w_o, w_gu, w_d, g_attn, g_ffn, layer_stride, layers0;
+    size_t emb, g_final, lm;
+    // KV caches (per-layer strides)
+    size_t ks, vs, kp, vp, ks_stride, kp_stride;
+    // activations
+    size_t x, act, part, q, o_part, ml_part, logits, status;
+    size_t part_floats;
+    size_t total;
+};
+
+int validate_cfg(const seed_model_cfg *c) {
+    if (c == nullptr) { set_error("cfg is NULL"); return SEED_E_NULL_PTR; }
+    if (c->dtype != SEED_DTYPE_F32 && c->dtype != SEED_DTYPE_BF16) {
+        set_error("unsupported dtype %d", c->dtype);
+        return SEED_E_UNSUPPORTED_DTYPE;
+    }
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->head_dim < 2 || c->d_ff < 1 || c->vocab < 1 ||
+        c->max_branches < 1 || c->max_rows_per_branch < 1 || c->max_shared < 0 || c->max_private < 0) {
+        set_error("model dimensions and capacities must be positive");
+        return SEED_E_INVALID_ARG;
+    }
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) {
+        set_error("rms_eps must be >= 0 and rope_theta > 0");
+        return SEED_E_INVALID_ARG;
+    }
+    const long HD = (long)c->n_heads * c->head_dim;
+    if (c->head_dim % 2) { set_error("head_dim must be even"); return SEED_E_SHAPE; }
+    if (c->dtype == SEED_DTYPE_BF16) {
+        if (c->d_model % 32 || c->d_ff % 32 || HD % 32 || c->vocab % 16) {
+            set_error("bf16 path needs d_model, d_ff, n_heads*head_dim multiples of 32 and vocab a multiple of 16");
+            return SEED_E_SHAPE;
+        }
+        if (c->head_dim != 64 && c->head_dim != 128) {
+            set_error("bf16 path supports head_dim 64 or 128");
+            return SEED_E_SHAPE;
+        }
+        if ((long)c->max_branches * c->max_rows_per_branch > 128) {
+            set_error("bf16 path supports at most 128 rows per step (max_branches * max_rows_per_branch)");
+            return SEED_E_CAPACITY;
+        }
+    } else {
+        if (c->d_model % 8 || c->d_ff % 8 || HD % 8) {
+            set_error("fp32 path needs d_model, d_ff, n_heads*head_dim multiples of 8");
+            return SEED_E_SHAPE;
+        }
+        const long keys = (long)round_up(c->max_shared, 32) + round_up(c->max_private + c->max_rows_per_branch, 32);
+        if (keys * 4 > 60 * 1024) {
+            set_error("fp32 path supports at most %d cached keys per row", 60 * 1024 / 4);
+            return SEED_E_CAPACITY;
+        }
+        if ((long)c->max_branches * c->max_rows_per_branch > 4096) {
+            set_error("fp32 path supports at most 4096 rows per step");
+            return SEED_E_CAPACITY;
+        }
+    }
+    return SEED_OK;
+}
+
+Layout make_layout(const seed_model_cfg &c) {
+    Layout L{};
+    const bool bf = c.dtype == SEED_DTYPE_BF16;
+    L.es = bf ? 2 : 4;
+    const size_t d = c.d_model, F = c.d_ff, V = c.vocab, H = c.n_heads, dh = c.head_dim;
+    L.HD = (int)(H * dh);
+    const size_t HD = L.HD;
+    L.M_cap = c.max_branches * c.max_rows_per_branch;
+    L.Mp_cap = round_up(L.M_cap, 16);
+    L.Mq_cap = round_up(L.M_cap, 32);
+    L.cap_s = round_up(c.max_shared > 0 ? c.max_shared : 1, 32);
+    L.cap_p = round_up(c.max_private + c.max_rows_per_branch, 32);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    // one layer's weights
+    size_t lo = 0;
+    auto ltake = [&](size_t bytes) { size_t o = lo; lo = align_up(lo + bytes, 256); return o; };
+    L.w_qkv = ltake(3 * HD * d * L.es);
+    L.w_o = ltake(d * HD * L.es);
+    L.w_gu = ltake(2 * F * d * L.es);
+    L.w_d = ltake(d * F * L.es);
+    L.g_attn = ltake(d * L.es);
+    L.g_ffn = ltake(d * L.es);
+    L.layer_stride = lo;
+    L.layers0 = take(L.layer_stride * c.n_layers);
+    L.emb = take(V * d * L.es);
+    L.g_final = take(d * L.es);
+    L.lm = take(V * d * L.es);
+    L.ks_stride = align_up(H * L.cap_s * dh * L.es, 256);
+    L.kp_stride = align_up((size_t)c.max_branches * H * L.cap_p * dh * L.es, 256);
+    L.ks = take(L.ks_stride * c.n_layers);
+    L.vs = take(L.ks_stride * c.n_layers);
+    L.kp = take(L.kp_stride * c.n_layers);
+    L.vp = take(L.kp_stride * c.n_layers);
+    size_t widest = 3 * HD;
+    if (2 * F > widest) widest = 2 * F;
+    if (d > widest) widest = d;
+    size_t kmax = d > F ? d : F;
+    if (HD > kmax) kmax = HD;
+    L.x = take((size_t)L.Mp_cap * d * 4);
+    L.act = take((size_t)L.Mp_cap * kmax * L.es);
+    L.part_floats = (size_t)(bf ? kMaxSplitK : 1) * L.M_cap * widest;
+    L.part = take(L.part_floats * 4);
+    L.q = take((size_t)L.Mq_cap * HD * L.es);
+    L.o_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * HD * 4 : 256);
+    L.ml_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * H * 2 * 4 : 256);
+    L.logits = take((size_t)L.M_cap * V * 4);
+    L.status = take(256);
+    L.total = off;
+    return L;
+}
+
+// split-K factor: enough wavefronts to keep 256 CUs streaming, at least 8 k-tiles per split
+int pick_split_k(int n_groups, int KT) {
+    int sk = (2048 + n_groups - 1) / n_groups;
+    if (sk > kMaxSplitK) sk = kMaxSplitK;
+    while (sk > 1 && KT / sk < 8) --sk;
+    return sk < 1 ? 1 : sk;
+}
+
+}  // namespace
+}  // namespace seedv
+
+using namespace seedv;
+
+struct seed_ctx {
+    seed_model_cfg cfg;
+    Layout L;
+    char *ws;
+    hipStream_t stream;
+    bool bf16;
+};
+
+namespace {
+
+inline void *at(const seed_ctx *c, size_t off) { return c->ws + off; }
+inline void *layer_w(const seed_ctx *c, int l, size_t off) { return c->ws + c->L.layers0 + c->L.layer_stride * l + off; }
+
+int check_accept_args(const seed_accept_args *a) {
+    if (a == nullptr) { set_error("accept args is NULL"); return SEED_E_NULL_PTR; }
+    if (a->n_branches < 0 || a->gamma < 1 || a->vocab < 1) {
+        set_error("accept: need n_branches >= 0, gamma >= 1, vocab >= 1");
+        return SEED_E_INVALID_ARG;
+    }
+    if (a->n_target_rows != a->gamma && a->n_target_rows != a->gamma + 1) {
+        set_error("accept: n_target_rows must be gamma or gamma + 1");
+        return SEED_E_SHAPE;
+    }
+    if (a->gamma > 1023) { set_error("accept: gamma must be < 1024"); return SEED_E_CAPACITY; }
+    if (a->probs_kind != SEED_KIND_LOGITS && a->probs_kind != SEED_KIND_PROBS) {
+        set_error("accept: probs_kind must be SEED_KIND_LOGITS or SEED_KIND_PROBS");
+        return SEED_E_INVALID_ARG;
+    }
+    if (a->n_branches == 0) return SEED_OK;
+    if (!a->p_or_logits || !a->draft_tok || !a->accept_len || !a->out_tok || !a->n_out) {
+        set_error("accept: p_or_logits, draft_tok, accept_len, out_tok, n_out must be non-NULL");
+        return SEED_E_NULL_PTR;
+    }
+    if (a->greedy) {
+        if (a->probs_kind != SEED_KIND_LOGITS) {
+            set_error("accept: greedy mode needs logits");
+            return SEED_E_INVALID_ARG;
+        }
+    } else {
+        if (!a->q || !a->u_acc || !a->u_res) {
+            set_error("accept: q, u_acc, u_res must be non-NULL unless greedy");
+            return SEED_E_NULL_PTR;
+        }
+        if (a->probs_kind == SEED_KIND_LOGITS && !(a->temperature > 0.f)) {
+            set_error("accept: temperature must be > 0");
+            return SEED_E_INVALID_ARG;
+        }
+    }
+    return SEED_OK;
+}
+
+// The forward pass over M = N*T rows; leaves logits (if wanted) in `logits`.
+int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
+                const int32_t *private_len, float *logits) {
+    const seed_model_cfg &g = c->cfg;
+    const Layout &L = c->L;
+    hipStream_t st = c->stream;
+    const bool bf = c->bf16;
+    const int M = N * T, Mp = bf ? round_up(M, 16) : M, Mq = bf ? round_up(M, 32) : M;
+    const int d = g.d_model, F = g.d_ff, H = g.n_heads, dh = g.head_dim, HD = L.HD, V = g.vocab;
+    const int m_tiles = Mp / 16;
+    float *x = (float *)at(c, L.x);
+    void *act = at(c, L.act);
+    float *part = (float *)at(c, L.part);
+    void *q = at(c, L.q);
+    int32_t *status = (int32_t *)at(c, L.status);
+    int rc;
+
+    auto gemm = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
+                    int64_t *stride_out) -> int {
+        if (!bf) {
+            *sk_out = 1;
+            *stride_out = 0;
+            return launch_gemm_f32(W, act, out, M, Nout, K, ld, st);
+        }
+        const int NT = Nout / 16, KT = K / 32;
+        const int tn = gemm_bf16_pick_tn(NT, m_tiles);
+        int sk = allow_split ? pick_split_k(NT / tn, KT) : 1;
+        while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
+        *sk_out = sk;
+        *stride_out = (int64_t)M * Nout;
+        return launch_gemm_bf16(W, act, out, Nout, K, m_tiles, sk, M, *stride_out, ld, st);
+    };
+
+    int ks_shared = 1, keys_per_range = 32, ks_priv = 0;
+    if (bf) {
+        attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, L.cap_p, prefill_shared, &ks_shared, &keys_per_range,
+                       &ks_priv);
+        if (ks_shared + ks_priv > kMaxAttnSlots) {
+            set_error("attention plan needs %d partial slots (max %d)", ks_shared + ks_priv, kMaxAttnSlots);
+            return SEED_E_CAPACITY;
+        }
+    }
+
+    rc = launch_rownorm(bf, x, nullptr, 0, 0, row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), g.rms_eps, act, M,
+                        Mp, d, st);
+    if (rc) return rc;
+    for (int l = 0; l < g.n_layers; ++l) {
+        int sk;
+        int64_t stride;
+        rc = gemm(layer_w(c, l, L.w_qkv), 3 * HD, d, part, 3 * HD, true, &sk, &stride);
+        if (rc) return rc;
+        void *ksl = c->ws + L.ks + L.ks_stride * l, *vsl = c->ws + L.vs + L.ks_stride * l;
+        void *kpl = c->ws + L.kp + L.kp_stride * l, *vpl = c->ws + L.vp + L.kp_stride * l;
+        rc = launch_rope_kv(bf, part, sk, stride, q, ksl, vsl, kpl, vpl, private_len, M, Mq, T, H, dh, S,
+                            prefill_shared, L.cap_s, L.cap_p, g.max_private, g.rope_theta, status, st);
+        if (rc) return rc;
+        if (bf)
+            rc = launch_attn_bf16(dh, q, ksl, vsl, kpl, vpl, private_len, (float *)at(c, L.o_part),
+                                  (float *)at(c, L.ml_part), act, M, Mp, Mq, N, T, H, S, prefill_shared, L.cap_s,
+                                  L.cap_p, g.max_private, ks_shared, keys_per_range, ks_priv, st);
+        else
+            rc = launch_attn_f32(q, ksl, vsl, kpl, vpl, private_len, (float *)act, M, T, H, dh, S, prefill_shared,
+                                 L.cap_s, L.cap_p, g.max_private, st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_o), d, HD, part, d, true, &sk, &stride);
+        if (rc) return rc;
+        rc = launch_rownorm(bf, x, part, sk, stride, nullptr, nullptr, V, layer_w(c, l, L.g_ffn), g.rms_eps, act, M,
+                            Mp, d, st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_gu), 2 * F, d, part, 2 * F, true, &sk, &stride);
+        if (rc) return rc;
+        rc = launch_swiglu(bf, part, sk, stride, act, M, Mp, F, st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_d), d, F, part, d, true, &sk, &stride);
+        if (rc) return rc;
+        const void *next_gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
+        rc = launch_rownorm(bf, x, part, sk, stride, nullptr, nullptr, V, next_gain, g.rms_eps, act, M, Mp, d, st);
+        if (rc) return rc;
+    }
+    if (logits != nullptr) {
+        int sk;
+        int64_t stride;
+        rc = gemm(at(c, L.lm), V, d, logits, V, false, &sk, &stride);
+        if (rc) return rc;
+    }
+    return SEED_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *seed_last_error(void) { return g_err; }
+
+size_t seed_verify_workspace_bytes(const seed_model_cfg *cfg) {
+    if (validate_cfg(cfg) != SEED_OK) return 0;
+    return make_layout(*cfg).total;
+}
+
+int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weights *w, void *workspace,
+                     size_t workspace_bytes, void *hip_stream) {
+    if (out == nullptr) { set_error("out is NULL"); return SEED_E_NULL_PTR; }
+    *out = nullptr;
+    int rc = validate_cfg(cfg);
+    if (rc) return rc;
+    if (w == nullptr || workspace == nullptr) { set_error("weights / workspace is NULL"); return SEED_E_NULL_PTR; }
+    if (!w->tok_emb || !w->norm_final || !w->lm_head || !w->layers) {
+        set_error("weights: tok_emb, norm_final, lm_head, layers must be non-NULL");
+        return SEED_E_NULL_PTR;
+    }
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const seed_layer_w &lw = w->layers[l];
+        if (!lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.wgate || !lw.wup || !lw.wdown || !lw.norm_attn ||
+            !lw.norm_ffn) {
+            set_error("weights: layer %d has a NULL tensor", l);
+            return SEED_E_NULL_PTR;
+        }
+    }
+    if (((uintptr_t)workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return SEED_E_INVALID_ARG; }
+    Layout L = make_layout(*cfg);
+    if (workspace_bytes < L.total) {
+        set_error("workspace too small: %zu < %zu", workspace_bytes, L.total);
+        return SEED_E_CAPACITY;
+    }
+    seed_ctx *c = new (std::nothrow) seed_ctx;
+    if (c == nullptr) { set_error("out of host memory"); return SEED_E_INVALID_ARG; }
+    c->cfg = *cfg;
+    c->L = L;
+    c->ws = (char *)workspace;
+    c->stream = (hipStream_t)hip_stream;
+    c->bf16 = cfg->dtype == SEED_DTYPE_BF16;
+    hipStream_t st = c->stream;
+    const size_t es = L.es, d = cfg->d_model, F = cfg->d_ff, V = cfg->vocab, HD = L.HD;
+    auto copy = [&](void *dst, const void *src, size_t bytes) {
+        return hip_fail(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st), "weight copy");
+    };
+#define SEEDV_TRY(expr) do { rc = (expr); if (rc) { delete c; return rc; } } while (0)
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const seed_layer_w &lw = w->layers[l];
+        if (c->bf16) {
+            const int qt = (int)(HD / 16);
+            SEEDV_TRY(launch_pack_weight(lw.wq, layer_w(c, l, L.w_qkv), (int)HD, (int)d, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight(lw.wk, layer_w(c, l, L.w_qkv), (int)HD, (int)d, qt, 1, st));
+            SEEDV_TRY(launch_pack_weight(lw.wv, layer_w(c, l, L.w_qkv), (int)HD, (int)d, 2 * qt, 1, st));
+            SEEDV_TRY(launch_pack_weight(lw.wo, layer_w(c, l, L.w_o), (int)d, (int)HD, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight(lw.wgate, layer_w(c, l, L.w_gu), (int)F, (int)d, 0, 2, st));
+            SEEDV_TRY(launch_pack_weight(lw.wup, layer_w(c, l, L.w_gu), (int)F, (int)d, 1, 2, st));
+            SEEDV_TRY(launch_pack_weight(lw.wdown, layer_w(c, l, L.w_d), (int)d, (int)F, 0, 1, st));
+        } else {
+            char *qkv = (char *)layer_w(c, l, L.w_qkv);
+            SEEDV_TRY(copy(qkv, lw.wq, HD * d * es));
+            SEEDV_TRY(copy(qkv + HD * d * es, lw.wk, HD * d * es));
+            SEEDV_TRY(copy(qkv + 2 * HD * d * es, lw.wv, HD * d * es));
+            SEEDV_TRY(copy(layer_w(c, l, L.w_o), lw.wo, d * HD * es));
+            char *gu = (char *)layer_w(c, l, L.w_gu);
+            SEEDV_TRY(copy(gu, lw.wgate, F * d * es));
+            SEEDV_TRY(copy(gu + F * d * es, lw.wup, F * d * es));
+            SEEDV_TRY(copy(layer_w(c, l, L.w_d), lw.wdown, d * F * es));
+        }
+        SEEDV_TRY(copy(layer_w(c, l, L.g_attn), lw.norm_attn, d * es));
+        SEEDV_TRY(copy(layer_w(c, l, L.g_ffn), lw.norm_ffn, d * es));
+    }
+    SEEDV_TRY(copy(at(c, L.emb), w->tok_emb, V * d * es));
+    SEEDV_TRY(copy(at(c, L.g_final), w->norm_final, d * es));
+    if (c->bf16) SEEDV_TRY(launch_pack_weight(w->lm_head, at(c, L.lm), (int)V, (int)d, 0, 1, st));
+    else SEEDV_TRY(copy(at(c, L.lm), w->lm_head, V * d * es));
+    // KV caches and scratch start at zero: chunked key loops may touch (masked) entries past the valid length
+    SEEDV_TRY(hip_fail(hipMemsetAsync(at(c, L.ks), 0, L.total - L.ks, st), "workspace clear"));
+#undef SEEDV_TRY
+    *out = c;
+    return SEED_OK;
+}
+
+void seed_verify_destroy(seed_ctx *ctx) { delete ctx; }
+
+int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
+    int rc = check_accept_args(args);
+    if (rc) return rc;
+    return launch_accept(*args, (hipStream_t)hip_stream);
+}
+
+int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out, int32_t n_rows,
+                      int32_t vocab, void *hip_stream) {
+    if (n_rows < 0 || vocab < 1 || row_stride < vocab) {
+        set_error("sample: need n_rows >= 0, vocab >= 1, row_stride >= vocab");
+        return SEED_E_INVALID_ARG;
+    }
+    if (n_rows == 0) return SEED_OK;
+    if (!probs || !u || !tok_out) { set_error("sample: NULL pointer"); return SEED_E_NULL_PTR; }
+    return launch_sample_probs(probs, row_stride, u, tok_out, n_rows, vocab, (hipStream_t)hip_stream);
+}
+
+int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    if (a == nullptr) { set_error("step args is NULL"); return SEED_E_NULL_PTR; }
+    const seed_model_cfg &g = c->cfg;
+    const int N = a->n_branches, T = a->rows_per_branch;
+    const int prefill = (a->flags & SEED_STEP_PREFILL_SHARED) != 0;
+    if (N < 0 || T < 1 || a->shared_len < 0) { set_error("step: need N >= 0, T >= 1, shared_len >= 0"); return SEED_E_INVALID_ARG; }
+    if (a->flags & ~(SEED_STEP_PREFILL_SHARED | SEED_STEP_GREEDY | SEED_STEP_COMMIT_ALL)) {
+        set_error("step: unknown flag bits 0x%x", a->flags);
+        return SEED_E_INVALID_ARG;
+    }
+    if (N == 0) return SEED_OK;
+    if (prefill) {
+        if (N != 1) { set_error("step: PREFILL_SHARED needs n_branches == 1"); return SEED_E_SHAPE; }
+        if (a->accept != nullptr || (a->flags & SEED_STEP_COMMIT_ALL)) {
+            set_error("step: PREFILL_SHARED cannot be combined with accept or COMMIT_ALL");
+            return SEED_E_INVALID_ARG;
+        }
+        if (T > c->L.M_cap) { set_error("step: %d prefill rows exceed the row capacity %d", T, c->L.M_cap); return SEED_E_CAPACITY; }
+        if ((long)a->shared_len + T > g.max_shared) {
+            set_error("step: shared_len %d + %d rows exceeds max_shared %d", a->shared_len, T, g.max_shared);
+            return SEED_E_CAPACITY;
+        }
+    } else {
+        if (N > g.max_branches || T > g.max_rows_per_branch) {
+            set_error("step: N=%d, T=%d exceed capacity (%d, %d)", N, T, g.max_branches, g.max_rows_per_branch);
+            return SEED_E_CAPACITY;
+        }
+        if (a->shared_len > g.max_shared) { set_error("step: shared_len exceeds max_shared"); return SEED_E_CAPACITY; }
+        if (a->private_len == nullptr) { set_error("step: private_len is NULL"); return SEED_E_NULL_PTR; }
+    }
+    if (a->row_tok == nullptr) { set_error("step: row_tok is NULL"); return SEED_E_NULL_PTR; }
+    seed_accept_args acc;
+    if (a->accept != nullptr) {
+        if (a->flags & SEED_STEP_COMMIT_ALL) { set_error("step: COMMIT_ALL cannot be combined with accept"); return SEED_E_INVALID_ARG; }
+        acc = *a->accept;
+        acc.n_branches = N;
+        acc.n_target_rows = T;
+        acc.vocab = g.vocab;
+        acc.probs_kind = SEED_KIND_LOGITS;
+        acc.greedy = (a->flags & SEED_STEP_GREEDY) ? 1 : acc.greedy;
+        acc.p_or_logits = a->logits_out ? a->logits_out : (const float *)at(c, c->L.logits);
+        if (acc.private_len == nullptr) acc.private_len = a->private_len;
+        int rc = check_accept_args(&acc);
+        if (rc) return rc;
+    }
+    const bool want_logits = a->logits_out != nullptr || a->accept != nullptr;
+    float *logits = want_logits ? (a->logits_out ? a->logits_out : (float *)at(c, c->L.logits)) : nullptr;
+    int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, logits);
+    if (rc) return rc;
+    if (a->accept != nullptr) return launch_accept(acc, c->stream);
+    if (a->flags & SEED_STEP_COMMIT_ALL) return launch_add_len(a->private_len, N, T, c->stream);
+    return SEED_OK;
+}
+
+int seed_draft_step(seed_ctx *c, const seed_draft_args *a) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    if (a == nullptr) { set_error("draft args is NULL"); return SEED_E_NULL_PTR; }
+    const seed_model_cfg &g = c->cfg;
+    const int N = a->n_branches;
+    if (N < 0 || a->shared_len < 0) { set_error("draft: need N >= 0, shared_len >= 0"); return SEED_E_INVALID_ARG; }
+    if (a->flags & ~SEED_STEP_GREEDY) { set_error("draft: unknown flag bits 0x%x", a->flags); return SEED_E_INVALID_ARG; }
+    if (N == 0) return SEED_OK;
+    if (N > g.max_branches) { set_error("draft: N=%d exceeds max_branches %d", N, g.max_branches); return SEED_E_CAPACITY; }
+    if (a->shared_len > g.max_shared) { set_error("draft: shared_len exceeds max_shared"); return SEED_E_CAPACITY; }
+    const int greedy = (a->flags & SEED_STEP_GREEDY) != 0;
+    if (!a->row_tok || !a->private_len || !a->tok_out) { set_error("draft: row_tok, private_len, tok_out must be non-NULL"); return SEED_E_NULL_PTR; }
+    if (!greedy && !a->u) { set_error("draft: u is NULL"); return SEED_E_NULL_PTR; }
+    if (!(a->temperature > 0.f)) { set_error("draft: temperature must be > 0"); return SEED_E_INVALID_ARG; }
+    if (a->q_out != nullptr && a->q_stride < g.vocab) { set_error("draft: q_stride < vocab"); return SEED_E_INVALID_ARG; }
+    if (a->tok_stride < 1) { set_error("draft: tok_stride must be >= 1"); return SEED_E_INVALID_ARG; }
+    float *logits = a->logits_out ? a->logits_out : (float *)at(c, c->L.logits);
+    int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, logits);
+    if (rc) return rc;
+    return launch_softmax_sample(logits, g.vocab, a->temperature, greedy, a->u, a->q_out, a->q_stride, a->tok_out,
+                                 a->tok_stride, a->private_len, N, g.vocab, c->stream);
+}
+
+int seed_kv_load(seed_ctx *c, int32_t layer, const void *k_shared, const void *v_shared, int32_t shared_len,
+                 const void *k_private, const void *v_private, int32_t n_branches, int32_t private_len) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    const seed_model_cfg &g = c->cfg;
+    if (layer < 0 || layer >= g.n_layers || shared_len < 0 || private_len < 0 || n_branches < 0) {
+        set_error("kv_load: bad layer or negative length");
+        return SEED_E_INVALID_ARG;
+    }
+    if (shared_len > g.max_shared || private_len > g.max_private || n_branches > g.max_branches) {
+        set_error("kv_load: lengths exceed capacity");
+        return SEED_E_CAPACITY;
+    }
+    if (shared_len > 0 && (!k_shared || !v_shared)) { set_error("kv_load: shared KV is NULL"); return SEED_E_NULL_PTR; }
+    if (private_len > 0 && n_branches > 0 && (!k_private || !v_private)) { set_error("kv_load: private KV is NULL"); return SEED_E_NULL_PTR; }
+    const Layout &L = c->L;
+    const int H = g.n_heads, dh = g.head_dim;
+    int rc = SEED_OK;
+    if (shared_len > 0) {
+        rc = launch_kv_import(c->bf16, false, k_shared, c->ws + L.ks + L.ks_stride * layer, H, shared_len, dh, L.cap_s, c->stream);
+        if (rc) return rc;
+        rc = launch_kv_import(c->bf16, c->bf16, v_shared, c->ws + L.vs + L.ks_stride * layer, H, shared_len, dh, L.cap_s, c->stream);
+        if (rc) return rc;
+    }
+    if (private_len > 0 && n_branches > 0) {
+        rc = launch_kv_import(c->bf16, false, k_private, c->ws + L.kp + L.kp_stride * layer, n_branches * H, private_len, dh, L.cap_p, c->stream);
+        if (rc) return rc;
+        rc = launch_kv_import(c->bf16, c->bf16, v_private, c->ws + L.vp + L.kp_stride * layer, n_branches * H, private_len, dh, L.cap_p, c->stream);
+    }
+    return rc;
+}
+
+int seed_verify_status(seed_ctx *c, int32_t *host_status) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    if (host_status == nullptr) { set_error("host_status is NULL"); return SEED_E_NULL_PTR; }
+    int rc = hip_fail(hipMemcpyAsync(host_status, at(c, c->L.status), 4, hipMemcpyDeviceToHost, c->stream), "status copy");
+    if (rc) return rc;
+    rc = hip_fail(hipStreamSynchronize(c->stream), "stream sync");
+    if (rc) return rc;
+    return hip_fail(hipMemsetAsync(at(c, c->L.status), 0, 4, c->stream), "status clear");
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Internal declarations shared by the translation units of libseed_verify (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/seed_verify.h"
+
+namespace seedv {
+
+void set_error(const char *fmt, ...);
+int hip_fail(hipError_t e, const char *what);
+
+// ---- accept.hip ------------------------------------------------------------------------------
+int launch_accept(const seed_accept_args &a, hipStream_t st);
+int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
+                          const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
+                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, hipStream_t st);
+int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
+                        int n_rows, int vocab, hipStream_t st);
+
+}  // namespace seedv
+
+namespace seedv {
+// ---- gemm_bf16.hip -----------------------------------------------------------------------------
+int gemm_bf16_pick_tn(int NT, int m_tiles);
+int launch_gemm_bf16(const void *Wp, const void *Xp, float *out, int Nout, int K, int m_tiles, int SK,
+                     int m_rows_out, int64_t split_stride, int ld_out, hipStream_t st);
+int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,
+                       hipStream_t st);
+// ---- rowops.hip ----------------------------------------------------------------------------------
+int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,
+                   const void *emb, int vocab, const void *gain, float eps, void *act, int M, int Mp, int d,
+                   hipStream_t st);
+int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, void *act, int M, int Mp, int F,
+                  hipStream_t st);
+int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, void *k_shared,
+                   void *v_shared, void *k_priv, void *v_priv, const int32_t *private_len, int M, int Mq,
+                   int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
+                   int max_private, float theta, int32_t *status, hipStream_t st);
+int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
+                     hipStream_t st);
+int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
+// ---- attention_bf16.hip ----------------------------------------------------------------------------
+void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
+                    int *ks_shared, int *keys_per_range, int *ks_priv);
+int launch_attn_bf16(int dh, const void *q, const void *k_shared, const void *vt_shared, const void *k_priv,
+                     const void *vt_priv, const int32_t *private_len, float *o_part, float *ml_part, void *act,
+                     int M, int Mp, int Mq, int N, int T, int H, int S, int prefill_shared, int cap_s, int cap_p,
+                     int max_private, int ks_shared, int keys_per_range, int ks_priv, hipStream_t st);
+// ---- fp32_path.hip -----------------------------------------------------------------------------------
+int launch_gemm_f32(const void *W, const void *X, float *Y, int M, int Nout, int K, int ldy, hipStream_t st);
+int launch_attn_f32(const void *q, const void *k_shared, const void *v_shared, const void *k_priv,
+                    const void *v_priv, const int32_t *private_len, float *out, int M, int T, int H, int dh, int S,
+                    int prefill_shared, int cap_s, int cap_p, int max_private, hipStream_t st);
+}  // namespace seedv

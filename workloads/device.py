@@ -1,0 +1,78 @@
+"""GPU-side harness helpers: upload seeded tensors as PyTorch device tensors and build a library
+context for a workload.  Pure plumbing (no arithmetic of the method)."""
+import numpy as np
+import torch
+
+from .gen import Weights
+
+
+def torch_dtype(model):
+    return torch.bfloat16 if model.dtype == "bf16" else torch.float32
+
+
+def to_device(arr, model, device="cuda:0"):
+    """float32 numpy (already on the model's storage grid) -> device tensor in the model dtype (exact)."""
+    t = torch.from_numpy(np.ascontiguousarray(arr))
+    return t.to(device=device, dtype=torch_dtype(model), non_blocking=False)
+
+
+class UploadingWeights:
+    """Wraps a Weights generator: every tensor handed out (e.g. to the oracle) is also uploaded once to the
+    GPU, so a large model is generated a single time for both sides."""
+
+    def __init__(self, model, seed, device="cuda:0", reuse_buffers=True):
+        self.inner = Weights(model, seed, reuse_buffers=reuse_buffers)
+        self.model = model
+        self.device = device
+        self.dev = {"layers": [None] * model.n_layers}
+
+    def tok_emb(self):
+        a = self.inner.tok_emb()
+        self.dev.setdefault("tok_emb", to_device(a, self.model, self.device))
+        return a
+
+    def norm_final(self):
+        a = self.inner.norm_final()
+        self.dev.setdefault("norm_final", to_device(a, self.model, self.device))
+        return a
+
+    def lm_head(self):
+        a = self.inner.lm_head()
+        self.dev.setdefault("lm_head", to_device(a, self.model, self.device))
+        return a
+
+    def layer(self, l):
+        w = self.inner.layer(l)
+        if self.dev["layers"][l] is None:
+            self.dev["layers"][l] = {k: to_device(v, self.model, self.device) for k, v in w.items()}
+        return w
+
+    def upload_all(self):
+        """Generate and upload whatever has not been requested yet; returns the device weight dict."""
+        if "tok_emb" not in self.dev:
+            self.tok_emb()
+        if "norm_final" not in self.dev:
+            self.norm_final()
+        if "lm_head" not in self.dev:
+            self.lm_head()
+        for l in range(self.model.n_layers):
+            if self.dev["layers"][l] is None:
+                self.layer(l)
+        return self.dev
+
+
+def make_context(model, dev_weights, *, max_branches, max_rows_per_branch, max_shared, max_private,
+                 device="cuda:0"):
+    from paper_2406_18200_amd import ModelShape, VerifyContext
+    shape = ModelShape(model.n_layers, model.d_model, model.n_heads, model.head_dim, model.d_ff, model.vocab,
+                       model.dtype, model.rms_eps, model.rope_theta, max_branches, max_rows_per_branch,
+                       max_shared, max_private)
+    return VerifyContext(shape, dev_weights, device)
+
+
+def i32(a, device="cuda:0"):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+
+
+def f32(a, device="cuda:0"):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
