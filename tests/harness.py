@@ -1,0 +1,169 @@
+"""Shared driver for the GPU parity tests: builds one workload's inputs once, runs the oracle and the HIP
+library on them and returns both results.  Oracle-side and GPU-side code meet only in the seeded inputs."""
+import time
+
+import numpy as np
+import torch
+
+import oracle
+import workloads as wl
+from workloads import gen
+from workloads.device import UploadingWeights, make_context, to_device, f32, i32
+from paper_2406_18200_amd import binding as B
+
+TOL = {"fp32": (1e-5, 1e-4), "bf16": (2e-2, 1e-2)}   # (absolute, relative): |got - ref| <= abs + rel * |ref|
+
+
+def check_logits(got, ref, dtype):
+    atol, rtol = TOL[dtype]
+    err = np.abs(got - ref)
+    bound = atol + rtol * np.abs(ref)
+    worst = float((err / bound).max())
+    return worst, float(err.max())
+
+
+def build_inputs(w, bonus=False, q_override=None):
+    """Host-side inputs of one verify step (everything except the model and the KV context)."""
+    G = w.gamma
+    pending = gen.pending_tokens(w)
+    q = q_override if q_override is not None else wl.random_draft_q(w)
+    u = wl.uniform24(w.seed + 3, (w.N, G))
+    drafts = wl.draw_tokens(q, u)
+    T = G + 1 if bonus else G
+    row_tok = np.concatenate([pending[:, None], drafts[:, :T - 1]], axis=1).astype(np.int32)
+    u_acc = wl.uniform24(w.seed + 4, (w.N, G))
+    u_res = wl.uniform24(w.seed + 4, (w.N,), stream=1)
+    return dict(q=q, drafts=drafts, row_tok=row_tok, u_acc=u_acc, u_res=u_res, T=T)
+
+
+class Case:
+    """Runs oracle and GPU on a workload.  branches = subset of branch indices the oracle evaluates (all by
+    default); the GPU always runs the full step in its benchmark launch configuration."""
+
+    def __init__(self, w, bonus=False, greedy=False, branches=None, device="cuda:0", log=print):
+        self.w, self.bonus, self.greedy, self.device, self.log = w, bonus, greedy, device, log
+        self.branches = list(range(w.N)) if branches is None else list(branches)
+        self.inp = build_inputs(w, bonus)
+
+    # ---------------------------------------------------------------- oracle side
+    def run_oracle(self):
+        w, m, inp = self.w, self.w.model, self.inp
+        t0 = time.time()
+        self.weights = UploadingWeights(m, w.seed, self.device)
+        W = self.weights
+        sel = self.branches
+        if w.kv_protocol == "true_prefix":
+            self.prefix = wl.prefix_tokens(w)
+            self.private = gen.private_tokens(w)
+            _, ks, vs = oracle.decode_rows(m, W, self.prefix)
+            pk, pv = {}, {}
+            for b in sel:
+                if w.R:
+                    _, kb, vb = oracle.decode_rows(m, W, self.private[b], ctx_kv=lambda l: (ks[l], vs[l]), pos0=w.S)
+                    pk[b], pv[b] = kb, vb
+
+            def ctx(l):
+                out = []
+                for b in sel:
+                    if w.R:
+                        out.append((np.concatenate([ks[l], pk[b][l]], 1), np.concatenate([vs[l], pv[b][l]], 1)))
+                    else:
+                        out.append((ks[l], vs[l]))
+                return out
+        else:
+            self.kv_dev = []
+
+            def ctx(l):
+                k_s, v_s, k_p, v_p = wl.synthetic_kv(w, l)
+                self.kv_dev.append(tuple(to_device(a, m, self.device) if a.size else None for a in (k_s, v_s, k_p, v_p)))
+                return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in sel]
+        pos0 = [w.S + w.R] * len(sel)
+        self.ref_logits = oracle.verify_forward(m, W, inp["row_tok"][sel], ctx, pos0)
+        G = w.gamma
+        if self.greedy:
+            res = oracle.accept_resample(None, None, inp["drafts"][sel], None, None, greedy=True, logits=self.ref_logits.astype(np.float32))
+            self.ref_p = None
+        else:
+            self.ref_p = oracle.softmax_temperature(self.ref_logits, w.temperature)
+            res = oracle.accept_resample(self.ref_p, inp["q"][sel], inp["drafts"][sel], inp["u_acc"][sel], inp["u_res"][sel])
+        self.ref_accept = res
+        self.log(f"oracle done in {time.time() - t0:.1f}s", flush=True)
+        return self
+
+    # ---------------------------------------------------------------- HIP side
+    def run_gpu(self, keep_ctx=False):
+        w, m, inp = self.w, self.w.model, self.inp
+        t0 = time.time()
+        dev = self.weights.upload_all()
+        T = inp["T"]
+        ctx = make_context(m, dev, max_branches=w.N, max_rows_per_branch=T, max_shared=max(w.S, 1),
+                           max_private=w.R, device=self.device)
+        plen = torch.zeros(w.N, dtype=torch.int32, device=self.device)
+        if w.kv_protocol == "true_prefix":
+            ctx.prefill_shared(i32(self.prefix, self.device))
+            if w.R:
+                for lo in range(0, w.R, T):       # private prefill in chunks of at most T rows per branch
+                    chunk = i32(self.private[:, lo:lo + T], self.device).contiguous()
+                    ctx.step(chunk, w.S, plen, flags=B.SEED_STEP_COMMIT_ALL)
+        else:
+            for l, (k_s, v_s, k_p, v_p) in enumerate(self.kv_dev):
+                ctx.kv_load(l, k_s, v_s, k_p, v_p)
+            plen += w.R
+        logits = torch.empty((w.N, T, m.vocab), dtype=torch.float32, device=self.device)
+        acc = dict(q=None if self.greedy else f32(inp["q"], self.device), draft_tok=i32(inp["drafts"], self.device),
+                   u_acc=None if self.greedy else f32(inp["u_acc"], self.device),
+                   u_res=None if self.greedy else f32(inp["u_res"], self.device),
+                   temperature=w.temperature, greedy=self.greedy)
+        flags = B.SEED_STEP_GREEDY if self.greedy else 0
+        outs = ctx.step(i32(inp["row_tok"], self.device), w.S, plen, flags=flags, logits_out=logits, accept=acc)
+        torch.cuda.synchronize()
+        self.status = ctx.status()
+        self.gpu_logits = logits.cpu().numpy()
+        self.gpu_accept = [o.cpu().numpy() if o is not None else None for o in outs]
+        self.gpu_plen = plen.cpu().numpy()
+        self.log(f"gpu done in {time.time() - t0:.1f}s", flush=True)
+        if keep_ctx:
+            self.ctx, self.dev_plen, self.dev_logits = ctx, plen, logits
+        else:
+            ctx.close()
+        return self
+
+    # ---------------------------------------------------------------- comparison
+    def compare(self):
+        w, inp, sel = self.w, self.inp, self.branches
+        G, T = w.gamma, inp["T"]
+        worst, max_err = check_logits(self.gpu_logits[sel], self.ref_logits, w.model.dtype)
+        self.log(f"logits: max abs err {max_err:.3e}, worst err/bound {worst:.3f}", flush=True)
+        assert self.status == 0
+        assert worst <= 1.0, (worst, max_err)
+        a_w, out_w, n_w, ptok_w = self.ref_accept
+        a_g, out_g, n_g, ptok_g = [x[sel] if x is not None else None for x in self.gpu_accept]
+        if self.greedy:
+            # argmax decided on each side from its own logits: identical unless the top two logits are within tolerance
+            top2 = np.sort(self.ref_logits, axis=-1)[..., -2:]
+            clear = ((top2[..., 1] - top2[..., 0]) > 2 * (TOL[w.model.dtype][0] + TOL[w.model.dtype][1] * np.abs(top2[..., 1])))[:, :G].all(axis=1)
+        else:
+            qtok = np.take_along_axis(inp["q"][sel], inp["drafts"][sel][..., None], -1)[..., 0]
+            ptol = 1e-5 if w.model.dtype == "fp32" else 5e-2       # p(x) = softmax of logits within tolerance
+            rel = np.abs(ptok_g - ptok_w) / np.maximum(ptok_w, 1e-30)
+            self.log(f"p_tok: max rel err {rel.max():.3e}", flush=True)
+            assert rel.max() <= (1e-3 if w.model.dtype == "fp32" else 0.2)
+            # (ii) decisions follow bit-exactly from the kernel's own p(x)
+            host_ok = (inp["u_acc"][sel] * qtok) < ptok_g
+            host_a = np.array([int(np.argmin(np.append(host_ok[i], False))) for i in range(len(sel))])
+            assert np.array_equal(a_g, host_a)
+            # (iii) equal to the oracle's unless u*q is within the logits tolerance of p (near-tie)
+            margin = np.abs(inp["u_acc"][sel] * qtok - ptok_w) / np.maximum(ptok_w, 1e-30)
+            self.log(f"minimum accept margin {margin.min():.3e}", flush=True)
+            clear = (margin > ptol).all(axis=1)
+        self.log(f"branches with clear decisions: {int(clear.sum())}/{len(sel)}; accepted {a_w.tolist()}", flush=True)
+        assert np.array_equal(a_g[clear], a_w[clear])
+        assert np.array_equal(n_g[clear], n_w[clear])
+        for i in np.nonzero(clear)[0]:
+            a = a_w[i]
+            assert np.array_equal(out_g[i, :a], out_w[i, :a])
+            assert (out_g[i, n_w[i]:] == -1).all()
+        # Algorithm 1 bookkeeping on the device
+        want_len = oracle.commit_lengths(np.full(w.N, w.R), self.gpu_accept[0], T)
+        assert np.array_equal(self.gpu_plen, want_len)
+        return worst, max_err
