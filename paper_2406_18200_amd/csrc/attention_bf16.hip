@@ -15,7 +15,8 @@
 //                          the four 16-lane groups
 //   O^T += V^T . P^T       A = V^T fragment (16 dims x 32 keys; V is cached transposed so this is one
 //                          16-byte load per lane), B = P^T built in registers from the S^T accumulators
-// and writes an unnormalised partial (max, sum, O) per (row, head, key range); a small merge kernel
+// (q and P are carried as hi/lo bf16 pairs, two MFMAs each, so that rounding them does not dominate the
+// error of the attention output) and writes an unnormalised partial (max, sum, O) per (row, head, key range); a small merge kernel
 // combines the partials by log-sum-exp and emits the bf16 activation tile of the O projection.
 //
 // The two S^T tiles of a 32-key chunk use the key order key = 8*(i/4) + (i%4) (+4 for the second tile),
@@ -27,12 +28,15 @@ namespace seedv {
 namespace {
 
 struct AttnParams {
-    const uint16_t *q;        // [Mq][H*DH] bf16
+    const uint16_t *q;        // [2][Mq][H*DH] bf16: hi plane, then lo plane (q = hi + lo)
+    size_t q_plane;           // elements between the planes
     const uint16_t *k_shared; // [H][cap_s][DH]
     const uint16_t *vt_shared;// [H][DH][cap_s]
     const uint16_t *k_priv;   // [Nmax][H][cap_p][DH]
     const uint16_t *vt_priv;  // [Nmax][H][DH][cap_p]
     const int32_t *private_len;
+    const float *k_new;       // [M][H*DH] fp32: rotated keys of this step's rows (in flight)
+    const float *v_new;       // [M][H*DH] fp32: values of this step's rows
     float *o_part;            // [P][Mq][H][DH]
     float *ml_part;           // [P][Mq][H][2]
     int M, Mq, N, T, H;
@@ -57,13 +61,15 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     const int HD = P.H * DH;
 
     // query fragments: B operand, lane holds Q[row0 + t*16 + col][h*DH + ks*32 + 8g .. +8]
-    bf16x8 qf[2][KS];
+    bf16x8 qf[2][KS][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qf[t][ks] = *reinterpret_cast<const bf16x8 *>(
-                P.q + (size_t)min(row0 + t * 16 + col, P.Mq - 1) * HD + h * DH + ks * 32 + 8 * g);
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint16_t *qp = P.q + (size_t)min(row0 + t * 16 + col, P.Mq - 1) * HD + h * DH + ks * 32 + 8 * g;
+            qf[t][ks][0] = *reinterpret_cast<const bf16x8 *>(qp);
+            qf[t][ks][1] = *reinterpret_cast<const bf16x8 *>(qp + P.q_plane);
+        }
 
     int limit[2];
 #pragma unroll
@@ -92,12 +98,14 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             for (int t = 0; t < 2; ++t) {
                 f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[t][ks], acc, 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[t][ks][1], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[t][ks][0], acc, 0, 0, 0);
+                }
                 s[kt][t] = acc;
             }
         }
-        bf16x8 pf[2];
+        bf16x8 pf[2][2];   // [row tile][hi|lo]
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             // lane holds keys c + 8g + {0..3} (tile 0) and c + 8g + {4..7} (tile 1) of query row `col`
@@ -127,15 +135,27 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             m_run[t] = m_new;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;
-            u32x4 w = {pack2bf(pv[0], pv[1]), pack2bf(pv[2], pv[3]), pack2bf(pv[4], pv[5]), pack2bf(pv[6], pv[7])};
-            pf[t] = *reinterpret_cast<bf16x8 *>(&w);
+            u32x4 wh, wl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint16_t h0, l0, h1, l1;
+                split_bf16(pv[2 * i], h0, l0);
+                split_bf16(pv[2 * i + 1], h1, l1);
+                wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            }
+            pf[t][0] = *reinterpret_cast<bf16x8 *>(&wh);
+            pf[t][1] = *reinterpret_cast<bf16x8 *>(&wl);
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             // A operand: V^T[d = dt*16 + col][keys c + 8g .. +8]
             const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[dt][t], 0, 0, 0);
+            for (int t = 0; t < 2; ++t) {
+                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][1], o[dt][t], 0, 0, 0);
+                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][0], o[dt][t], 0, 0, 0);
+            }
         }
     }
 #pragma unroll
@@ -153,6 +173,50 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             mp[0] = m_run[t];
             mp[1] = l;
         }
+    }
+}
+
+// In-flight segment: row j of a branch against rows 0..j of the same branch (the causal part of the tree
+// mask).  At most T keys per row, so it runs in plain fp32 on the vector ALUs from an fp32 side copy of the
+// new keys / values: the rows of one step see each other unrounded, while the cache keeps bf16.
+// One wavefront per (row, head); lanes own DH/64 dims; dot products are wavefront-shuffle reductions.
+template <int DH>
+__device__ void inflight_task(const AttnParams &P, int itask) {
+    constexpr int PER = DH / 64;
+    const int lane = threadIdx.x & 63;
+    const int r = itask / P.H, h = itask - r * P.H;
+    if (r >= P.M) return;
+    const int b = r / P.T, j = r - b * P.T;
+    const int HD = P.H * DH;
+    float qv[PER], o[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const size_t e = (size_t)r * HD + h * DH + lane * PER + i;
+        qv[i] = bf2f(P.q[e]) + bf2f(P.q[e + P.q_plane]);
+        o[i] = 0.f;
+    }
+    float m = -INFINITY, l = 0.f;
+    for (int jj = 0; jj <= j; ++jj) {
+        const size_t e = (size_t)(b * P.T + jj) * HD + h * DH + lane * PER;
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) s = fmaf(qv[i], P.k_new[e + i], s);
+        s = wave_reduce_sum(s) * P.scale_log2e;
+        const float m_new = fmaxf(m, s);
+        const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
+        l = l * alpha + p;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) o[i] = o[i] * alpha + p * P.v_new[e + i];
+        m = m_new;
+    }
+    const int part = P.ks_shared + P.ks_priv;
+    float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) op[i] = o[i];
+    if (lane == 0) {
+        float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
+        mp[0] = m;
+        mp[1] = l;
     }
 }
 
@@ -175,20 +239,23 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
     }
     const int ptask = task - n_shared;
     const int n_priv = P.N * P.H * P.groups_priv * P.ks_priv;
-    if (ptask >= n_priv) return;
+    if (ptask >= n_priv) {
+        if (!P.prefill_shared) inflight_task<DH>(P, ptask - n_priv);
+        return;
+    }
     const int ks = ptask % P.ks_priv;
     const int grp = (ptask / P.ks_priv) % P.groups_priv;
     const int h = (ptask / (P.ks_priv * P.groups_priv)) % P.H;
     const int b = ptask / (P.ks_priv * P.groups_priv * P.H);
     const int pl = min(max(P.private_len[b], 0), P.max_private);
-    const int total = pl + P.T;                       // private context + in-flight rows
+    const int total = pl;                             // committed private context; in-flight rows are separate
     const int kbeg = ks * P.keys_per_range;
     const int kend = min(total, kbeg + P.keys_per_range);
     const int row_first = b * P.T;
-    // row j of the branch sees private keys < pl + j + 1
+    // every row of the branch sees all pl committed private keys
     attn_task<DH>(P, h, row_first + grp * 32, row_first + P.T,
                   P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH, P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p,
-                  P.cap_p, kbeg, max(kbeg, kend), pl + 1, row_first, 1, P.ks_shared + ks);
+                  P.cap_p, kbeg, max(kbeg, kend), pl, row_first, 0, P.ks_shared + ks);
 }
 
 // Combine the partials of one (row, head) by log-sum-exp and write the bf16 activation (fragment-packed,
@@ -205,7 +272,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
     constexpr int PER = DH / 64;     // output dims per lane
     if (r >= M) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) act[packed_offset(r, h * DH + lane * PER + i, KT)] = 0;
+        for (int i = 0; i < PER; ++i) {
+            const size_t o = packed_offset(r, h * DH + lane * PER + i, KT);
+            act[o] = 0;
+            act[o + kActLoOffset] = 0;
+        }
         return;
     }
     const int np = prefill_shared ? n_part_shared : n_part_total;
@@ -226,7 +297,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) act[packed_offset(r, h * DH + lane * PER + i, KT)] = f2bf(acc[i] * inv);
+    for (int i = 0; i < PER; ++i) {
+        const size_t o = packed_offset(r, h * DH + lane * PER + i, KT);
+        split_bf16(acc[i] * inv, act[o], act[o + kActLoOffset]);
+    }
 }
 
 }  // namespace
@@ -248,20 +322,24 @@ void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_
     ks = (chunks * 32 + per - 1) / per;
     *ks_shared = ks;
     *keys_per_range = per;
-    *ks_priv = prefill_shared ? 0 : (cap_priv_keys + per - 1) / per;
+    *ks_priv = (prefill_shared || cap_priv_keys <= 0) ? 0 : (cap_priv_keys + per - 1) / per;
 }
 
-int launch_attn_bf16(int dh, const void *q, const void *k_shared, const void *vt_shared, const void *k_priv,
-                     const void *vt_priv, const int32_t *private_len, float *o_part, float *ml_part, void *act,
+int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared, const void *vt_shared, const void *k_priv,
+                     const void *vt_priv, const int32_t *private_len, const float *k_new, const float *v_new,
+                     float *o_part, float *ml_part, void *act,
                      int M, int Mp, int Mq, int N, int T, int H, int S, int prefill_shared, int cap_s, int cap_p,
                      int max_private, int ks_shared, int keys_per_range, int ks_priv, hipStream_t st) {
     AttnParams P;
     P.q = (const uint16_t *)q;
+    P.q_plane = q_plane;
     P.k_shared = (const uint16_t *)k_shared;
     P.vt_shared = (const uint16_t *)vt_shared;
     P.k_priv = (const uint16_t *)k_priv;
     P.vt_priv = (const uint16_t *)vt_priv;
     P.private_len = private_len;
+    P.k_new = k_new;
+    P.v_new = v_new;
     P.o_part = o_part;
     P.ml_part = ml_part;
     P.M = M; P.Mq = Mq; P.N = N; P.T = T; P.H = H; P.S = S;
@@ -273,8 +351,8 @@ int launch_attn_bf16(int dh, const void *q, const void *k_shared, const void *vt
     P.ks_priv = ks_priv;
     P.groups_priv = (T + 31) / 32;
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-    const int tasks = H * P.n_groups * ks_shared + (prefill_shared ? 0 : N * H * P.groups_priv * ks_priv);
-    const int n_total = ks_shared + ks_priv;
+    const int tasks = H * P.n_groups * ks_shared + (prefill_shared ? 0 : N * H * P.groups_priv * ks_priv + M * H);
+    const int n_total = ks_shared + ks_priv + 1;      // + the in-flight slot
     if (dh == 128) {
         hipLaunchKernelGGL(attn_partial_kernel<128>, dim3((tasks + 3) / 4), dim3(256), 0, st, P);
         hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((Mp * H + 3) / 4), dim3(256), 0, st, o_part, ml_part,

@@ -7,7 +7,9 @@
 //   * W is repacked once at init into MFMA A-fragment order: tile (nt, kt) = 16 output features x 32
 //     inputs = 1 KiB contiguous, lane l holding W[nt*16 + l%16][kt*32 + 8*(l/16) .. +8].  All k-tiles of
 //     an n-tile are contiguous, so a wavefront's stream is one contiguous run.
-//   * X (activations, tiny, L2-resident) is kept in the matching B-fragment order by its producer.
+//   * X (activations, tiny, L2-resident) is kept in the matching B-fragment order by its producer, as a
+//     hi/lo pair of bf16 values per element (two MFMAs per weight fragment): the weights stay bf16 but the
+//     activations keep ~16 significant bits, so their rounding does not pile up over 32-40 layers.
 //   * v_mfma_f32_16x16x32_bf16 computes Y^T tiles: D[i = feature][j = token row].
 //   * Split-K partial sums go to a [SK][Mpad][Nout] fp32 buffer that the next row kernel reduces in a
 //     fixed order (deterministic; no atomics).
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(256) void gemm_ws_kernel(const bf16x8 *__restrict__
 
     int kt = k0;
     for (; kt + kUnroll <= k1; kt += kUnroll) {
-        bf16x8 a[kUnroll][TN], b[kUnroll][TM];
+        bf16x8 a[kUnroll][TN], b[kUnroll][TM][2];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
@@ -52,14 +54,19 @@ __global__ __launch_bounds__(256) void gemm_ws_kernel(const bf16x8 *__restrict__
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) b[u][tm] = xbase[((size_t)tm * KT + kt + u) * 64];
+            for (int tm = 0; tm < TM; ++tm) {
+                b[u][tm][0] = xbase[((size_t)tm * KT + kt + u) * 128];
+                b[u][tm][1] = xbase[((size_t)tm * KT + kt + u) * 128 + 64];
+            }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][tm], acc[tn][tm], 0, 0, 0);
+                for (int tm = 0; tm < TM; ++tm) {
+                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][tm][1], acc[tn][tm], 0, 0, 0);
+                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][tm][0], acc[tn][tm], 0, 0, 0);
+                }
     }
     for (; kt < k1; ++kt) {
 #pragma unroll
@@ -67,8 +74,10 @@ __global__ __launch_bounds__(256) void gemm_ws_kernel(const bf16x8 *__restrict__
             bf16x8 a = __builtin_nontemporal_load(wbase + ((size_t)tn * KT + kt) * 64);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                bf16x8 b = xbase[((size_t)tm * KT + kt) * 64];
-                acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[tn][tm], 0, 0, 0);
+                const bf16x8 bh = xbase[((size_t)tm * KT + kt) * 128];
+                const bf16x8 bl = xbase[((size_t)tm * KT + kt) * 128 + 64];
+                acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[tn][tm], 0, 0, 0);
+                acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[tn][tm], 0, 0, 0);
             }
         }
     }

@@ -18,8 +18,18 @@ __device__ __forceinline__ float load_w(const void *p, size_t i) {
 template <bool BF16>
 __device__ __forceinline__ void store_act8(void *base, int r, int c, int K, const float *v) {
     if (BF16) {
-        u32x4 w = {pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7])};
-        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(base) + packed_offset(r, c, K >> 5)) = w;
+        uint16_t hi[8], lo[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) split_bf16(v[i], hi[i], lo[i]);
+        u32x4 wh, wl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            wh[i] = (uint32_t)hi[2 * i] | ((uint32_t)hi[2 * i + 1] << 16);
+            wl[i] = (uint32_t)lo[2 * i] | ((uint32_t)lo[2 * i + 1] << 16);
+        }
+        uint16_t *dst = reinterpret_cast<uint16_t *>(base) + packed_offset(r, c, K >> 5);
+        *reinterpret_cast<u32x4 *>(dst) = wh;
+        *reinterpret_cast<u32x4 *>(dst + kActLoOffset) = wl;
     } else {
         float *d = reinterpret_cast<float *>(base) + (size_t)r * K + c;
         *reinterpret_cast<f32x4 *>(d) = (f32x4){v[0], v[1], v[2], v[3]};
@@ -118,17 +128,19 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ p
 //   fp32: K and V caches [H][cap][dh]
 template <bool BF16>
 __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ part, int SK, int64_t split_stride,
-                                                      void *q_out, void *k_shared, void *v_shared,
-                                                      void *k_priv, void *v_priv, const int32_t *private_len,
-                                                      int M, int T, int H, int dh, int S, int prefill_shared,
+                                                      void *q_out, size_t q_plane, void *k_shared, void *v_shared,
+                                                      void *k_priv, void *v_priv, float *k_new, float *v_new,
+                                                      const int32_t *private_len, int M, int T, int H, int dh, int S, int prefill_shared,
                                                       int cap_shared, int cap_priv, int max_private,
                                                       float theta, int32_t *status) {
     const int r = blockIdx.x;
     const int HD = H * dh, half = dh >> 1;
     if (r >= M) {   // padding rows of the q tile: zeros
         for (int c = threadIdx.x; c < HD; c += 256) {
-            if (BF16) reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c] = 0;
-            else reinterpret_cast<float *>(q_out)[(size_t)r * HD + c] = 0.f;
+            if (BF16) {
+                reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c] = 0;
+                reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c + q_plane] = 0;
+            } else reinterpret_cast<float *>(q_out)[(size_t)r * HD + c] = 0.f;
         }
         return;
     }
@@ -172,8 +184,14 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
         const size_t qo = (size_t)r * HD + h * dh + i;
         if (BF16) {
             uint16_t *q16 = reinterpret_cast<uint16_t *>(q_out);
-            q16[qo] = f2bf(qa);
-            q16[qo + half] = f2bf(qb);
+            split_bf16(qa, q16[qo], q16[qo + q_plane]);              // q = hi + lo planes
+            split_bf16(qb, q16[qo + half], q16[qo + half + q_plane]);
+            if (!prefill_shared) {                                   // unrounded copy for the in-flight segment
+                k_new[qo] = ka;
+                k_new[qo + half] = kb;
+                v_new[qo] = v1;
+                v_new[qo + half] = v2;
+            }
             if (store_kv) {
                 uint16_t *kc = reinterpret_cast<uint16_t *>(prefill_shared ? k_shared : k_priv);
                 uint16_t *vc = reinterpret_cast<uint16_t *>(prefill_shared ? v_shared : v_priv);
@@ -245,17 +263,18 @@ int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, vo
     return hip_fail(hipGetLastError(), "swiglu launch");
 }
 
-int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, void *k_shared,
-                   void *v_shared, void *k_priv, void *v_priv, const int32_t *private_len, int M, int Mq,
+int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, size_t q_plane,
+                   void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
+                   const int32_t *private_len, int M, int Mq,
                    int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
                    int max_private, float theta, int32_t *status, hipStream_t st) {
     if (bf16)
         hipLaunchKernelGGL(rope_kv_kernel<true>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
-                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S, prefill_shared,
+                           q_plane, k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S, prefill_shared,
                            cap_shared, cap_priv, max_private, theta, status);
     else
         hipLaunchKernelGGL(rope_kv_kernel<false>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
-                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S, prefill_shared,
+                           q_plane, k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S, prefill_shared,
                            cap_shared, cap_priv, max_private, theta, status);
     return hip_fail(hipGetLastError(), "rope_kv launch");
 }

@@ -42,7 +42,7 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act, part, q, o_part, ml_part, logits, status;
+    size_t x, act, part, q, k_new, v_new, o_part, ml_part, logits, status;
     size_t part_floats;
     size_t total;
 };
@@ -135,10 +135,12 @@ Layout make_layout(const seed_model_cfg &c) {
     size_t kmax = d > F ? d : F;
     if (HD > kmax) kmax = HD;
     L.x = take((size_t)L.Mp_cap * d * 4);
-    L.act = take((size_t)L.Mp_cap * kmax * L.es);
+    L.act = take((size_t)L.Mp_cap * kmax * (bf ? 4 : 4));   // bf16 path: hi + lo halves
     L.part_floats = (size_t)(bf ? kMaxSplitK : 1) * L.M_cap * widest;
     L.part = take(L.part_floats * 4);
-    L.q = take((size_t)L.Mq_cap * HD * L.es);
+    L.q = take((size_t)L.Mq_cap * HD * 4);   // bf16 path: hi and lo planes
+    L.k_new = take((size_t)L.M_cap * HD * 4);
+    L.v_new = take((size_t)L.M_cap * HD * 4);
     L.o_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * HD * 4 : 256);
     L.ml_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * H * 2 * 4 : 256);
     L.logits = take((size_t)L.M_cap * V * 4);
@@ -246,9 +248,9 @@ int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int3
 
     int ks_shared = 1, keys_per_range = 32, ks_priv = 0;
     if (bf) {
-        attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, L.cap_p, prefill_shared, &ks_shared, &keys_per_range,
+        attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, g.max_private, prefill_shared, &ks_shared, &keys_per_range,
                        &ks_priv);
-        if (ks_shared + ks_priv > kMaxAttnSlots) {
+        if (ks_shared + ks_priv + 1 > kMaxAttnSlots) {
             set_error("attention plan needs %d partial slots (max %d)", ks_shared + ks_priv, kMaxAttnSlots);
             return SEED_E_CAPACITY;
         }
@@ -264,11 +266,13 @@ int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int3
         if (rc) return rc;
         void *ksl = c->ws + L.ks + L.ks_stride * l, *vsl = c->ws + L.vs + L.ks_stride * l;
         void *kpl = c->ws + L.kp + L.kp_stride * l, *vpl = c->ws + L.vp + L.kp_stride * l;
-        rc = launch_rope_kv(bf, part, sk, stride, q, ksl, vsl, kpl, vpl, private_len, M, Mq, T, H, dh, S,
+        rc = launch_rope_kv(bf, part, sk, stride, q, (size_t)L.Mq_cap * HD, ksl, vsl, kpl, vpl,
+                            (float *)at(c, L.k_new), (float *)at(c, L.v_new), private_len, M, Mq, T, H, dh, S,
                             prefill_shared, L.cap_s, L.cap_p, g.max_private, g.rope_theta, status, st);
         if (rc) return rc;
         if (bf)
-            rc = launch_attn_bf16(dh, q, ksl, vsl, kpl, vpl, private_len, (float *)at(c, L.o_part),
+            rc = launch_attn_bf16(dh, q, (size_t)L.Mq_cap * HD, ksl, vsl, kpl, vpl, private_len,
+                                  (const float *)at(c, L.k_new), (const float *)at(c, L.v_new), (float *)at(c, L.o_part),
                                   (float *)at(c, L.ml_part), act, M, Mp, Mq, N, T, H, S, prefill_shared, L.cap_s,
                                   L.cap_p, g.max_private, ks_shared, keys_per_range, ks_priv, st);
         else

@@ -32,8 +32,9 @@ int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split
                    hipStream_t st);
 int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, void *act, int M, int Mp, int F,
                   hipStream_t st);
-int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, void *k_shared,
-                   void *v_shared, void *k_priv, void *v_priv, const int32_t *private_len, int M, int Mq,
+int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, size_t q_plane,
+                   void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
+                   const int32_t *private_len, int M, int Mq,
                    int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
                    int max_private, float theta, int32_t *status, hipStream_t st);
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
@@ -42,8 +43,9 @@ int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv);
-int launch_attn_bf16(int dh, const void *q, const void *k_shared, const void *vt_shared, const void *k_priv,
-                     const void *vt_priv, const int32_t *private_len, float *o_part, float *ml_part, void *act,
+int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared, const void *vt_shared, const void *k_priv,
+                     const void *vt_priv, const int32_t *private_len, const float *k_new, const float *v_new,
+                     float *o_part, float *ml_part, void *act,
                      int M, int Mp, int Mq, int N, int T, int H, int S, int prefill_shared, int cap_s, int cap_p,
                      int max_private, int ks_shared, int keys_per_range, int ks_priv, hipStream_t st);
 // ---- fp32_path.hip -----------------------------------------------------------------------------------
