@@ -207,6 +207,17 @@ int seed_kv_load(seed_ctx *ctx, int32_t layer, const void *k_shared, const void 
  * overflowed its private capacity) in *host_status, then clears it. */
 int seed_verify_status(seed_ctx *ctx, int32_t *host_status);
 
+/*
+ * Measurement aid for the weight-streaming projection kernel (the dominant kernel of a step).  While
+ * enabled, every projection launch is bracketed by two HIP events on the context's stream.
+ * seed_verify_profile_read synchronises the stream and returns, summed over the launches recorded since
+ * the last read: their number, their total duration in milliseconds and the weight bytes they streamed
+ * (2 bytes per parameter on the bf16 path, 4 on the fp32 path); then forgets them.  Any output pointer may
+ * be NULL.  Profiling adds event packets between kernels, so step timings are taken with it disabled.
+ */
+int seed_verify_profile_enable(seed_ctx *ctx, int32_t enable);
+int seed_verify_profile_read(seed_ctx *ctx, int64_t *launches, double *total_ms, double *weight_bytes);
+
 void seed_verify_destroy(seed_ctx *ctx);
 
 const char *seed_last_error(void);

@@ -55,7 +55,7 @@ class DraftArgsC(C.Structure):
 
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
            "seed_accept_resample", "seed_sample_probs", "seed_kv_load", "seed_verify_status",
-           "seed_verify_destroy", "seed_last_error")
+           "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_destroy", "seed_last_error")
 
 
 def library_path():
@@ -83,6 +83,9 @@ def load_library():
     lib.seed_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.c_int32, C.c_int32]
     lib.seed_verify_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+    lib.seed_verify_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.seed_verify_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                             C.POINTER(C.c_double)]
     lib.seed_verify_destroy.argtypes = [C.c_void_p]
     lib.seed_verify_destroy.restype = None
     _LIB = lib
@@ -260,6 +263,15 @@ class VerifyContext:
                        _ptr(q_out), int(q_stride or 0), _ptr(tok_out), int(tok_stride), _ptr(logits_out))
         _check(self.lib.seed_draft_step(self.handle, C.byref(a)))
         return tok_out
+
+    def profile_enable(self, on):
+        _check(self.lib.seed_verify_profile_enable(self.handle, int(bool(on))))
+
+    def profile_read(self):
+        """(launches, total milliseconds, weight bytes) of the projection launches since the last read."""
+        n, ms, by = C.c_int64(0), C.c_double(0), C.c_double(0)
+        _check(self.lib.seed_verify_profile_read(self.handle, C.byref(n), C.byref(ms), C.byref(by)))
+        return n.value, ms.value, by.value
 
     def status(self):
         s = C.c_int32(0)

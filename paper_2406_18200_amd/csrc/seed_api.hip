@@ -168,6 +168,11 @@ struct seed_ctx {
     char *ws;
     hipStream_t stream;
     bool bf16;
+    // projection-kernel profiling (seed_verify_profile_*)
+    bool profiling = false;
+    std::vector<hipEvent_t> ev_pool;     // start/stop pairs, reused
+    size_t ev_used = 0;
+    double prof_bytes = 0.0;
 };
 
 namespace {
@@ -230,8 +235,8 @@ int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int3
     int32_t *status = (int32_t *)at(c, L.status);
     int rc;
 
-    auto gemm = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
-                    int64_t *stride_out) -> int {
+    auto gemm_launch = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
+                           int64_t *stride_out) -> int {
         if (!bf) {
             *sk_out = 1;
             *stride_out = 0;
@@ -244,6 +249,28 @@ int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int3
         *sk_out = sk;
         *stride_out = (int64_t)M * Nout;
         return launch_gemm_bf16(W, act, out, Nout, K, m_tiles, sk, M, *stride_out, ld, st);
+    };
+    auto gemm = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
+                    int64_t *stride_out) -> int {
+        if (!c->profiling) return gemm_launch(W, Nout, K, out, ld, allow_split, sk_out, stride_out);
+        if (c->ev_used + 2 > c->ev_pool.size()) {
+            for (int i = 0; i < 2; ++i) {
+                hipEvent_t e;
+                int rc2 = hip_fail(hipEventCreate(&e), "event create");
+                if (rc2) return rc2;
+                c->ev_pool.push_back(e);
+            }
+        }
+        hipEvent_t e0 = c->ev_pool[c->ev_used], e1 = c->ev_pool[c->ev_used + 1];
+        int rc2 = hip_fail(hipEventRecord(e0, st), "event record");
+        if (rc2) return rc2;
+        rc2 = gemm_launch(W, Nout, K, out, ld, allow_split, sk_out, stride_out);
+        if (rc2) return rc2;
+        rc2 = hip_fail(hipEventRecord(e1, st), "event record");
+        if (rc2) return rc2;
+        c->ev_used += 2;
+        c->prof_bytes += (double)Nout * K * (double)L.es;
+        return SEED_OK;
     };
 
     int ks_shared = 1, keys_per_range = 32, ks_priv = 0;
@@ -388,7 +415,36 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     return SEED_OK;
 }
 
-void seed_verify_destroy(seed_ctx *ctx) { delete ctx; }
+void seed_verify_destroy(seed_ctx *ctx) {
+    if (ctx == nullptr) return;
+    for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int seed_verify_profile_enable(seed_ctx *c, int32_t enable) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    c->profiling = enable != 0;
+    return SEED_OK;
+}
+
+int seed_verify_profile_read(seed_ctx *c, int64_t *launches, double *total_ms, double *weight_bytes) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    int rc = hip_fail(hipStreamSynchronize(c->stream), "stream sync");
+    if (rc) return rc;
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float t = 0.f;
+        rc = hip_fail(hipEventElapsedTime(&t, c->ev_pool[i], c->ev_pool[i + 1]), "event elapsed");
+        if (rc) return rc;
+        ms += t;
+    }
+    if (launches) *launches = (int64_t)(c->ev_used / 2);
+    if (total_ms) *total_ms = ms;
+    if (weight_bytes) *weight_bytes = c->prof_bytes;
+    c->ev_used = 0;
+    c->prof_bytes = 0.0;
+    return SEED_OK;
+}
 
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     int rc = check_accept_args(args);
