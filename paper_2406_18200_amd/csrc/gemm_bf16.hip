@@ -1,38 +1,113 @@
 // Weight-streaming skinny GEMM for the verify step:  Y[M][Nout] = X[M][K] . W[Nout][K]^T  with M <= 128
-// token rows (N branches x gamma drafts), bf16 operands, fp32 accumulation on the MFMA units.
+// token rows (N branches x gamma drafts), bf16 weights, fp32 accumulation on the MFMA units, with the
+// row-wise work that follows each projection fused into its epilogue.
 //
-// These projections (QKV, O, gate/up, down, LM head) carry 85-98 % of the bytes of a verify step and
-// each weight is used by M <= 128 rows only, so the kernel is HBM-bound: the design goal is that every
-// wavefront streams its share of W exactly once with 1 KiB fully-coalesced loads and no LDS staging.
+// These projections (QKV, O, gate/up, down, LM head) carry 85-98 % of the bytes of a verify step and each
+// weight is used by M <= 128 rows only, so the kernel is HBM-bound.  Design:
 //   * W is repacked once at init into MFMA A-fragment order: tile (nt, kt) = 16 output features x 32
-//     inputs = 1 KiB contiguous, lane l holding W[nt*16 + l%16][kt*32 + 8*(l/16) .. +8].  All k-tiles of
-//     an n-tile are contiguous, so a wavefront's stream is one contiguous run.
-//   * X (activations, tiny, L2-resident) is kept in the matching B-fragment order by its producer, as a
+//     inputs = 1 KiB contiguous, lane l holding W[nt*16 + l%16][kt*32 + 8*(l/16) .. +8]; all k-tiles of an
+//     n-tile are contiguous.  Every wavefront streams its n-tile(s) with fully coalesced 1 KiB non-temporal
+//     loads straight into registers, prefetched one group of k-tiles ahead; W never touches LDS.
+//   * X (activations: tiny, L2-resident) is kept in the matching B-fragment order by its producer, as a
 //     hi/lo pair of bf16 values per element (two MFMAs per weight fragment): the weights stay bf16 but the
 //     activations keep ~16 significant bits, so their rounding does not pile up over 32-40 layers.
+//     The 8 wavefronts of a workgroup own different n-tiles but the same k-range, and stage the X
+//     fragments of that range through LDS in chunks, so each fragment crosses the L2->CU path once per
+//     workgroup instead of once per wavefront (measured: that path, not HBM, was the limiter otherwise).
 //   * v_mfma_f32_16x16x32_bf16 computes Y^T tiles: D[i = feature][j = token row].
-//   * Split-K partial sums go to a [SK][Mpad][Nout] fp32 buffer that the next row kernel reduces in a
-//     fixed order (deterministic; no atomics).
+//   * Split-K across workgroups (narrow outputs need it to fill 256 CUs): partial sums go to an fp32 buffer,
+//     and the LAST workgroup to finish a column group (device-scope counter) re-reads all partials in a fixed
+//     order and runs the epilogue, so results are deterministic and no separate reduction kernel is needed.
+//   * Epilogues: STORE (optional per-row scale = the RMSNorm factor of the input rows), RESID (residual add,
+//     next RMSNorm's gain folded into the packed hi/lo activation, per-tile sums of squares of the new
+//     residual rows), SWIGLU (gate and up tiles are interleaved in the packed weight so one wavefront holds
+//     both; emits the packed activation of the down projection).  The RMSNorm factor 1/rms of the input rows
+//     is applied AFTER the contraction: each consuming workgroup sums the producer's per-tile sums of squares
+//     in a fixed order at its start, while its first weight loads are already in flight.
 #include "seed_internal.h"
 #include "device_utils.h"
 
 namespace seedv {
 namespace {
 
-constexpr int kUnroll = 4;   // k-tiles in flight per wavefront and n-tile
+template <int TM, int WN, int WK>
+int launch_valid(const GemmArgs &a, int epi, hipStream_t st);
 
-template <int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_ws_kernel(const bf16x8 *__restrict__ Wp,
-                                                      const bf16x8 *__restrict__ Xp,
-                                                      float *__restrict__ out, int n_groups, int KT,
-                                                      int SK, int kt_per_split, int m_rows_out,
-                                                      int64_t split_stride, int ld_out) {
-    const int lane = threadIdx.x & 63;
-    const int wid = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wid >= n_groups * SK) return;
-    const int ng = wid / SK, sk = wid - ng * SK;
-    const int k0 = sk * kt_per_split;
-    const int k1 = min(KT, k0 + kt_per_split);
+// Workgroup shapes: WN wavefronts side by side on different n-tile groups x WK wavefronts splitting every
+// k-chunk of the same n-tiles (their partial tiles are summed through LDS at the end, in a fixed order).
+//   wide outputs  (many n-tiles): WN large -> each activation fragment is shared by more wavefronts
+//   narrow outputs (d_model wide): WK large -> enough wavefronts per n-tile to keep 256 CUs streaming
+// U = k-tiles each wavefront prefetches per chunk; a chunk is WK * U k-tiles.
+template <int TM, int WN, int WK>
+struct Shape {
+    static constexpr int kWaves = WN * WK;
+    // LDS budget for the staged activation chunk: 32 KiB for one or two row tiles, 64 KiB above
+    static constexpr int kCap = (TM <= 2 ? 16 : 32) / (WK * TM);        // k-tiles per wavefront that fit
+    static constexpr bool kValid = kCap >= 1;
+    static constexpr int U = kCap >= 4 ? 4 : (kCap >= 2 ? 2 : 1);
+    static constexpr int KC = WK * U;
+    // tiles summed per round of the cross-wavefront reduction (<= 64 KiB of LDS per round)
+    static constexpr int kRedTiles = (64 / (WK * WN)) >= 1 ? (64 / (WK * WN)) : 1;
+};
+
+// Data handed from one workgroup to another INSIDE a launch (split-K partials, per-tile sums of squares)
+// moves with agent-scope relaxed atomic stores / loads: they write through, resp. read around, the per-XCD
+// L2, so the hand-over needs no full-L2 write-back / invalidate fence (which costs ~100 us per launch when
+// every workgroup issues one); ordering is "wait for my stores, workgroup barrier, bump the counter".
+__device__ __forceinline__ void store4_agent(float *p, const f32x4 &v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 load4_agent(const float *p) {
+    f32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+// all of this workgroup's earlier stores have completed; returns true in the workgroup that arrives last
+__device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_flag) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (old == expected - 1);
+        if (*s_flag) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // re-arm
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+__device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int KT, const float *v) {
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split_bf16(v[i], hi[i], lo[i]);
+    uint16_t *dst = act + packed_offset(row, col0, KT);
+    uint2 wh = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+    uint2 wl = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+    *reinterpret_cast<uint2 *>(dst) = wh;
+    *reinterpret_cast<uint2 *>(dst + kActLoOffset) = wl;
+}
+
+template <int TM, int TN, int WN, int WK, int EPI>
+__global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
+    using S = Shape<TM, WN, WK>;
+    constexpr int U = S::U, KC = S::KC, kWaves = S::kWaves;
+    constexpr int FR = KC * TM * 2;                       // 1 KiB activation fragments per chunk
+    constexpr int PER = (FR + kWaves - 1) / kWaves;       // fragments each wavefront copies
+    constexpr int XS_BYTES = FR * 1024;
+    constexpr int RT = S::kRedTiles < TN * TM ? S::kRedTiles : TN * TM;   // tiles per reduction round
+    constexpr int RED_BYTES = (WK > 1) ? WK * WN * RT * 1024 : 16;
+    __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
+    __shared__ int s_last;
+    __shared__ float s_rinv[128];
+    bf16x8(*xs)[TM][2][64] = reinterpret_cast<bf16x8(*)[TM][2][64]>(smem);                 // [KC][TM][2][64]
+    f32x4(*red)[WN][RT][64] = reinterpret_cast<f32x4(*)[WN][RT][64]>(smem);                 // [WK][WN][RT][64]
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wn = w % WN, wk = w / WN;
+    const int nt0 = (blockIdx.x * WN + wn) * TN;
+    const bool active = nt0 < a.NT;
+    const int KT = a.KT;
+    const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
 
     f32x4 acc[TN][TM];
 #pragma unroll
@@ -40,57 +115,193 @@ __global__ __launch_bounds__(256) void gemm_ws_kernel(const bf16x8 *__restrict__
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const bf16x8 *wbase = Wp + ((size_t)ng * TN * KT) * 64 + lane;
-    const bf16x8 *xbase = Xp + lane;
-
-    int kt = k0;
-    for (; kt + kUnroll <= k1; kt += kUnroll) {
-        bf16x8 a[kUnroll][TN], b[kUnroll][TM][2];
+    const bf16x8 *wbase = reinterpret_cast<const bf16x8 *>(a.Wp) + ((size_t)(active ? nt0 : 0) * KT) * 64 + lane;
+    const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(a.Xp);
+    bf16x8 xr[PER];
+    auto load_x = [&](int kc0) {                          // chunk at k-tile kc0 -> registers
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                a[u][tn] = __builtin_nontemporal_load(wbase + ((size_t)tn * KT + kt + u) * 64);
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                b[u][tm][0] = xbase[((size_t)tm * KT + kt + u) * 128];
-                b[u][tm][1] = xbase[((size_t)tm * KT + kt + u) * 128 + 64];
+        for (int i = 0; i < PER; ++i) {
+            const int f = w + i * kWaves;                 // fragment (k, tm, hi|lo) of the chunk
+            if (f < FR) {
+                const int k = f / (TM * 2), r = f - k * (TM * 2);
+                xr[i] = xp[(((size_t)(r >> 1) * KT + min(kc0 + k, KT - 1)) * 2 + (r & 1)) * 64 + lane];
             }
+        }
+    };
+    auto store_x = [&]() {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
+        for (int i = 0; i < PER; ++i) {
+            const int f = w + i * kWaves;
+            if (f < FR) {
+                const int k = f / (TM * 2), r = f - k * (TM * 2);
+                xs[k][r >> 1][r & 1][lane] = xr[i];
+            }
+        }
+    };
+    bf16x8 a_nxt[U][TN];
+    auto load_a = [&](int k) {                            // this wavefront's U k-tiles of the chunk at k
+#pragma unroll
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][tm][1], acc[tn][tm], 0, 0, 0);
-                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][tm][0], acc[tn][tm], 0, 0, 0);
-                }
+                a_nxt[u][tn] = __builtin_nontemporal_load(wbase + ((size_t)tn * KT + min(k + wk * U + u, KT - 1)) * 64);
+    };
+    if (k0 < k1) {
+        load_x(k0);
+        if (active) load_a(k0);
     }
-    for (; kt < k1; ++kt) {
+    if (EPI != EPI_RESID && a.ssq_in != nullptr) {
+        // 1/rms of the input rows from the producer's per-tile sums of squares (visible to the whole
+        // workgroup after the barriers of the chunk loop)
+        for (int row = w; row < a.M; row += kWaves) {
+            float ssum = 0.f;
+            for (int t = lane; t < a.NT_in; t += 64) ssum += a.ssq_in[(size_t)row * a.NT_in + t];
+            ssum = wave_reduce_sum(ssum);
+            if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
+        }
+    }
+    for (int kc = k0; kc < k1; kc += KC) {
+        __syncthreads();
+        store_x();
+        __syncthreads();
+        if (kc + KC < k1) load_x(kc + KC);
+        if (active) {
+            bf16x8 af[U][TN];
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            bf16x8 a = __builtin_nontemporal_load(wbase + ((size_t)tn * KT + kt) * 64);
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const bf16x8 bh = xbase[((size_t)tm * KT + kt) * 128];
-                const bf16x8 bl = xbase[((size_t)tm * KT + kt) * 128 + 64];
-                acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[tn][tm], 0, 0, 0);
-                acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[tn][tm], 0, 0, 0);
+                for (int tn = 0; tn < TN; ++tn) af[u][tn] = a_nxt[u][tn];
+            if (kc + KC < k1) load_a(kc + KC);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (kc + wk * U + u < k1) {
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        const bf16x8 bh = xs[wk * U + u][tm][0][lane], bl = xs[wk * U + u][tm][1][lane];
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][tn], bl, acc[tn][tm], 0, 0, 0);
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][tn], bh, acc[tn][tm], 0, 0, 0);
+                        }
+                    }
+                }
             }
         }
     }
-    // D[i][j]: lane holds features 4*(lane/16)+0..3 of token row lane%16
-    float *obase = out + (size_t)sk * split_stride;
+
+    if (WK > 1) {
+        // sum the WK partial tiles of each n-tile group through LDS (fixed order), RT tiles per round;
+        // wavefronts with wk == 0 end up holding the finished tiles
+#pragma unroll
+        for (int t0 = 0; t0 < TN * TM; t0 += RT) {
+            __syncthreads();                              // xs / the previous round is no longer read
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                if (t0 + t < TN * TM) red[wk][wn][t][lane] = acc[(t0 + t) / TM][(t0 + t) % TM];
+            __syncthreads();
+            if (wk == 0) {
+#pragma unroll
+                for (int t = 0; t < RT; ++t)
+                    if (t0 + t < TN * TM) {
+                        f32x4 s = red[0][wn][t][lane];
+#pragma unroll
+                        for (int i = 1; i < WK; ++i) s += red[i][wn][t][lane];
+                        acc[(t0 + t) / TM][(t0 + t) % TM] = s;
+                    }
+            }
+        }
+    }
+    const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
+
+    // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
+    const int g = lane >> 4, rlow = lane & 15;
+    const int ld_part = a.NT * 16;
+    if (a.SK > 1) {
+        // split-K across workgroups: publish the partial, then the last workgroup of this column group sums
+        // all partials in a fixed order
+        if (owner) {
+            float *pb = a.part + (size_t)blockIdx.y * a.M * ld_part;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = tm * 16 + rlow;
+                if (row >= a.M) continue;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
+            }
+        }
+        if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
+        if (owner) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = tm * 16 + rlow;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (row < a.M) {
+                        const float *pp = a.part + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g;
+                        const size_t ps = (size_t)a.M * ld_part;
+                        int sk = 0;
+                        for (; sk + 4 <= a.SK; sk += 4) {        // four loads in flight; summed in fixed order
+                            const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
+                            const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
+                            s += p0;
+                            s += p1;
+                            s += p2;
+                            s += p3;
+                        }
+                        for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
+                    }
+                    acc[tn][tm] = s;
+                }
+            }
+        }
+    }
+
+    if (!owner) return;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int row = tm * 16 + (lane & 15);
-        if (row >= m_rows_out) continue;
+        const int row = tm * 16 + rlow;
+        const bool valid = row < a.M;
+        if (EPI == EPI_STORE) {
+            const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
+            if (valid) {
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const int col = (ng * TN + tn) * 16 + 4 * (lane >> 4);
-            *reinterpret_cast<f32x4 *>(obase + (size_t)row * ld_out + col) = acc[tn][tm];
+                for (int tn = 0; tn < TN; ++tn)
+                    *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + (nt0 + tn) * 16 + 4 * g) = acc[tn][tm] * sc;
+            }
+        } else if (EPI == EPI_RESID) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int col = (nt0 + tn) * 16 + 4 * g;
+                float ss = 0.f;
+                if (valid) {
+                    float *xp2 = a.x + (size_t)row * ld_part + col;
+                    f32x4 xv = *reinterpret_cast<f32x4 *>(xp2) + acc[tn][tm];
+                    *reinterpret_cast<f32x4 *>(xp2) = xv;
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        ss += xv[i] * xv[i];
+                        v[i] = xv[i] * bf2f(reinterpret_cast<const uint16_t *>(a.gain)[col + i]);
+                    }
+                    store_act4(a.act_out, row, col, a.KT_out, v);
+                }
+                ss += __shfl_xor(ss, 16);
+                ss += __shfl_xor(ss, 32);
+                if (valid && g == 0) a.ssq[(size_t)row * a.NT + nt0 + tn] = ss;
+            }
+        } else {   // EPI_SWIGLU: tile nt0 = gate, nt0 + 1 = up of feature block nt0 / 2
+            if (valid) {
+                const float sc = s_rinv[row];
+                float h[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float gt = acc[0][tm][i] * sc, up = acc[TN - 1][tm][i] * sc;
+                    h[i] = gt / (1.0f + expf(-gt)) * up;
+                }
+                store_act4(a.act_out, row, (nt0 >> 1) * 16 + 4 * g, a.KT_out, h);
+            }
         }
     }
 }
@@ -111,42 +322,91 @@ __global__ void pack_weight_kernel(const uint16_t *__restrict__ W, u32x4 *__rest
     dst[(((size_t)(dst_tile0 + nt * dst_tile_step)) * KT + kt) * 64 + lane] = v;
 }
 
-template <int TM, int TN>
-void launch_one(const void *Wp, const void *Xp, float *out, int NT, int KT, int SK, int m_rows_out,
-                int64_t split_stride, int ld_out, hipStream_t st) {
-    const int n_groups = NT / TN;
-    const int kt_per_split = (KT + SK - 1) / SK;
-    const int waves = n_groups * SK;
-    hipLaunchKernelGGL((gemm_ws_kernel<TM, TN>), dim3((waves + 3) / 4), dim3(256), 0, st,
-                       (const bf16x8 *)Wp, (const bf16x8 *)Xp, out, n_groups, KT, SK, kt_per_split,
-                       m_rows_out, split_stride, ld_out);
+template <int TM, int WN, int WK>
+int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
+    if constexpr (!Shape<TM, WN, WK>::kValid) {
+        set_error("gemm: workgroup shape %dx%d does not fit %d row tiles", WN, WK, TM);
+        return SEED_E_CAPACITY;
+    } else {
+        return launch_valid<TM, WN, WK>(a, epi, st);
+    }
+}
+
+template <int TM, int WN, int WK>
+int launch_valid(const GemmArgs &a, int epi, hipStream_t st) {
+    constexpr int KC = Shape<TM, WN, WK>::KC;
+    GemmArgs b = a;
+    b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
+    b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
+    const int tn = epi == EPI_SWIGLU ? 2 : 1;
+    dim3 grid((a.NT + WN * tn - 1) / (WN * tn), b.SK), block(WN * WK * 64);
+    switch (epi) {
+        case EPI_STORE: hipLaunchKernelGGL((gemm_kernel<TM, 1, WN, WK, EPI_STORE>), grid, block, 0, st, b); break;
+        case EPI_RESID: hipLaunchKernelGGL((gemm_kernel<TM, 1, WN, WK, EPI_RESID>), grid, block, 0, st, b); break;
+        default: hipLaunchKernelGGL((gemm_kernel<TM, 2, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b); break;
+    }
+    return hip_fail(hipGetLastError(), "gemm launch");
+}
+
+template <int TM>
+int launch_tm(const GemmArgs &a, int epi, int wn, int wk, hipStream_t st) {
+    if (wn == 8 && wk == 1) return launch_shape<TM, 8, 1>(a, epi, st);
+    if (wn == 4 && wk == 2) return launch_shape<TM, 4, 2>(a, epi, st);
+    if (wn == 2 && wk == 4) return launch_shape<TM, 2, 4>(a, epi, st);
+    if (wn == 1 && wk == 8) return launch_shape<TM, 1, 8>(a, epi, st);
+    if (wn == 4 && wk == 4) return launch_shape<TM, 4, 4>(a, epi, st);
+    if (wn == 2 && wk == 8) return launch_shape<TM, 2, 8>(a, epi, st);
+    if (wn == 1 && wk == 16) return launch_shape<TM, 1, 16>(a, epi, st);
+    set_error("gemm: unsupported workgroup shape %dx%d", wn, wk);
+    return SEED_E_INVALID_ARG;
 }
 
 }  // namespace
 
-int gemm_bf16_pick_tn(int NT, int m_tiles) {
-    // two n-tiles per wavefront once there are several m-tiles to reuse the activation fragments
-    return (m_tiles >= 3 && NT % 2 == 0) ? 2 : 1;
-}
-
-int launch_gemm_bf16(const void *Wp, const void *Xp, float *out, int Nout, int K, int m_tiles, int SK,
-                     int m_rows_out, int64_t split_stride, int ld_out, hipStream_t st) {
-    const int NT = Nout / 16, KT = K / 32;
-    const int TN = gemm_bf16_pick_tn(NT, m_tiles);
-#define SEEDV_CASE(TMv)                                                                              \
-    case TMv:                                                                                        \
-        if (TN == 2) launch_one<TMv, 2>(Wp, Xp, out, NT, KT, SK, m_rows_out, split_stride, ld_out, st); \
-        else launch_one<TMv, 1>(Wp, Xp, out, NT, KT, SK, m_rows_out, split_stride, ld_out, st);       \
-        break;
+// Launch with an explicit workgroup shape (wn x wk wavefronts) and a.SK workgroups along K.
+int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, hipStream_t st) {
     switch (m_tiles) {
-        SEEDV_CASE(1) SEEDV_CASE(2) SEEDV_CASE(3) SEEDV_CASE(4) SEEDV_CASE(5) SEEDV_CASE(6) SEEDV_CASE(7)
-        SEEDV_CASE(8)
+        case 1: return launch_tm<1>(a, epi, wn, wk, st);
+        case 2: return launch_tm<2>(a, epi, wn, wk, st);
+        case 3: return launch_tm<3>(a, epi, wn, wk, st);
+        case 4: return launch_tm<4>(a, epi, wn, wk, st);
+        case 5: return launch_tm<5>(a, epi, wn, wk, st);
+        case 6: return launch_tm<6>(a, epi, wn, wk, st);
+        case 7: return launch_tm<7>(a, epi, wn, wk, st);
+        case 8: return launch_tm<8>(a, epi, wn, wk, st);
         default:
             set_error("gemm: unsupported m_tiles %d", m_tiles);
             return SEED_E_CAPACITY;
     }
-#undef SEEDV_CASE
-    return hip_fail(hipGetLastError(), "gemm launch");
+}
+
+// Workgroup shape and split from a sweep on MI355X over the 7B / 13B projection shapes at 12, 40 and 96
+// rows: wide outputs share activation fragments across wavefronts (WN), narrow outputs split K inside the
+// workgroup (WK) and, when that still leaves CUs idle, across two or four workgroups.
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *sk) {
+    const int units = epi == EPI_SWIGLU ? NT / 2 : NT;     // n-tile groups a wavefront owns one of
+    *sk = 1;
+    if (m_tiles == 1) {
+        if (units >= 1536) { *wn = 4; *wk = 2; }
+        else if (units >= 600) { *wn = epi == EPI_SWIGLU ? 4 : 2; *wk = 4; }
+        else { *wn = 1; *wk = 8; *sk = 2; }
+    } else if (m_tiles <= 4) {
+        if (units >= 1536) { *wn = 8; *wk = 1; }
+        else if (units >= 600) { *wn = 4; *wk = (m_tiles <= 2 || epi != EPI_SWIGLU) ? 4 : 2; }
+        else { *wn = 4; *wk = 2; *sk = KT >= 256 ? 4 : 2; }
+    } else {
+        if (units >= 1536) { *wn = 4; *wk = 2; }
+        else if (units >= 600) { *wn = 4; *wk = epi == EPI_SWIGLU ? 2 : 4; }
+        else { *wn = 2; *wk = 4; *sk = 2; }
+    }
+    if (KT < 64) *sk = 1;
+}
+
+int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
+    int wn, wk, sk;
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &sk);
+    if (a.SK < 1) a.SK = sk;
+    return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, st);
 }
 
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,

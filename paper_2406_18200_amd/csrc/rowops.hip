@@ -122,25 +122,42 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ p
     store_act8<BF16>(act, r, f, F, h);
 }
 
-// Reduce the QKV partials, rotate q and k (pair (i, i + dh/2), angle pos * theta^(-2i/dh)), store q for the
-// attention kernel and append k, v to the KV cache.
-//   bf16: K cache [H][cap][dh], V cache transposed [H][dh][cap] (the attention kernel reads V^T fragments)
-//   fp32: K and V caches [H][cap][dh]
+// cos/sin table of the rotary embedding, evaluated once in double precision: table[pos][i] = (cos, sin) of
+// pos * theta^(-2i/dh).
+__global__ void rope_table_kernel(float *table, int n_pos, int half, int dh, float theta) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_pos * half) return;
+    const int pos = idx / half, i = idx - pos * half;
+    const double inv_freq = pow((double)theta, -2.0 * (double)i / (double)dh);
+    double sn, cs;
+    sincos((double)pos * inv_freq, &sn, &cs);
+    table[2 * idx] = (float)cs;
+    table[2 * idx + 1] = (float)sn;
+}
+
+// Rotate q and k of the new rows (pair (i, i + dh/2)), store q for the attention kernel and append k, v to
+// the KV cache.  One workgroup per (row, head).
+//   bf16: K cache [H][cap][dh], V cache transposed [H][dh][cap] (the attention kernel reads V^T fragments);
+//         q as hi/lo bf16 planes; an fp32 copy of the new k, v feeds the in-flight attention segment
+//   fp32: K and V caches [H][cap][dh], q fp32
 template <bool BF16>
-__global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ part, int SK, int64_t split_stride,
-                                                      void *q_out, size_t q_plane, void *k_shared, void *v_shared,
-                                                      void *k_priv, void *v_priv, float *k_new, float *v_new,
-                                                      const int32_t *private_len, int M, int T, int H, int dh, int S, int prefill_shared,
-                                                      int cap_shared, int cap_priv, int max_private,
-                                                      float theta, int32_t *status) {
-    const int r = blockIdx.x;
+__global__ __launch_bounds__(64) void rope_kv_kernel(const float *__restrict__ qkv, const float *__restrict__ table,
+                                                     void *q_out, size_t q_plane, void *k_shared, void *v_shared,
+                                                     void *k_priv, void *v_priv, float *k_new, float *v_new,
+                                                     const int32_t *private_len, int M, int T, int H, int dh, int S,
+                                                     int prefill_shared, int cap_shared, int cap_priv,
+                                                     int max_private, int32_t *status) {
+    const int r = blockIdx.x, h = blockIdx.y;
     const int HD = H * dh, half = dh >> 1;
     if (r >= M) {   // padding rows of the q tile: zeros
-        for (int c = threadIdx.x; c < HD; c += 256) {
+        for (int c = threadIdx.x; c < dh; c += 64) {
+            const size_t o = (size_t)r * HD + h * dh + c;
             if (BF16) {
-                reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c] = 0;
-                reinterpret_cast<uint16_t *>(q_out)[(size_t)r * HD + c + q_plane] = 0;
-            } else reinterpret_cast<float *>(q_out)[(size_t)r * HD + c] = 0.f;
+                reinterpret_cast<uint16_t *>(q_out)[o] = 0;
+                reinterpret_cast<uint16_t *>(q_out)[o + q_plane] = 0;
+            } else {
+                reinterpret_cast<float *>(q_out)[o] = 0.f;
+            }
         }
         return;
     }
@@ -154,7 +171,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
     } else {
         int pl = private_len[b];
         if (pl < 0 || pl > max_private) {          // capacity overflow: drop the append, flag it
-            if (threadIdx.x == 0) atomicOr(status, 1);
+            if (threadIdx.x == 0 && h == 0) atomicOr(status, 1);
             pl = min(max(pl, 0), max_private);
             store_kv = false;
         }
@@ -162,23 +179,13 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
         idx = pl + j;
         cap = cap_priv;
     }
-    const float *row = part + (size_t)r * 3 * HD;
-    for (int p = threadIdx.x; p < H * half; p += 256) {
-        const int h = p / half, i = p - h * half;
-        float q1 = 0.f, q2 = 0.f, k1 = 0.f, k2 = 0.f, v1 = 0.f, v2 = 0.f;
-        for (int s = 0; s < SK; ++s) {
-            const float *pr = row + (size_t)s * split_stride + h * dh + i;
-            q1 += pr[0];
-            q2 += pr[half];
-            k1 += pr[HD];
-            k2 += pr[HD + half];
-            v1 += pr[2 * HD];
-            v2 += pr[2 * HD + half];
-        }
-        const double inv_freq = pow((double)theta, -2.0 * (double)i / (double)dh);
-        double sn, cs;
-        sincos((double)pos * inv_freq, &sn, &cs);
-        const float c = (float)cs, s_ = (float)sn;
+    const float *row = qkv + (size_t)r * 3 * HD + h * dh;
+    const float *tb = table + (size_t)pos * half * 2;
+    for (int i = threadIdx.x; i < half; i += 64) {
+        const float q1 = row[i], q2 = row[i + half];
+        const float k1 = row[HD + i], k2 = row[HD + i + half];
+        const float v1 = row[2 * HD + i], v2 = row[2 * HD + i + half];
+        const float c = tb[2 * i], s_ = tb[2 * i + 1];
         const float qa = q1 * c - q2 * s_, qb = q2 * c + q1 * s_;
         const float ka = k1 * c - k2 * s_, kb = k2 * c + k1 * s_;
         const size_t qo = (size_t)r * HD + h * dh + i;
@@ -215,6 +222,32 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *__restrict__ 
                 vc[(head * cap + idx) * dh + i + half] = v2;
             }
         }
+    }
+}
+
+// First stage of a step (bf16 path): x = emb[tok]; act = hi/lo pack of x * gain (un-normalised: the 1/rms
+// factor is applied by the epilogue of the projection that consumes act); ssq[row][t] = sum of squares of
+// the 16 columns of tile t.
+__global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t *__restrict__ tok, const uint16_t *__restrict__ emb,
+                                                         int vocab, const uint16_t *__restrict__ gain,
+                                                         float *__restrict__ x, void *act, float *__restrict__ ssq,
+                                                         int d) {
+    const int r = blockIdx.x;
+    const int t = min(max(tok[r], 0), vocab - 1);
+    const int n8 = d >> 3;                                  // even: d is a multiple of 32
+    for (int c8 = threadIdx.x; c8 < n8; c8 += 256) {
+        const int c = c8 * 8;
+        float v[8], vg[8], ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            v[i] = bf2f(emb[(size_t)t * d + c + i]);
+            x[(size_t)r * d + c + i] = v[i];
+            ss += v[i] * v[i];
+            vg[i] = v[i] * bf2f(gain[c + i]);
+        }
+        store_act8<true>(act, r, c, d, vg);
+        ss += __shfl_xor(ss, 1);                            // the two halves of a 16-column tile
+        if ((c8 & 1) == 0) ssq[(size_t)r * (d >> 4) + (c8 >> 1)] = ss;
     }
 }
 
@@ -263,20 +296,32 @@ int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, vo
     return hip_fail(hipGetLastError(), "swiglu launch");
 }
 
-int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, size_t q_plane,
+int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
                    void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
-                   const int32_t *private_len, int M, int Mq,
-                   int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
-                   int max_private, float theta, int32_t *status, hipStream_t st) {
+                   const int32_t *private_len, int M, int Mq, int T, int H, int dh, int S, int prefill_shared,
+                   int cap_shared, int cap_priv, int max_private, int32_t *status, hipStream_t st) {
     if (bf16)
-        hipLaunchKernelGGL(rope_kv_kernel<true>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
-                           q_plane, k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S, prefill_shared,
-                           cap_shared, cap_priv, max_private, theta, status);
+        hipLaunchKernelGGL(rope_kv_kernel<true>, dim3(Mq, H), dim3(64), 0, st, qkv, rope_table, q_out, q_plane,
+                           k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S,
+                           prefill_shared, cap_shared, cap_priv, max_private, status);
     else
-        hipLaunchKernelGGL(rope_kv_kernel<false>, dim3(Mq), dim3(256), 0, st, part, SK, split_stride, q_out,
-                           q_plane, k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S, prefill_shared,
-                           cap_shared, cap_priv, max_private, theta, status);
+        hipLaunchKernelGGL(rope_kv_kernel<false>, dim3(Mq, H), dim3(64), 0, st, qkv, rope_table, q_out, q_plane,
+                           k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S,
+                           prefill_shared, cap_shared, cap_priv, max_private, status);
     return hip_fail(hipGetLastError(), "rope_kv launch");
+}
+
+int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t st) {
+    const int n = n_pos * (dh / 2);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, table, n_pos, dh / 2, dh, theta);
+    return hip_fail(hipGetLastError(), "rope_table launch");
+}
+
+int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void *gain, float *x, void *act,
+                      float *ssq, int M, int d, hipStream_t st) {
+    hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(256), 0, st, tok, (const uint16_t *)emb, vocab,
+                       (const uint16_t *)gain, x, act, ssq, d);
+    return hip_fail(hipGetLastError(), "embed_norm launch");
 }
 
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,

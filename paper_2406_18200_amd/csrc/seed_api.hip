@@ -27,7 +27,7 @@ int hip_fail(hipError_t e, const char *what) {
 
 namespace {
 
-constexpr int kMaxSplitK = 16;
+constexpr int kMaxCounters = 4096;
 constexpr int kMaxAttnSlots = 128;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -42,7 +42,8 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act, part, q, k_new, v_new, o_part, ml_part, logits, status;
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, rope, q, k_new, v_new, o_part, ml_part, logits, status;
+    int n_pos;
     size_t part_floats;
     size_t total;
 };
@@ -132,12 +133,19 @@ Layout make_layout(const seed_model_cfg &c) {
     size_t widest = 3 * HD;
     if (2 * F > widest) widest = 2 * F;
     if (d > widest) widest = d;
-    size_t kmax = d > F ? d : F;
-    if (HD > kmax) kmax = HD;
     L.x = take((size_t)L.Mp_cap * d * 4);
-    L.act = take((size_t)L.Mp_cap * kmax * (bf ? 4 : 4));   // bf16 path: hi + lo halves
-    L.part_floats = (size_t)(bf ? kMaxSplitK : 1) * L.M_cap * widest;
+    L.act_d = take((size_t)L.Mp_cap * d * 4);             // bf16 path: hi + lo halves; fp32 path: plain floats
+    L.act_hd = take((size_t)L.Mp_cap * HD * 4);
+    L.act_f = take((size_t)L.Mp_cap * F * 4);
+    // split-K partials: SK * Nout stays near 384 workgroups * 128 columns; V covers an unsplit LM head
+    L.part_floats = (size_t)L.M_cap * (bf ? (widest > 65536 ? widest : 65536) : widest);
     L.part = take(L.part_floats * 4);
+    L.qkv = take((size_t)L.M_cap * 3 * HD * 4);
+    L.rinv = take((size_t)L.Mp_cap * 4);
+    L.ssq = take((size_t)L.M_cap * (d / 16 + 1) * 4);
+    L.counters = take(4096 * 4);
+    L.n_pos = c.max_shared + c.max_private + c.max_rows_per_branch + 1;
+    L.rope = take((size_t)L.n_pos * dh * 4);
     L.q = take((size_t)L.Mq_cap * HD * 4);   // bf16 path: hi and lo planes
     L.k_new = take((size_t)L.M_cap * HD * 4);
     L.v_new = take((size_t)L.M_cap * HD * 4);
@@ -147,14 +155,6 @@ Layout make_layout(const seed_model_cfg &c) {
     L.status = take(256);
     L.total = off;
     return L;
-}
-
-// split-K factor: enough wavefronts to keep 256 CUs streaming, at least 8 k-tiles per split
-int pick_split_k(int n_groups, int KT) {
-    int sk = (2048 + n_groups - 1) / n_groups;
-    if (sk > kMaxSplitK) sk = kMaxSplitK;
-    while (sk > 1 && KT / sk < 8) --sk;
-    return sk < 1 ? 1 : sk;
 }
 
 }  // namespace
@@ -218,116 +218,185 @@ int check_accept_args(const seed_accept_args *a) {
     return SEED_OK;
 }
 
-// The forward pass over M = N*T rows; leaves logits (if wanted) in `logits`.
-int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
-                const int32_t *private_len, float *logits) {
+// Wraps one projection launch with the optional profiling events.
+template <class F>
+int profiled(seed_ctx *c, double weight_bytes, F &&launch) {
+    if (!c->profiling) return launch();
+    if (c->ev_used + 2 > c->ev_pool.size()) {
+        for (int i = 0; i < 2; ++i) {
+            hipEvent_t e;
+            int rc = hip_fail(hipEventCreate(&e), "event create");
+            if (rc) return rc;
+            c->ev_pool.push_back(e);
+        }
+    }
+    hipEvent_t e0 = c->ev_pool[c->ev_used], e1 = c->ev_pool[c->ev_used + 1];
+    int rc = hip_fail(hipEventRecord(e0, c->stream), "event record");
+    if (rc) return rc;
+    rc = launch();
+    if (rc) return rc;
+    rc = hip_fail(hipEventRecord(e1, c->stream), "event record");
+    if (rc) return rc;
+    c->ev_used += 2;
+    c->prof_bytes += weight_bytes;
+    return SEED_OK;
+}
+
+struct KvPtrs { void *ks, *vs, *kp, *vp; };
+KvPtrs kv_layer(const seed_ctx *c, int l) {
+    const Layout &L = c->L;
+    return {c->ws + L.ks + L.ks_stride * l, c->ws + L.vs + L.ks_stride * l, c->ws + L.kp + L.kp_stride * l,
+            c->ws + L.vp + L.kp_stride * l};
+}
+
+// bf16 path: projections with fused epilogues (see gemm_bf16.hip); 7 launches per layer.
+int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
+                     const int32_t *private_len, float *logits) {
     const seed_model_cfg &g = c->cfg;
     const Layout &L = c->L;
     hipStream_t st = c->stream;
-    const bool bf = c->bf16;
-    const int M = N * T, Mp = bf ? round_up(M, 16) : M, Mq = bf ? round_up(M, 32) : M;
+    const int M = N * T, Mp = round_up(M, 16), Mq = round_up(M, 32);
     const int d = g.d_model, F = g.d_ff, H = g.n_heads, dh = g.head_dim, HD = L.HD, V = g.vocab;
     const int m_tiles = Mp / 16;
     float *x = (float *)at(c, L.x);
-    void *act = at(c, L.act);
-    float *part = (float *)at(c, L.part);
-    void *q = at(c, L.q);
+    float *ssq = (float *)at(c, L.ssq);
     int32_t *status = (int32_t *)at(c, L.status);
+    const size_t q_plane = (size_t)L.Mq_cap * HD;
     int rc;
 
-    auto gemm_launch = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
-                           int64_t *stride_out) -> int {
-        if (!bf) {
-            *sk_out = 1;
-            *stride_out = 0;
-            return launch_gemm_f32(W, act, out, M, Nout, K, ld, st);
-        }
-        const int NT = Nout / 16, KT = K / 32;
-        const int tn = gemm_bf16_pick_tn(NT, m_tiles);
-        int sk = allow_split ? pick_split_k(NT / tn, KT) : 1;
+    auto gemm = [&](int epi, const void *W, int Nout, int K, const void *Xp, GemmArgs a) -> int {
+        a.Wp = W;
+        a.Xp = Xp;
+        a.NT = Nout / 16;
+        a.KT = K / 32;
+        a.M = M;
+        a.part = (float *)at(c, L.part);
+        a.counters = (int *)at(c, L.counters);
+        a.eps = g.rms_eps;
+        int wn, wk, sk;
+        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &sk);
         while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
-        *sk_out = sk;
-        *stride_out = (int64_t)M * Nout;
-        return launch_gemm_bf16(W, act, out, Nout, K, m_tiles, sk, M, *stride_out, ld, st);
-    };
-    auto gemm = [&](const void *W, int Nout, int K, float *out, int ld, bool allow_split, int *sk_out,
-                    int64_t *stride_out) -> int {
-        if (!c->profiling) return gemm_launch(W, Nout, K, out, ld, allow_split, sk_out, stride_out);
-        if (c->ev_used + 2 > c->ev_pool.size()) {
-            for (int i = 0; i < 2; ++i) {
-                hipEvent_t e;
-                int rc2 = hip_fail(hipEventCreate(&e), "event create");
-                if (rc2) return rc2;
-                c->ev_pool.push_back(e);
-            }
+        a.SK = sk;
+        if (sk > 1 && a.NT / wn + 2 > kMaxCounters) {
+            set_error("projection with %d column groups exceeds the counter array", a.NT / wn);
+            return SEED_E_CAPACITY;
         }
-        hipEvent_t e0 = c->ev_pool[c->ev_used], e1 = c->ev_pool[c->ev_used + 1];
-        int rc2 = hip_fail(hipEventRecord(e0, st), "event record");
-        if (rc2) return rc2;
-        rc2 = gemm_launch(W, Nout, K, out, ld, allow_split, sk_out, stride_out);
-        if (rc2) return rc2;
-        rc2 = hip_fail(hipEventRecord(e1, st), "event record");
-        if (rc2) return rc2;
-        c->ev_used += 2;
-        c->prof_bytes += (double)Nout * K * (double)L.es;
-        return SEED_OK;
+        return profiled(c, (double)Nout * K * 2.0, [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
     };
 
     int ks_shared = 1, keys_per_range = 32, ks_priv = 0;
-    if (bf) {
-        attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, g.max_private, prefill_shared, &ks_shared, &keys_per_range,
-                       &ks_priv);
-        if (ks_shared + ks_priv + 1 > kMaxAttnSlots) {
-            set_error("attention plan needs %d partial slots (max %d)", ks_shared + ks_priv, kMaxAttnSlots);
-            return SEED_E_CAPACITY;
-        }
+    attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, g.max_private, prefill_shared, &ks_shared, &keys_per_range,
+                   &ks_priv);
+    if (ks_shared + ks_priv + 1 > kMaxAttnSlots) {
+        set_error("attention plan needs %d partial slots (max %d)", ks_shared + ks_priv + 1, kMaxAttnSlots);
+        return SEED_E_CAPACITY;
     }
 
-    rc = launch_rownorm(bf, x, nullptr, 0, 0, row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), g.rms_eps, act, M,
-                        Mp, d, st);
+    rc = launch_embed_norm(row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), x, at(c, L.act_d), ssq, M, d, st);
     if (rc) return rc;
     for (int l = 0; l < g.n_layers; ++l) {
-        int sk;
-        int64_t stride;
-        rc = gemm(layer_w(c, l, L.w_qkv), 3 * HD, d, part, 3 * HD, true, &sk, &stride);
+        GemmArgs a{};
+        a.out = (float *)at(c, L.qkv);
+        a.ld_out = 3 * HD;
+        a.ssq_in = ssq;
+        a.NT_in = d / 16;
+        rc = gemm(EPI_STORE, layer_w(c, l, L.w_qkv), 3 * HD, d, at(c, L.act_d), a);
         if (rc) return rc;
-        void *ksl = c->ws + L.ks + L.ks_stride * l, *vsl = c->ws + L.vs + L.ks_stride * l;
-        void *kpl = c->ws + L.kp + L.kp_stride * l, *vpl = c->ws + L.vp + L.kp_stride * l;
-        rc = launch_rope_kv(bf, part, sk, stride, q, (size_t)L.Mq_cap * HD, ksl, vsl, kpl, vpl,
-                            (float *)at(c, L.k_new), (float *)at(c, L.v_new), private_len, M, Mq, T, H, dh, S,
-                            prefill_shared, L.cap_s, L.cap_p, g.max_private, g.rope_theta, status, st);
+        const KvPtrs kv = kv_layer(c, l);
+        rc = launch_rope_kv(true, (const float *)at(c, L.qkv), (const float *)at(c, L.rope), at(c, L.q), q_plane, kv.ks,
+                            kv.vs, kv.kp, kv.vp, (float *)at(c, L.k_new), (float *)at(c, L.v_new), private_len, M, Mq, T,
+                            H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private, status, st);
         if (rc) return rc;
-        if (bf)
-            rc = launch_attn_bf16(dh, q, (size_t)L.Mq_cap * HD, ksl, vsl, kpl, vpl, private_len,
-                                  (const float *)at(c, L.k_new), (const float *)at(c, L.v_new), (float *)at(c, L.o_part),
-                                  (float *)at(c, L.ml_part), act, M, Mp, Mq, N, T, H, S, prefill_shared, L.cap_s,
-                                  L.cap_p, g.max_private, ks_shared, keys_per_range, ks_priv, st);
-        else
-            rc = launch_attn_f32(q, ksl, vsl, kpl, vpl, private_len, (float *)act, M, T, H, dh, S, prefill_shared,
-                                 L.cap_s, L.cap_p, g.max_private, st);
+        rc = launch_attn_bf16(dh, at(c, L.q), q_plane, kv.ks, kv.vs, kv.kp, kv.vp, private_len,
+                              (const float *)at(c, L.k_new), (const float *)at(c, L.v_new), (float *)at(c, L.o_part),
+                              (float *)at(c, L.ml_part), at(c, L.act_hd), M, Mp, Mq, N, T, H, S, prefill_shared, L.cap_s,
+                              L.cap_p, g.max_private, ks_shared, keys_per_range, ks_priv, st);
         if (rc) return rc;
-        rc = gemm(layer_w(c, l, L.w_o), d, HD, part, d, true, &sk, &stride);
+        GemmArgs o{};
+        o.x = x;
+        o.gain = layer_w(c, l, L.g_ffn);
+        o.act_out = (uint16_t *)at(c, L.act_d);
+        o.KT_out = d / 32;
+        o.ssq = ssq;
+        rc = gemm(EPI_RESID, layer_w(c, l, L.w_o), d, HD, at(c, L.act_hd), o);
         if (rc) return rc;
-        rc = launch_rownorm(bf, x, part, sk, stride, nullptr, nullptr, V, layer_w(c, l, L.g_ffn), g.rms_eps, act, M,
-                            Mp, d, st);
+        GemmArgs gu{};
+        gu.ssq_in = ssq;
+        gu.NT_in = d / 16;
+        gu.act_out = (uint16_t *)at(c, L.act_f);
+        gu.KT_out = F / 32;
+        rc = gemm(EPI_SWIGLU, layer_w(c, l, L.w_gu), 2 * F, d, at(c, L.act_d), gu);
         if (rc) return rc;
-        rc = gemm(layer_w(c, l, L.w_gu), 2 * F, d, part, 2 * F, true, &sk, &stride);
-        if (rc) return rc;
-        rc = launch_swiglu(bf, part, sk, stride, act, M, Mp, F, st);
-        if (rc) return rc;
-        rc = gemm(layer_w(c, l, L.w_d), d, F, part, d, true, &sk, &stride);
-        if (rc) return rc;
-        const void *next_gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
-        rc = launch_rownorm(bf, x, part, sk, stride, nullptr, nullptr, V, next_gain, g.rms_eps, act, M, Mp, d, st);
+        GemmArgs dn = o;
+        dn.gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
+        rc = gemm(EPI_RESID, layer_w(c, l, L.w_d), d, F, at(c, L.act_f), dn);
         if (rc) return rc;
     }
     if (logits != nullptr) {
-        int sk;
-        int64_t stride;
-        rc = gemm(at(c, L.lm), V, d, logits, V, false, &sk, &stride);
+        GemmArgs a{};
+        a.out = logits;
+        a.ld_out = V;
+        a.ssq_in = ssq;
+        a.NT_in = d / 16;
+        rc = gemm(EPI_STORE, at(c, L.lm), V, d, at(c, L.act_d), a);
         if (rc) return rc;
     }
     return SEED_OK;
+}
+
+// fp32 path: plain kernels, one stage per launch.
+int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
+                    const int32_t *private_len, float *logits) {
+    const seed_model_cfg &g = c->cfg;
+    const Layout &L = c->L;
+    hipStream_t st = c->stream;
+    const int M = N * T;
+    const int d = g.d_model, F = g.d_ff, H = g.n_heads, dh = g.head_dim, HD = L.HD, V = g.vocab;
+    float *x = (float *)at(c, L.x);
+    float *part = (float *)at(c, L.part);
+    void *act_d = at(c, L.act_d), *act_hd = at(c, L.act_hd), *act_f = at(c, L.act_f);
+    int32_t *status = (int32_t *)at(c, L.status);
+    int rc;
+    auto gemm = [&](const void *W, int Nout, int K, const void *X, float *out, int ld) -> int {
+        return profiled(c, (double)Nout * K * 4.0, [&]() { return launch_gemm_f32(W, X, out, M, Nout, K, ld, st); });
+    };
+    rc = launch_rownorm(false, x, nullptr, 0, 0, row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), g.rms_eps, act_d, M,
+                        M, d, st);
+    if (rc) return rc;
+    for (int l = 0; l < g.n_layers; ++l) {
+        rc = gemm(layer_w(c, l, L.w_qkv), 3 * HD, d, act_d, part, 3 * HD);
+        if (rc) return rc;
+        const KvPtrs kv = kv_layer(c, l);
+        rc = launch_rope_kv(false, part, (const float *)at(c, L.rope), at(c, L.q), 0, kv.ks, kv.vs, kv.kp, kv.vp, nullptr,
+                            nullptr, private_len, M, M, T, H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private,
+                            status, st);
+        if (rc) return rc;
+        rc = launch_attn_f32(at(c, L.q), kv.ks, kv.vs, kv.kp, kv.vp, private_len, (float *)act_hd, M, T, H, dh, S,
+                             prefill_shared, L.cap_s, L.cap_p, g.max_private, st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_o), d, HD, act_hd, part, d);
+        if (rc) return rc;
+        rc = launch_rownorm(false, x, part, 1, 0, nullptr, nullptr, V, layer_w(c, l, L.g_ffn), g.rms_eps, act_d, M, M, d,
+                            st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_gu), 2 * F, d, act_d, part, 2 * F);
+        if (rc) return rc;
+        rc = launch_swiglu(false, part, 1, 0, act_f, M, M, F, st);
+        if (rc) return rc;
+        rc = gemm(layer_w(c, l, L.w_d), d, F, act_f, part, d);
+        if (rc) return rc;
+        const void *next_gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
+        rc = launch_rownorm(false, x, part, 1, 0, nullptr, nullptr, V, next_gain, g.rms_eps, act_d, M, M, d, st);
+        if (rc) return rc;
+    }
+    if (logits != nullptr) return gemm(at(c, L.lm), V, d, act_d, logits, V);
+    return SEED_OK;
+}
+
+int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
+                const int32_t *private_len, float *logits) {
+    return c->bf16 ? run_forward_bf16(c, N, T, S, prefill_shared, row_tok, private_len, logits)
+                   : run_forward_f32(c, N, T, S, prefill_shared, row_tok, private_len, logits);
 }
 
 }  // namespace
@@ -410,6 +479,7 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     else SEEDV_TRY(copy(at(c, L.lm), w->lm_head, V * d * es));
     // KV caches and scratch start at zero: chunked key loops may touch (masked) entries past the valid length
     SEEDV_TRY(hip_fail(hipMemsetAsync(at(c, L.ks), 0, L.total - L.ks, st), "workspace clear"));
+    SEEDV_TRY(launch_rope_table((float *)at(c, L.rope), L.n_pos, cfg->head_dim, cfg->rope_theta, st));
 #undef SEEDV_TRY
     *out = c;
     return SEED_OK;

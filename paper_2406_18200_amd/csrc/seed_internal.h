@@ -21,9 +21,27 @@ int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, 
 
 namespace seedv {
 // ---- gemm_bf16.hip -----------------------------------------------------------------------------
-int gemm_bf16_pick_tn(int NT, int m_tiles);
-int launch_gemm_bf16(const void *Wp, const void *Xp, float *out, int Nout, int K, int m_tiles, int SK,
-                     int m_rows_out, int64_t split_stride, int ld_out, hipStream_t st);
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+struct GemmArgs {
+    const void *Wp;        // packed bf16 weights, NT x KT tiles of 1 KiB
+    const void *Xp;        // packed hi/lo bf16 activations [m-tile][KT][hi|lo][64][8]
+    int NT, KT, kt_per_split, SK, M;
+    float *part;           // [SK][M][NT*16] split-K partial sums (SK > 1)
+    int *counters;         // >= groups + 1 ints, zero on entry and left zero on exit
+    float *out;            // STORE: out[row * ld_out + col]
+    int ld_out;
+    const float *ssq_in;   // STORE (optional) / SWIGLU: [M][NT_in] per-tile sums of squares of the input rows;
+    int NT_in;             //   the epilogue scales row r by 1/sqrt(sum / (16 NT_in) + eps)
+    float *x;              // RESID: fp32 residual stream [M][NT*16], updated in place
+    const void *gain;      // RESID: bf16 gain [NT*16] of the norm that follows
+    uint16_t *act_out;     // RESID / SWIGLU: packed hi/lo activation for the next projection
+    int KT_out;            //   its k-tile count
+    float *ssq;            // RESID: [M][NT] per-tile sums of squares of the new residual stream (out)
+    float eps;
+};
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *sk);
+int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, hipStream_t st);
+int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st);   // a.SK < 1: pick automatically
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,
                        hipStream_t st);
 // ---- rowops.hip ----------------------------------------------------------------------------------
@@ -32,11 +50,14 @@ int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split
                    hipStream_t st);
 int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, void *act, int M, int Mp, int F,
                   hipStream_t st);
-int launch_rope_kv(bool bf16, const float *part, int SK, int64_t split_stride, void *q_out, size_t q_plane,
+int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void *gain, float *x, void *act,
+                      float *ssq, int M, int d, hipStream_t st);
+int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t st);
+int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
                    void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
                    const int32_t *private_len, int M, int Mq,
                    int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
-                   int max_private, float theta, int32_t *status, hipStream_t st);
+                   int max_private, int32_t *status, hipStream_t st);
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
                      hipStream_t st);
 int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
