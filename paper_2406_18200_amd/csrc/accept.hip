@@ -177,53 +177,125 @@ __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, 
     return sm.tok;
 }
 
+// Per-row results of the parallel first phase
+struct RowInfo {
+    float mx[16], sum[16];
+    int ok[16], best[16];
+    float wm[kWaves];
+    int wi[kWaves];
+};
+
+// One workgroup per branch.  Phase 1: the (up to 16) target rows of the branch are handled concurrently, each
+// by a group of 16 / rows wavefronts: softmax statistics (or argmax in greedy mode), p(x) and the accept test.
+// Phase 2: the whole workgroup draws the replacement / bonus token for the one row that needs it.
 __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a) {
     __shared__ Shared sm;
+    __shared__ RowInfo ri;
     const int b = blockIdx.x;
     const int G = a.gamma, Tp = a.n_target_rows, V = a.vocab;
     const int is_logits = a.probs_kind == SEED_KIND_LOGITS;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int acc = 0, new_tok = -1;
     bool rejected = false;
-    for (int j = 0; j < G; ++j) {
-        if (rejected && (a.p_tok == nullptr || a.greedy)) break;
-        const float *src = a.p_or_logits + ((size_t)b * Tp + j) * V;
-        const int x = a.draft_tok[b * G + j];
-        bool ok;
-        int best = -1;
-        TargetRow row{src, 0, 0.f, 1.f, 1.f};
-        if (a.greedy) {
-            best = block_argmax(src, V, sm);
-            ok = (x == best);
-        } else {
-            row = make_row(src, is_logits, a.temperature, V, sm);
-            const float pj = row.p(x);
-            if (a.p_tok != nullptr && threadIdx.x == 0) a.p_tok[b * G + j] = pj;
-            const float qj = a.q[((size_t)b * G + j) * V + x];
-            ok = __fmul_rn(a.u_acc[b * G + j], qj) < pj;
+    int rej_row = -1;
+    for (int r0 = 0; r0 < Tp; r0 += 16) {
+        const int rows = min(16, Tp - r0);
+        int wpr = 1;                                       // wavefronts per row: power of two <= 16 / rows
+        while (wpr * 2 * rows <= kWaves) wpr *= 2;
+        const int r = wave / wpr, sub = wave - r * wpr;    // this wavefront's row (if r < rows) and slice
+        const bool has_row = r < rows;
+        const float *src = a.p_or_logits + ((size_t)b * Tp + r0 + (has_row ? r : 0)) * V;
+        // pass 1: maximum (and its lowest index) of the row
+        float mv = -INFINITY;
+        int mi = 0x7fffffff;
+        if (has_row && (is_logits || a.greedy)) {
+            for (int v = sub * 64 + lane; v < V; v += wpr * 64) {
+                const float x = src[v];
+                if (x > mv) { mv = x; mi = v; }
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const float ov = __shfl_xor(mv, off);
+                const int oi = __shfl_xor(mi, off);
+                if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+            }
         }
-        if (rejected) continue;
-        if (ok) { ++acc; continue; }
-        rejected = true;
-        if (a.greedy) {
-            new_tok = best;
-        } else {
-            const float *q = a.q + ((size_t)b * G + j) * V;
-            new_tok = draw_fixed<1>(row, q, a.u_res[b], V, sm);
-            if (new_tok < 0) new_tok = draw_fixed<0>(row, q, a.u_res[b], V, sm);
+        if (lane == 0) { ri.wm[wave] = mv; ri.wi[wave] = mi; }
+        __syncthreads();
+        if (has_row) {
+            mv = ri.wm[r * wpr];
+            mi = ri.wi[r * wpr];
+            for (int i = 1; i < wpr; ++i) {
+                const float ov = ri.wm[r * wpr + i];
+                const int oi = ri.wi[r * wpr + i];
+                if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+            }
         }
+        __syncthreads();
+        // pass 2: sum of exp((x - max) / temperature)
+        float sv = 0.f;
+        if (has_row && is_logits && !a.greedy) {
+            for (int v = sub * 64 + lane; v < V; v += wpr * 64) sv += expf(__fdiv_rn(src[v] - mv, a.temperature));
+            sv = wave_sum(sv);
+        }
+        if (lane == 0) ri.wm[wave] = sv;
+        __syncthreads();
+        if (has_row && sub == 0 && lane == 0) {
+            float tot = ri.wm[r * wpr];
+            for (int i = 1; i < wpr; ++i) tot += ri.wm[r * wpr + i];       // fixed order
+            const int j = r0 + r;
+            ri.mx[r] = mv;
+            ri.sum[r] = (is_logits && !a.greedy) ? tot : 1.f;
+            ri.best[r] = mi;
+            int ok = 0;
+            if (j < G) {
+                const int x = a.draft_tok[b * G + j];
+                if (a.greedy) {
+                    ok = (x == mi);
+                    if (a.p_tok != nullptr) a.p_tok[b * G + j] = 0.f;
+                } else {
+                    const TargetRow row{src, is_logits, mv, ri.sum[r], a.temperature};
+                    const float pj = row.p(x);
+                    if (a.p_tok != nullptr) a.p_tok[b * G + j] = pj;
+                    ok = __fmul_rn(a.u_acc[b * G + j], a.q[((size_t)b * G + j) * V + x]) < pj;
+                }
+            }
+            ri.ok[r] = ok;
+        }
+        __syncthreads();
+        // left-to-right scan of this batch (uniform over the workgroup)
+        for (int r2 = 0; r2 < rows && !rejected; ++r2) {
+            const int j = r0 + r2;
+            if (j >= G) break;
+            if (ri.ok[r2]) { ++acc; continue; }
+            rejected = true;
+            rej_row = r2;
+        }
+        const bool bonus_here = !rejected && Tp == G + 1 && G >= r0 && G < r0 + rows;
+        if (rej_row >= 0 || bonus_here) {
+            const int r2 = rej_row >= 0 ? rej_row : G - r0;
+            const int j = r0 + r2;
+            const float *rsrc = a.p_or_logits + ((size_t)b * Tp + j) * V;
+            if (a.greedy) {
+                new_tok = ri.best[r2];
+            } else {
+                const TargetRow row{rsrc, is_logits, ri.mx[r2], ri.sum[r2], a.temperature};
+                if (rej_row >= 0) {
+                    const float *q = a.q + ((size_t)b * G + j) * V;
+                    new_tok = draw_fixed<1>(row, q, a.u_res[b], V, sm);
+                    if (new_tok < 0) new_tok = draw_fixed<0>(row, q, a.u_res[b], V, sm);
+                } else {
+                    new_tok = draw_fixed<0>(row, nullptr, a.u_res[b], V, sm);
+                }
+            }
+            rej_row = -1;
+        }
+        __syncthreads();
+        if (rejected && (a.p_tok == nullptr || a.greedy)) break;     // later rows only matter for p_tok
     }
-    if (!rejected && Tp == G + 1) {
-        const float *src = a.p_or_logits + ((size_t)b * Tp + G) * V;
-        if (a.greedy) {
-            new_tok = block_argmax(src, V, sm);
-        } else {
-            TargetRow row = make_row(src, is_logits, a.temperature, V, sm);
-            new_tok = draw_fixed<0>(row, nullptr, a.u_res[b], V, sm);
-        }
-    }
-    if (a.greedy && a.p_tok != nullptr && threadIdx.x < G) a.p_tok[b * G + threadIdx.x] = 0.f;
-    if (threadIdx.x <= G) {
-        const int j = threadIdx.x;
+    if (a.greedy && a.p_tok != nullptr)
+        for (int j = threadIdx.x; j < G; j += kBlock) a.p_tok[b * G + j] = 0.f;
+    for (int j = threadIdx.x; j <= G; j += kBlock) {
         int t = -1;
         if (j < acc) t = a.draft_tok[b * G + j];
         else if (j == acc) t = new_tok;

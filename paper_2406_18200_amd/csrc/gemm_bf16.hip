@@ -30,22 +30,22 @@
 namespace seedv {
 namespace {
 
-template <int TM, int WN, int WK>
-int launch_valid(const GemmArgs &a, int epi, hipStream_t st);
-
 // Workgroup shapes: WN wavefronts side by side on different n-tile groups x WK wavefronts splitting every
 // k-chunk of the same n-tiles (their partial tiles are summed through LDS at the end, in a fixed order).
 //   wide outputs  (many n-tiles): WN large -> each activation fragment is shared by more wavefronts
 //   narrow outputs (d_model wide): WK large -> enough wavefronts per n-tile to keep 256 CUs streaming
 // U = k-tiles each wavefront prefetches per chunk; a chunk is WK * U k-tiles.
-template <int TM, int WN, int WK>
+template <int TM, int TN, int WN, int WK>
 struct Shape {
     static constexpr int kWaves = WN * WK;
     // LDS budget for the staged activation chunk: 32 KiB for one or two row tiles, 64 KiB above
     static constexpr int kCap = (TM <= 2 ? 16 : 32) / (WK * TM);        // k-tiles per wavefront that fit
     static constexpr bool kValid = kCap >= 1;
-    static constexpr int U = kCap >= 4 ? 4 : (kCap >= 2 ? 2 : 1);
+    static constexpr int kWant = TM <= 2 ? 4 : (TN >= 4 ? 1 : 2);        // k-tiles per prefetch group
+    static constexpr int U = kCap >= kWant ? kWant : (kCap >= 2 ? 2 : 1);
     static constexpr int KC = WK * U;
+    // weight groups (U k-tiles x TN tiles) a wavefront keeps in flight (deeper was measured no faster)
+    static constexpr int D = (16 / (U * TN)) >= 2 ? 2 : 1;
     // tiles summed per round of the cross-wavefront reduction (<= 64 KiB of LDS per round)
     static constexpr int kRedTiles = (64 / (WK * WN)) >= 1 ? (64 / (WK * WN)) : 1;
 };
@@ -77,6 +77,13 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_f
     return *s_flag != 0;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load of the wavefront (vmcnt(0)), which would drain the weight prefetch queue at each chunk; here only the
+// LDS counter is drained, the weight loads stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int KT, const float *v) {
     uint16_t hi[4], lo[4];
 #pragma unroll
@@ -90,8 +97,8 @@ __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int
 
 template <int TM, int TN, int WN, int WK, int EPI>
 __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
-    using S = Shape<TM, WN, WK>;
-    constexpr int U = S::U, KC = S::KC, kWaves = S::kWaves;
+    using S = Shape<TM, TN, WN, WK>;
+    constexpr int U = S::U, KC = S::KC, D = S::D, kWaves = S::kWaves;
     constexpr int FR = KC * TM * 2;                       // 1 KiB activation fragments per chunk
     constexpr int PER = (FR + kWaves - 1) / kWaves;       // fragments each wavefront copies
     constexpr int XS_BYTES = FR * 1024;
@@ -115,44 +122,76 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const bf16x8 *wbase = reinterpret_cast<const bf16x8 *>(a.Wp) + ((size_t)(active ? nt0 : 0) * KT) * 64 + lane;
+    const bf16x8 *wbase = reinterpret_cast<const bf16x8 *>(a.Wp) + lane;
+    const int nt_last = a.NT - 1;                        // a ragged last group re-reads the last tile (never stored)
     const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(a.Xp);
+    // The k loop is straight-line code (no data-dependent branches, clamped addresses), so that the compiler
+    // keeps the prefetched registers live across iterations without copies and never has to wait for the
+    // youngest loads: a ragged tail is handled by feeding ZERO activation fragments for k-tiles >= k1.
     bf16x8 xr[PER];
     auto load_x = [&](int kc0) {                          // chunk at k-tile kc0 -> registers
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int f = w + i * kWaves;                 // fragment (k, tm, hi|lo) of the chunk
-            if (f < FR) {
-                const int k = f / (TM * 2), r = f - k * (TM * 2);
-                xr[i] = xp[(((size_t)(r >> 1) * KT + min(kc0 + k, KT - 1)) * 2 + (r & 1)) * 64 + lane];
-            }
+            const int f = min(w + i * kWaves, FR - 1);    // fragment (k, tm, hi|lo) of the chunk
+            const int k = f / (TM * 2), r = f - k * (TM * 2);
+            xr[i] = xp[(((size_t)(r >> 1) * KT + min(kc0 + k, KT - 1)) * 2 + (r & 1)) * 64 + lane];
         }
     };
-    auto store_x = [&]() {
+    auto store_x = [&](int kc0) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int f = w + i * kWaves;
-            if (f < FR) {
+            if (f < FR) {                                  // compile-time for all but the last i
                 const int k = f / (TM * 2), r = f - k * (TM * 2);
-                xs[k][r >> 1][r & 1][lane] = xr[i];
+                bf16x8 v = xr[i];
+                if (kc0 + k >= k1) v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+                xs[k][r >> 1][r & 1][lane] = v;
             }
         }
     };
-    bf16x8 a_nxt[U][TN];
-    auto load_a = [&](int k) {                            // this wavefront's U k-tiles of the chunk at k
+    bf16x8 ring[D][U][TN];                                // weight fragments in flight: D chunks ahead
+    auto load_a = [&](bf16x8 (&dst)[U][TN], int k) {      // this wavefront's U k-tiles of the chunk at k
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-                a_nxt[u][tn] = __builtin_nontemporal_load(wbase + ((size_t)tn * KT + min(k + wk * U + u, KT - 1)) * 64);
+                dst[u][tn] = __builtin_nontemporal_load(
+                    wbase + ((size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1)) * 64);
     };
-    if (k0 < k1) {
-        load_x(k0);
-        if (active) load_a(k0);
+    load_x(k0);
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd) load_a(ring[dd], k0 + dd * KC);
+    const int n_outer = (k1 - k0 + D * KC - 1) / (D * KC);
+    for (int it = 0; it < n_outer; ++it) {
+#pragma unroll
+        for (int dd = 0; dd < D; ++dd) {
+            const int kc = k0 + (it * D + dd) * KC;
+            lds_barrier();                                // the previous chunk is no longer read
+            store_x(kc);
+            lds_barrier();
+            load_x(kc + KC);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                bf16x8 bh[TM], bl[TM];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    bh[tm] = xs[wk * U + u][tm][0][lane];
+                    bl[tm] = xs[wk * U + u][tm][1][lane];
+                }
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
+                    }
+            }
+            load_a(ring[dd], kc + D * KC);                // refill this slot D chunks ahead (clamped)
+        }
     }
     if (EPI != EPI_RESID && a.ssq_in != nullptr) {
-        // 1/rms of the input rows from the producer's per-tile sums of squares (visible to the whole
-        // workgroup after the barriers of the chunk loop)
+        // 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order
+        // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
         for (int row = w; row < a.M; row += kWaves) {
             float ssum = 0.f;
             for (int t = lane; t < a.NT_in; t += 64) ssum += a.ssq_in[(size_t)row * a.NT_in + t];
@@ -160,34 +199,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
         }
     }
-    for (int kc = k0; kc < k1; kc += KC) {
-        __syncthreads();
-        store_x();
-        __syncthreads();
-        if (kc + KC < k1) load_x(kc + KC);
-        if (active) {
-            bf16x8 af[U][TN];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) af[u][tn] = a_nxt[u][tn];
-            if (kc + KC < k1) load_a(kc + KC);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (kc + wk * U + u < k1) {
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-                        const bf16x8 bh = xs[wk * U + u][tm][0][lane], bl = xs[wk * U + u][tm][1][lane];
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][tn], bl, acc[tn][tm], 0, 0, 0);
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][tn], bh, acc[tn][tm], 0, 0, 0);
-                        }
-                    }
-                }
-            }
-        }
-    }
+    __syncthreads();                                      // s_rinv visible; xs no longer read
 
     if (WK > 1) {
         // sum the WK partial tiles of each n-tile group through LDS (fixed order), RT tiles per round;
@@ -227,7 +239,8 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                 if (row >= a.M) continue;
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
+                    if (nt0 + tn <= nt_last)
+                        store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
             }
         }
         if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
@@ -238,7 +251,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
                     f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    if (row < a.M) {
+                    if (row < a.M && nt0 + tn <= nt_last) {
                         const float *pp = a.part + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g;
                         const size_t ps = (size_t)a.M * ld_part;
                         int sk = 0;
@@ -268,14 +281,16 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             if (valid) {
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + (nt0 + tn) * 16 + 4 * g) = acc[tn][tm] * sc;
+                    if (nt0 + tn <= nt_last)
+                        *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + (nt0 + tn) * 16 + 4 * g) = acc[tn][tm] * sc;
             }
         } else if (EPI == EPI_RESID) {
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 const int col = (nt0 + tn) * 16 + 4 * g;
                 float ss = 0.f;
-                if (valid) {
+                const bool tile_ok = nt0 + tn <= nt_last;
+                if (valid && tile_ok) {
                     float *xp2 = a.x + (size_t)row * ld_part + col;
                     f32x4 xv = *reinterpret_cast<f32x4 *>(xp2) + acc[tn][tm];
                     *reinterpret_cast<f32x4 *>(xp2) = xv;
@@ -289,18 +304,21 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                 }
                 ss += __shfl_xor(ss, 16);
                 ss += __shfl_xor(ss, 32);
-                if (valid && g == 0) a.ssq[(size_t)row * a.NT + nt0 + tn] = ss;
+                if (valid && tile_ok && g == 0) a.ssq[(size_t)row * a.NT + nt0 + tn] = ss;
             }
-        } else {   // EPI_SWIGLU: tile nt0 = gate, nt0 + 1 = up of feature block nt0 / 2
+        } else {   // EPI_SWIGLU: tiles (nt0 + 2p, nt0 + 2p + 1) = (gate, up) of feature block nt0 / 2 + p
             if (valid) {
                 const float sc = s_rinv[row];
-                float h[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float gt = acc[0][tm][i] * sc, up = acc[TN - 1][tm][i] * sc;
-                    h[i] = gt / (1.0f + expf(-gt)) * up;
+                for (int p = 0; p < TN / 2; ++p) {
+                    float h[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float gt = acc[2 * p][tm][i] * sc, up = acc[(2 * p + 1) % TN][tm][i] * sc;
+                        h[i] = gt / (1.0f + expf(-gt)) * up;
+                    }
+                    store_act4(a.act_out, row, ((nt0 >> 1) + p) * 16 + 4 * g, a.KT_out, h);
                 }
-                store_act4(a.act_out, row, (nt0 >> 1) * 16 + 4 * g, a.KT_out, h);
             }
         }
     }
@@ -322,58 +340,76 @@ __global__ void pack_weight_kernel(const uint16_t *__restrict__ W, u32x4 *__rest
     dst[(((size_t)(dst_tile0 + nt * dst_tile_step)) * KT + kt) * 64 + lane] = v;
 }
 
-template <int TM, int WN, int WK>
+template <int TM, int TN, int WN, int WK>
 int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
-    if constexpr (!Shape<TM, WN, WK>::kValid) {
+    using S = Shape<TM, TN, WN, WK>;
+    if constexpr (!S::kValid) {
         set_error("gemm: workgroup shape %dx%d does not fit %d row tiles", WN, WK, TM);
         return SEED_E_CAPACITY;
     } else {
-        return launch_valid<TM, WN, WK>(a, epi, st);
+        constexpr int KC = S::KC;
+        GemmArgs b = a;
+        b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
+        b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
+        dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
+        if (epi == EPI_SWIGLU) {
+            if constexpr (TN >= 2) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
+            else { set_error("gemm: SwiGLU epilogue needs paired tiles"); return SEED_E_INVALID_ARG; }
+        } else if (epi == EPI_RESID) {
+            hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID>), grid, block, 0, st, b);
+        } else {
+            hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE>), grid, block, 0, st, b);
+        }
+        return hip_fail(hipGetLastError(), "gemm launch");
     }
 }
 
-template <int TM, int WN, int WK>
-int launch_valid(const GemmArgs &a, int epi, hipStream_t st) {
-    constexpr int KC = Shape<TM, WN, WK>::KC;
-    GemmArgs b = a;
-    b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
-    b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
-    const int tn = epi == EPI_SWIGLU ? 2 : 1;
-    dim3 grid((a.NT + WN * tn - 1) / (WN * tn), b.SK), block(WN * WK * 64);
-    switch (epi) {
-        case EPI_STORE: hipLaunchKernelGGL((gemm_kernel<TM, 1, WN, WK, EPI_STORE>), grid, block, 0, st, b); break;
-        case EPI_RESID: hipLaunchKernelGGL((gemm_kernel<TM, 1, WN, WK, EPI_RESID>), grid, block, 0, st, b); break;
-        default: hipLaunchKernelGGL((gemm_kernel<TM, 2, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b); break;
-    }
-    return hip_fail(hipGetLastError(), "gemm launch");
-}
-
+// One or two row tiles (<= 32 rows): one or two n-tiles per wavefront, all workgroup shapes.
 template <int TM>
-int launch_tm(const GemmArgs &a, int epi, int wn, int wk, hipStream_t st) {
-    if (wn == 8 && wk == 1) return launch_shape<TM, 8, 1>(a, epi, st);
-    if (wn == 4 && wk == 2) return launch_shape<TM, 4, 2>(a, epi, st);
-    if (wn == 2 && wk == 4) return launch_shape<TM, 2, 4>(a, epi, st);
-    if (wn == 1 && wk == 8) return launch_shape<TM, 1, 8>(a, epi, st);
-    if (wn == 4 && wk == 4) return launch_shape<TM, 4, 4>(a, epi, st);
-    if (wn == 2 && wk == 8) return launch_shape<TM, 2, 8>(a, epi, st);
-    if (wn == 1 && wk == 16) return launch_shape<TM, 1, 16>(a, epi, st);
+int launch_small(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t st) {
+#define SEEDV_SHAPE(WNv, WKv)                                                             \
+    if (wn == WNv && wk == WKv)                                                           \
+        return tn == 2 ? launch_shape<TM, 2, WNv, WKv>(a, epi, st) : launch_shape<TM, 1, WNv, WKv>(a, epi, st);
+    SEEDV_SHAPE(8, 1) SEEDV_SHAPE(4, 2) SEEDV_SHAPE(2, 4) SEEDV_SHAPE(1, 8) SEEDV_SHAPE(4, 4) SEEDV_SHAPE(1, 16)
+#undef SEEDV_SHAPE
     set_error("gemm: unsupported workgroup shape %dx%d", wn, wk);
+    return SEED_E_INVALID_ARG;
+}
+
+// Three to eight row tiles: two n-tiles per wavefront (every activation fragment read from LDS feeds two
+// MFMAs), fewer shapes.  (Four tiles per wavefront were measured slower at 40 and 96 rows.)
+template <int TM>
+int launch_large(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t st) {
+    if (tn != 2) {
+        set_error("gemm: %d row tiles run with two n-tiles per wavefront", TM);
+        return SEED_E_INVALID_ARG;
+    }
+#define SEEDV_SHAPE(WNv, WKv)                                                             \
+    if (wn == WNv && wk == WKv) return launch_shape<TM, 2, WNv, WKv>(a, epi, st);
+    SEEDV_SHAPE(8, 1) SEEDV_SHAPE(4, 2) SEEDV_SHAPE(2, 4)
+#undef SEEDV_SHAPE
+    set_error("gemm: unsupported workgroup shape %dx%d for %d row tiles", wn, wk, TM);
     return SEED_E_INVALID_ARG;
 }
 
 }  // namespace
 
-// Launch with an explicit workgroup shape (wn x wk wavefronts) and a.SK workgroups along K.
-int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, hipStream_t st) {
+// Launch with an explicit workgroup shape (wn x wk wavefronts, tn n-tiles per wavefront) and a.SK
+// workgroups along K.
+int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, int tn, hipStream_t st) {
+    if (epi == EPI_SWIGLU && (tn < 2 || a.NT % 2 != 0)) {
+        set_error("gemm: the SwiGLU epilogue needs paired tiles (tn=%d, NT=%d)", tn, a.NT);
+        return SEED_E_INVALID_ARG;
+    }
     switch (m_tiles) {
-        case 1: return launch_tm<1>(a, epi, wn, wk, st);
-        case 2: return launch_tm<2>(a, epi, wn, wk, st);
-        case 3: return launch_tm<3>(a, epi, wn, wk, st);
-        case 4: return launch_tm<4>(a, epi, wn, wk, st);
-        case 5: return launch_tm<5>(a, epi, wn, wk, st);
-        case 6: return launch_tm<6>(a, epi, wn, wk, st);
-        case 7: return launch_tm<7>(a, epi, wn, wk, st);
-        case 8: return launch_tm<8>(a, epi, wn, wk, st);
+        case 1: return launch_small<1>(a, epi, wn, wk, tn, st);
+        case 2: return launch_small<2>(a, epi, wn, wk, tn, st);
+        case 3: return launch_large<3>(a, epi, wn, wk, tn, st);
+        case 4: return launch_large<4>(a, epi, wn, wk, tn, st);
+        case 5: return launch_large<5>(a, epi, wn, wk, tn, st);
+        case 6: return launch_large<6>(a, epi, wn, wk, tn, st);
+        case 7: return launch_large<7>(a, epi, wn, wk, tn, st);
+        case 8: return launch_large<8>(a, epi, wn, wk, tn, st);
         default:
             set_error("gemm: unsupported m_tiles %d", m_tiles);
             return SEED_E_CAPACITY;
@@ -383,30 +419,27 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
 // Workgroup shape and split from a sweep on MI355X over the 7B / 13B projection shapes at 12, 40 and 96
 // rows: wide outputs share activation fragments across wavefronts (WN), narrow outputs split K inside the
 // workgroup (WK) and, when that still leaves CUs idle, across two or four workgroups.
-void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *sk) {
-    const int units = epi == EPI_SWIGLU ? NT / 2 : NT;     // n-tile groups a wavefront owns one of
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk) {
     *sk = 1;
-    if (m_tiles == 1) {
-        if (units >= 1536) { *wn = 4; *wk = 2; }
-        else if (units >= 600) { *wn = epi == EPI_SWIGLU ? 4 : 2; *wk = 4; }
-        else { *wn = 1; *wk = 8; *sk = 2; }
-    } else if (m_tiles <= 4) {
-        if (units >= 1536) { *wn = 8; *wk = 1; }
-        else if (units >= 600) { *wn = 4; *wk = (m_tiles <= 2 || epi != EPI_SWIGLU) ? 4 : 2; }
-        else { *wn = 4; *wk = 2; *sk = KT >= 256 ? 4 : 2; }
-    } else {
-        if (units >= 1536) { *wn = 4; *wk = 2; }
-        else if (units >= 600) { *wn = 4; *wk = epi == EPI_SWIGLU ? 2 : 4; }
+    if (m_tiles <= 2) {
+        *tn = epi == EPI_SWIGLU ? 2 : 1;
+        const int units = NT / *tn;                        // n-tile groups a wavefront owns one of
+        if (units >= 600) { *wn = 4; *wk = 2; }
         else { *wn = 2; *wk = 4; *sk = 2; }
+    } else {
+        *tn = 2;
+        if (NT >= 1300) { *wn = 4; *wk = 2; }
+        else if (NT >= 600) { *wn = 2; *wk = 4; }
+        else { *wn = 2; *wk = 4; *sk = m_tiles <= 4 ? 2 : 4; }
     }
     if (KT < 64) *sk = 1;
 }
 
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
-    int wn, wk, sk;
-    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &sk);
+    int wn, wk, tn, sk;
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk);
     if (a.SK < 1) a.SK = sk;
-    return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, st);
+    return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, st);
 }
 
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,

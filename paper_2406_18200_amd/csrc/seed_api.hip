@@ -273,12 +273,12 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.part = (float *)at(c, L.part);
         a.counters = (int *)at(c, L.counters);
         a.eps = g.rms_eps;
-        int wn, wk, sk;
-        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &sk);
+        int wn, wk, tn, sk;
+        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk);
         while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
         a.SK = sk;
-        if (sk > 1 && a.NT / wn + 2 > kMaxCounters) {
-            set_error("projection with %d column groups exceeds the counter array", a.NT / wn);
+        if (sk > 1 && a.NT / (wn * tn) + 2 > kMaxCounters) {
+            set_error("projection with %d column groups exceeds the counter array", a.NT / (wn * tn));
             return SEED_E_CAPACITY;
         }
         return profiled(c, (double)Nout * K * 2.0, [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
