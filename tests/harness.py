@@ -22,6 +22,55 @@ def check_logits(got, ref, dtype):
     return worst, float(err.max())
 
 
+class CachedWeights:
+    """Memoises a small model's tensors so repeated oracle calls do not regenerate them."""
+
+    def __init__(self, inner):
+        self.inner, self.cache = inner, {}
+
+    def _get(self, key, fn):
+        if key not in self.cache:
+            self.cache[key] = np.array(fn(), copy=True)
+        return self.cache[key]
+
+    def tok_emb(self):
+        return self._get("emb", self.inner.tok_emb)
+
+    def norm_final(self):
+        return self._get("nf", self.inner.norm_final)
+
+    def lm_head(self):
+        return self._get("lm", self.inner.lm_head)
+
+    def layer(self, l):
+        if ("layer", l) not in self.cache:
+            self.cache[("layer", l)] = {k: np.array(v, copy=True) for k, v in self.inner.layer(l).items()}
+        return self.cache[("layer", l)]
+
+
+def perturbed_q_autoregressive(w, W):
+    """Draft distributions that are a perturbed copy of the target's (target logits + noise, same
+    temperature), built autoregressively with the ORACLE: row j's logits depend on the drafts sampled from
+    q_<j.  Synthetic-KV protocol.  Returns q [N][gamma][V]."""
+    m, G = w.model, w.gamma
+    pending = gen.pending_tokens(w)
+    u = wl.uniform24(w.seed + 3, (w.N, G))
+    q = np.zeros((w.N, G, m.vocab), np.float32)
+    drafts = np.zeros((w.N, G), np.int32)
+    kv = [wl.synthetic_kv(w, l) for l in range(m.n_layers)]
+
+    def ctx(l):
+        k_s, v_s, k_p, v_p = kv[l]
+        return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in range(w.N)]
+    for j in range(G):
+        rows = np.concatenate([pending[:, None], drafts[:, :j]], axis=1)
+        logits = oracle.verify_forward(m, W, rows, ctx, [w.S + w.R] * w.N)[:, j]
+        for b in range(w.N):
+            q[b, j] = wl.perturbed_draft_q(w, logits[b].astype(np.float32), b, j)
+        drafts[:, j] = wl.draw_tokens(q[:, j], u[:, j])
+    return q
+
+
 def build_inputs(w, bonus=False, q_override=None):
     """Host-side inputs of one verify step (everything except the model and the KV context)."""
     G = w.gamma
@@ -40,10 +89,10 @@ class Case:
     """Runs oracle and GPU on a workload.  branches = subset of branch indices the oracle evaluates (all by
     default); the GPU always runs the full step in its benchmark launch configuration."""
 
-    def __init__(self, w, bonus=False, greedy=False, branches=None, device="cuda:0", log=print):
+    def __init__(self, w, bonus=False, greedy=False, branches=None, device="cuda:0", log=print, q_override=None):
         self.w, self.bonus, self.greedy, self.device, self.log = w, bonus, greedy, device, log
         self.branches = list(range(w.N)) if branches is None else list(branches)
-        self.inp = build_inputs(w, bonus)
+        self.inp = build_inputs(w, bonus, q_override)
 
     # ---------------------------------------------------------------- oracle side
     def run_oracle(self):

@@ -15,3 +15,11 @@ def test_c3_7b_full_step_all_rows():
 
 def test_c4_7b_wide_sampled_branches():
     Case(wl.get_workload("c4"), branches=[0, 7, 15]).run_oracle().run_gpu().compare()
+
+
+def test_c5_13b_sampled_branches_random_q():
+    """13B shapes, N=8 x gamma=5 over a 4096-token shared prefix, full 40 layers.  The draft distributions
+    here are the random-logit kind: building the perturbed-target kind needs gamma sequential oracle passes
+    over 25.7 GB of weights; that recipe is exercised at two layers in test_gpu_verify.py."""
+    w = wl.get_workload("c5").scaled(q_kind="random", q_temp=1.0)
+    Case(w, branches=[0, 5]).run_oracle().run_gpu().compare()
