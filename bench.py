@@ -99,6 +99,9 @@ def main():
                     "the reported number is then NOT the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--greedy", action="store_true")
+    ap.add_argument("--copy-probe-mb", type=int, default=0, help="also launch a plain device-to-device copy "
+                    "of this many MiB (three times) before the timed region: the known-size kernel against "
+                    "which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -173,6 +176,13 @@ def main():
         plen.copy_(plen0)                    # every step sees the same context lengths
         return ctx.step(d_row, w.S, plen, flags=flags, accept=acc)
 
+    if args.copy_probe_mb:
+        src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         outs = one_step()
     torch.cuda.synchronize()

@@ -88,26 +88,36 @@ __device__ int block_argmax(const float *row, int V, Shared &sm) {
     return ri;
 }
 
+// exp((x - mx) / temperature) with the hardware exp2: a few instructions instead of ~70 for the IEEE
+// division + libm exp (the kernel runs on as few CUs as there are branches, so it is ALU-bound); relative
+// error ~1e-6, far inside the tolerance of the LOGITS mode.  Every use of p goes through the same function,
+// so the accept test and the residual draw see the same bits.
+__device__ __forceinline__ float exp_scaled(float x, float mx, float inv_temp) {
+    return __builtin_amdgcn_exp2f((x - mx) * inv_temp * 1.4426950408889634f);
+}
+
 // A row of target probabilities, either given or defined by softmax(logits / temperature).
 struct TargetRow {
     const float *src;
     int is_logits;
-    float mx, sum, temp;
+    float mx, inv_sum, inv_temp;
     __device__ __forceinline__ float p(int v) const {
         if (!is_logits) return src[v];
-        return __fdiv_rn(expf(__fdiv_rn(src[v] - mx, temp)), sum);
+        return exp_scaled(src[v], mx, inv_temp) * inv_sum;
     }
 };
 
 __device__ TargetRow make_row(const float *src, int is_logits, float temp, int V, Shared &sm) {
-    TargetRow r{src, is_logits, 0.f, 1.f, temp};
+    TargetRow r{src, is_logits, 0.f, 1.f, 1.f / temp};
     if (!is_logits) return r;
     float m = -INFINITY;
+#pragma unroll 8
     for (int v = threadIdx.x; v < V; v += kBlock) m = fmaxf(m, src[v]);
     r.mx = block_max(m, sm);
     float s = 0.f;
-    for (int v = threadIdx.x; v < V; v += kBlock) s += expf(__fdiv_rn(src[v] - r.mx, temp));
-    r.sum = block_sum(s, sm);
+#pragma unroll 8
+    for (int v = threadIdx.x; v < V; v += kBlock) s += exp_scaled(src[v], r.mx, r.inv_temp);
+    r.inv_sum = 1.0f / block_sum(s, sm);
     return r;
 }
 
@@ -136,6 +146,7 @@ __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, 
     const int base = wave * per;
     const int end = min(V, base + per);
     unsigned long long local = 0;
+#pragma unroll 8
     for (int v = base + lane; v < end; v += 64) local += weight_fixed<RESIDUAL>(row, q, v);
     local = wave_sum_u64(local);
     __syncthreads();
@@ -209,6 +220,7 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         float mv = -INFINITY;
         int mi = 0x7fffffff;
         if (has_row && (is_logits || a.greedy)) {
+#pragma unroll 8
             for (int v = sub * 64 + lane; v < V; v += wpr * 64) {
                 const float x = src[v];
                 if (x > mv) { mv = x; mi = v; }
@@ -235,7 +247,9 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         // pass 2: sum of exp((x - max) / temperature)
         float sv = 0.f;
         if (has_row && is_logits && !a.greedy) {
-            for (int v = sub * 64 + lane; v < V; v += wpr * 64) sv += expf(__fdiv_rn(src[v] - mv, a.temperature));
+            const float inv_t = 1.0f / a.temperature;
+#pragma unroll 8
+            for (int v = sub * 64 + lane; v < V; v += wpr * 64) sv += exp_scaled(src[v], mv, inv_t);
             sv = wave_sum(sv);
         }
         if (lane == 0) ri.wm[wave] = sv;
@@ -245,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
             for (int i = 1; i < wpr; ++i) tot += ri.wm[r * wpr + i];       // fixed order
             const int j = r0 + r;
             ri.mx[r] = mv;
-            ri.sum[r] = (is_logits && !a.greedy) ? tot : 1.f;
+            ri.sum[r] = (is_logits && !a.greedy) ? 1.0f / tot : 1.f;          // stored as 1 / sum
             ri.best[r] = mi;
             int ok = 0;
             if (j < G) {
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
                     ok = (x == mi);
                     if (a.p_tok != nullptr) a.p_tok[b * G + j] = 0.f;
                 } else {
-                    const TargetRow row{src, is_logits, mv, ri.sum[r], a.temperature};
+                    const TargetRow row{src, is_logits, mv, ri.sum[r], 1.0f / a.temperature};
                     const float pj = row.p(x);
                     if (a.p_tok != nullptr) a.p_tok[b * G + j] = pj;
                     ok = __fmul_rn(a.u_acc[b * G + j], a.q[((size_t)b * G + j) * V + x]) < pj;
@@ -279,7 +293,7 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
             if (a.greedy) {
                 new_tok = ri.best[r2];
             } else {
-                const TargetRow row{rsrc, is_logits, ri.mx[r2], ri.sum[r2], a.temperature};
+                const TargetRow row{rsrc, is_logits, ri.mx[r2], ri.sum[r2], 1.0f / a.temperature};
                 if (rej_row >= 0) {
                     const float *q = a.q + ((size_t)b * G + j) * V;
                     new_tok = draw_fixed<1>(row, q, a.u_res[b], V, sm);
