@@ -38,14 +38,18 @@ namespace {
 template <int TM, int TN, int WN, int WK>
 struct Shape {
     static constexpr int kWaves = WN * WK;
-    // LDS budget for the staged activation chunk: 32 KiB for one or two row tiles, 64 KiB above
-    static constexpr int kCap = (TM <= 2 ? 16 : 32) / (WK * TM);        // k-tiles per wavefront that fit
-    static constexpr bool kValid = kCap >= 1;
-    static constexpr int kWant = TM <= 2 ? 4 : (TN >= 4 ? 1 : 2);        // k-tiles per prefetch group
-    static constexpr int U = kCap >= kWant ? kWant : (kCap >= 2 ? 2 : 1);
-    static constexpr int KC = WK * U;
-    // weight groups (U k-tiles x TN tiles) a wavefront keeps in flight (deeper was measured no faster)
-    static constexpr int D = (16 / (U * TN)) >= 2 ? 2 : 1;
+    // k-tiles of staged activations (2 KiB per k-tile and row tile) that fit the LDS budget: 64 KiB, 96 KiB
+    // for five row tiles and more (at most a workgroup or two per CU are resident anyway)
+    static constexpr int kBudget = (TM <= 4 ? 32 : 48) / TM;
+    static constexpr int kWant = TM <= 2 ? 4 : (TM <= 4 ? 2 : 1);        // k-tiles per wavefront and group
+    static constexpr int U = (WK * kWant <= kBudget) ? kWant : ((WK * 2 <= kBudget && kWant >= 2) ? 2 : 1);
+    static constexpr int KC = WK * U;                                    // k-tiles per weight group
+    static constexpr bool kValid = KC <= kBudget;
+    // weight groups (U k-tiles x TN tiles per wavefront) kept in flight (deeper was measured no faster)
+    static constexpr int D = (2 * KC <= kBudget && U * TN <= 8) ? 2 : 1;
+    // weight groups per staged activation chunk (a multiple of D): fewer workgroup barriers per k-tile
+    static constexpr int kFit = kBudget / KC;
+    static constexpr int XG = kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1));
     // tiles summed per round of the cross-wavefront reduction (<= 64 KiB of LDS per round)
     static constexpr int kRedTiles = (64 / (WK * WN)) >= 1 ? (64 / (WK * WN)) : 1;
 };
@@ -98,8 +102,9 @@ __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int
 template <int TM, int TN, int WN, int WK, int EPI>
 __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     using S = Shape<TM, TN, WN, WK>;
-    constexpr int U = S::U, KC = S::KC, D = S::D, kWaves = S::kWaves;
-    constexpr int FR = KC * TM * 2;                       // 1 KiB activation fragments per chunk
+    constexpr int U = S::U, KC = S::KC, D = S::D, XG = S::XG, kWaves = S::kWaves;
+    constexpr int XKT = XG * KC;                          // k-tiles per staged activation chunk
+    constexpr int FR = XKT * TM * 2;                      // 1 KiB activation fragments per chunk
     constexpr int PER = (FR + kWaves - 1) / kWaves;       // fragments each wavefront copies
     constexpr int XS_BYTES = FR * 1024;
     constexpr int RT = S::kRedTiles < TN * TM ? S::kRedTiles : TN * TM;   // tiles per reduction round
@@ -107,7 +112,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
     __shared__ int s_last;
     __shared__ float s_rinv[128];
-    bf16x8(*xs)[TM][2][64] = reinterpret_cast<bf16x8(*)[TM][2][64]>(smem);                 // [KC][TM][2][64]
+    bf16x8(*xs)[TM][2][64] = reinterpret_cast<bf16x8(*)[TM][2][64]>(smem);                 // [XKT][TM][2][64]
     f32x4(*red)[WN][RT][64] = reinterpret_cast<f32x4(*)[WN][RT][64]>(smem);                 // [WK][WN][RT][64]
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wn = w % WN, wk = w / WN;
@@ -161,22 +166,25 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     load_x(k0);
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) load_a(ring[dd], k0 + dd * KC);
-    const int n_outer = (k1 - k0 + D * KC - 1) / (D * KC);
+    const int n_outer = (k1 - k0 + XKT - 1) / XKT;
     for (int it = 0; it < n_outer; ++it) {
+        const int kx = k0 + it * XKT;
+        lds_barrier();                                    // the previous chunk is no longer read
+        store_x(kx);
+        lds_barrier();
+        load_x(kx + XKT);
 #pragma unroll
-        for (int dd = 0; dd < D; ++dd) {
-            const int kc = k0 + (it * D + dd) * KC;
-            lds_barrier();                                // the previous chunk is no longer read
-            store_x(kc);
-            lds_barrier();
-            load_x(kc + KC);
+        for (int gq = 0; gq < XG; ++gq) {
+            constexpr int kRing = D;                       // XG is a multiple of D: slot = gq % D
+            const int dd = gq % kRing;
+            const int kc = kx + gq * KC;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 bf16x8 bh[TM], bl[TM];
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) {
-                    bh[tm] = xs[wk * U + u][tm][0][lane];
-                    bl[tm] = xs[wk * U + u][tm][1][lane];
+                    bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
+                    bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
                 }
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
@@ -186,7 +194,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                         acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
                     }
             }
-            load_a(ring[dd], kc + D * KC);                // refill this slot D chunks ahead (clamped)
+            load_a(ring[dd], kc + D * KC);                // refill this slot D groups ahead (clamped)
         }
     }
     if (EPI != EPI_RESID && a.ssq_in != nullptr) {
@@ -347,7 +355,7 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         set_error("gemm: workgroup shape %dx%d does not fit %d row tiles", WN, WK, TM);
         return SEED_E_CAPACITY;
     } else {
-        constexpr int KC = S::KC;
+        constexpr int KC = S::XG * S::KC;                  // splits cover whole staged chunks
         GemmArgs b = a;
         b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
         b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
