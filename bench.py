@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per projection launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy
 # kernel of known size); see profiles/.  None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"c3": 107.2e6}     # profiles/gemm_kernel_c3.md: 2 x 51,707 KiB fetched + 1,265 KiB written
 
 
 def algorithmic_bytes(w):
