@@ -118,8 +118,9 @@ typedef struct {
 } seed_accept_args;
 
 /*
- * One target forward over N x T rows (paper Section 3.1: the drafts "along with c are passed to M_t to
- * obtain their output distribution ... in parallel"), optionally followed by accept / resample.
+ * One target forward over N x T rows (paper Section 3.1: the context and the draft tokens go through the
+ * target model together, which yields the distribution at every draft position in one pass), optionally
+ * followed by accept / resample.
  *   row_tok[b][0] is the branch's pending token (validated, KV not yet cached); row_tok[b][j], j >= 1,
  *   is draft token j.  Row j sits at position shared_len + private_len[b] + j and attends to the shared
  *   prefix (read once for all branches), to the branch's private context and causally to rows 0..j of

@@ -1,7 +1,7 @@
 """CPU oracle for the batched speculative-decoding verify step -- TEST INFRASTRUCTURE ONLY.
 
 A plain, slow, float64 numpy statement of what the hot path computes: the decoder forward pass over
-the draft rows of every branch (Section 3.1: the target model scores the draft tokens "in parallel")
+the draft rows of every branch (Section 3.1: the target model scores all draft positions of a sequence in one pass)
 and the speculative-sampling accept / resample rule (Section 3.1; Algorithm 1, verification process).
 It shares no code with the HIP library and is imported only by the tests, by the smoke check and by
 the benchmark's CPU-baseline leg.  The product path never routes through it.

@@ -4,9 +4,9 @@ Architecture (the LLaMA family the paper evaluates, Section 4.1 "Models"): pre-n
 attention with rotary position embedding (rotate-half pairing (i, i + dh/2), base theta), scale
 1/sqrt(dh), causal mask, SwiGLU feed-forward, final RMSNorm, untied LM head, no biases.
 
-The verify phase (Section 3.1; Algorithm 1 "E(M_t, c_i, X_i[1:k])") asks for the target model's
+The verify phase (Section 3.1; the verify call E of Algorithm 1) asks for the target model's
 next-token distribution at each draft position of each branch, given that branch's context.  Branches
-do not interact (Section 3, "distinct branches ... do not interfere with each other"), so the oracle
+do not interact (Section 3: each generation runs in its own branch, independent of the others), so the oracle
 simply runs an ordinary causal forward per branch over the new rows against that branch's context KV.
 """
 import numpy as np

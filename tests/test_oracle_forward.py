@@ -97,7 +97,7 @@ def test_verify_rows_equal_separate_plain_forwards(tiny):
 
 def test_branches_do_not_interfere(tiny):
     """Permuting branches permutes the outputs bit for bit; changing one branch's rows leaves the
-    others bit-identical (Section 3: branches "do not interfere with each other")."""
+    others bit-identical (Section 3: branches are independent of each other)."""
     w, W = tiny
     m = w.model
     rng = np.random.default_rng(11)
