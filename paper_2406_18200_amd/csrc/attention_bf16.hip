@@ -86,7 +86,8 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 
     const int krow = 8 * (col >> 2) + (col & 3);   // key (within the chunk) of A-operand row `col`, tile 0
-    for (int c = kbeg; c < kend; c += 32) {
+    const int wv = threadIdx.x >> 6;                      // the 4 wavefronts of the workgroup interleave chunks
+    for (int c = kbeg + 32 * wv; c < kend; c += 128) {
         f32x4 s[2][2];                              // [key tile][row tile]
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
@@ -158,20 +159,58 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             }
         }
     }
+    // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
+    // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
+    __shared__ float sm_m[4][32], sm_l[4][32];
+    __shared__ float sm_o[4][32][DH + 4];
+    float scale[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         float l = l_run[t];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        const int r = row0 + t * 16 + col;
-        if (r >= rows_hi) continue;
-        float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(op + dt * 16 + 4 * g) = o[dt][t];
         if (g == 0) {
+            sm_m[wv][t * 16 + col] = m_run[t];
+            sm_l[wv][t * 16 + col] = l;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int rr = t * 16 + col;
+        float mstar = sm_m[0][rr];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) mstar = fmaxf(mstar, sm_m[i][rr]);
+        scale[t] = (m_run[t] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[t] - mstar);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const f32x4 v = o[dt][t] * scale[t];
+            *reinterpret_cast<f32x4 *>(&sm_o[wv][rr][dt * 16 + 4 * g]) = v;
+        }
+    }
+    __syncthreads();
+    // wavefront wv finishes rows wv*8 .. wv*8+7: lanes own DH/64 consecutive dims
+    constexpr int PERD = DH / 64;
+    for (int rr = wv * 8; rr < wv * 8 + 8; ++rr) {
+        const int r = row0 + rr;
+        if (r >= rows_hi) continue;
+        float mstar = sm_m[0][rr];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) mstar = fmaxf(mstar, sm_m[i][rr]);
+        float L = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            L += (sm_m[i][rr] == -INFINITY) ? 0.f : sm_l[i][rr] * __builtin_amdgcn_exp2f(sm_m[i][rr] - mstar);
+        float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PERD;
+#pragma unroll
+        for (int i = 0; i < PERD; ++i) {
+            const int d = lane * PERD + i;
+            op[i] = ((sm_o[0][rr][d] + sm_o[1][rr][d]) + sm_o[2][rr][d]) + sm_o[3][rr][d];
+        }
+        if (lane == 0) {
             float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
-            mp[0] = m_run[t];
-            mp[1] = l;
+            mp[0] = mstar;
+            mp[1] = L;
         }
     }
 }
@@ -222,7 +261,9 @@ __device__ void inflight_task(const AttnParams &P, int itask) {
 
 template <int DH>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
-    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
+    // then four in-flight (row, head) wavefront tasks per workgroup
+    const int task = blockIdx.x;
     const int n_shared = P.H * P.n_groups * P.ks_shared;
     if (task < n_shared) {
         const int ks = task % P.ks_shared;
@@ -238,9 +279,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
         return;
     }
     const int ptask = task - n_shared;
-    const int n_priv = P.N * P.H * P.groups_priv * P.ks_priv;
+    const int n_priv = P.prefill_shared ? 0 : P.N * P.H * P.groups_priv * P.ks_priv;
     if (ptask >= n_priv) {
-        if (!P.prefill_shared) inflight_task<DH>(P, ptask - n_priv);
+        if (!P.prefill_shared) inflight_task<DH>(P, (ptask - n_priv) * 4 + (threadIdx.x >> 6));
         return;
     }
     const int ks = ptask % P.ks_priv;
@@ -308,21 +349,23 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
 // Number of partial slots per (row, head) for a given configuration; also fills the split parameters.
 void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv) {
-    // aim for >= ~2048 wavefront tasks, at least 64 keys per task, ranges of a multiple of 32 keys
+    // aim for ~512 workgroups of four wavefronts; a key range is a multiple of 128 keys (one 32-key chunk per
+    // wavefront and round), at least 128 keys
     const int n_groups = (Mq + 31) / 32;
     const int base_tasks = H * n_groups;
-    int want = (2048 + base_tasks - 1) / base_tasks;
-    int chunks = (total_shared_keys + 31) / 32;
-    if (chunks < 1) chunks = 1;
-    int ks = want;
-    if (ks > (chunks + 1) / 2) ks = (chunks + 1) / 2;
+    const int want = (512 + base_tasks - 1) / base_tasks;
+    int rounds = (total_shared_keys + 127) / 128;      // 128-key rounds in the shared segment
+    if (rounds < 1) rounds = 1;
+    int ks = want < rounds ? want : rounds;
     if (ks < 1) ks = 1;
-    if (ks > 64) ks = 64;
-    int per = ((chunks + ks - 1) / ks) * 32;
-    ks = (chunks * 32 + per - 1) / per;
+    if (ks > 32) ks = 32;
+    const int per = ((rounds + ks - 1) / ks) * 128;
+    ks = (rounds * 128 + per - 1) / per;
     *ks_shared = ks;
     *keys_per_range = per;
     *ks_priv = (prefill_shared || cap_priv_keys <= 0) ? 0 : (cap_priv_keys + per - 1) / per;
+    (void)N;
+    (void)T;
 }
 
 int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared, const void *vt_shared, const void *k_priv,
@@ -351,14 +394,14 @@ int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared
     P.ks_priv = ks_priv;
     P.groups_priv = (T + 31) / 32;
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-    const int tasks = H * P.n_groups * ks_shared + (prefill_shared ? 0 : N * H * P.groups_priv * ks_priv + M * H);
+    const int blocks = H * P.n_groups * ks_shared + (prefill_shared ? 0 : N * H * P.groups_priv * ks_priv + (M * H + 3) / 4);
     const int n_total = ks_shared + ks_priv + 1;      // + the in-flight slot
     if (dh == 128) {
-        hipLaunchKernelGGL(attn_partial_kernel<128>, dim3((tasks + 3) / 4), dim3(256), 0, st, P);
+        hipLaunchKernelGGL(attn_partial_kernel<128>, dim3(blocks), dim3(256), 0, st, P);
         hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((Mp * H + 3) / 4), dim3(256), 0, st, o_part, ml_part,
                            (uint16_t *)act, M, Mq, Mp, H, ks_shared, n_total, prefill_shared);
     } else if (dh == 64) {
-        hipLaunchKernelGGL(attn_partial_kernel<64>, dim3((tasks + 3) / 4), dim3(256), 0, st, P);
+        hipLaunchKernelGGL(attn_partial_kernel<64>, dim3(blocks), dim3(256), 0, st, P);
         hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((Mp * H + 3) / 4), dim3(256), 0, st, o_part, ml_part,
                            (uint16_t *)act, M, Mq, Mp, H, ks_shared, n_total, prefill_shared);
     } else {
