@@ -38,18 +38,22 @@ namespace {
 template <int TM, int TN, int WN, int WK>
 struct Shape {
     static constexpr int kWaves = WN * WK;
-    // k-tiles of staged activations (2 KiB per k-tile and row tile) that fit the LDS budget: 64 KiB, 96 KiB
-    // for five row tiles and more (at most a workgroup or two per CU are resident anyway)
-    static constexpr int kBudget = (TM <= 4 ? 32 : 48) / TM;
-    static constexpr int kWant = TM <= 2 ? 4 : (TM <= 4 ? 2 : 1);        // k-tiles per wavefront and group
-    static constexpr int U = (WK * kWant <= kBudget) ? kWant : ((WK * 2 <= kBudget && kWant >= 2) ? 2 : 1);
+    // k-tiles of staged activations (2 KiB per k-tile and row tile) that fit the LDS budget: 64 KiB for one or
+    // two row tiles, 96 KiB above (at most a workgroup or two per CU are resident anyway)
+    static constexpr int kBudget = TM <= 2 ? 32 / TM : 48 / TM;
+    static constexpr int kWant = TM <= 2 ? 4 : 2;                        // k-tiles per wavefront and group
+    // largest U <= kWant that still lets two weight groups (prefetch depth 2) fit the staged chunk
+    static constexpr int U = (2 * WK * kWant <= kBudget) ? kWant : ((2 * WK * 2 <= kBudget && kWant >= 2) ? 2 : 1);
     static constexpr int KC = WK * U;                                    // k-tiles per weight group
     static constexpr bool kValid = KC <= kBudget;
-    // weight groups (U k-tiles x TN tiles per wavefront) kept in flight (deeper was measured no faster)
-    static constexpr int D = (2 * KC <= kBudget && U * TN <= 8) ? 2 : 1;
-    // weight groups per staged activation chunk (a multiple of D): fewer workgroup barriers per k-tile
+    // weight groups per staged activation chunk: fewer workgroup barriers per k-tile
     static constexpr int kFit = kBudget / KC;
     static constexpr int XG = kFit >= 8 ? 8 : (kFit >= 4 ? 4 : (kFit >= 2 ? 2 : 1));
+    // weight groups (U k-tiles x TN tiles per wavefront) kept in flight: 2 (4 was measured no faster at 12 rows
+    // and slower for the 4x2 shapes at 40 and 96).  When a chunk holds fewer groups than that, the k loop is
+    // unrolled over OU chunks so that ring slots stay compile-time indices.
+    static constexpr int D = 2;
+    static constexpr int OU = D > XG ? D / XG : 1;
     // tiles summed per round of the cross-wavefront reduction (<= 64 KiB of LDS per round)
     static constexpr int kRedTiles = (64 / (WK * WN)) >= 1 ? (64 / (WK * WN)) : 1;
 };
@@ -163,41 +167,89 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                 dst[u][tn] = __builtin_nontemporal_load(
                     wbase + ((size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1)) * 64);
     };
+    // Epilogue operands that do not depend on this launch are requested FIRST (vector loads complete in order,
+    // so they are back long before they are used and the tail of the kernel has no global load left to wait
+    // for): the residual rows and the next norm's gain (RESID, small M), the input rows' sums of squares.
+    constexpr bool kPre = TM <= 2;
+    const int g = lane >> 4, rlow = lane & 15;
+    f32x4 x_pre[TN][TM];
+    uint2 gain_pre[TN];
+    if (EPI == EPI_RESID && kPre && wk == 0) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int col = min(nt0 + tn, nt_last) * 16 + 4 * g;
+            gain_pre[tn] = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = min(tm * 16 + rlow, a.M - 1);
+                x_pre[tn][tm] = *reinterpret_cast<const f32x4 *>(a.x + (size_t)row * (a.NT * 16) + col);
+            }
+        }
+    }
+    constexpr int kSsqRows = 2;                            // rows per wavefront handled by the early path
+    constexpr int kSsqPer = 8;                             // and 64-wide slices of their sums of squares
+    const bool ssq_early = EPI != EPI_RESID && a.ssq_in != nullptr && a.M <= kSsqRows * kWaves &&
+                           a.NT_in <= 64 * kSsqPer;
+    float ssq_pre[kSsqRows][kSsqPer];
+    if (ssq_early) {
+#pragma unroll
+        for (int r = 0; r < kSsqRows; ++r)
+#pragma unroll
+            for (int i = 0; i < kSsqPer; ++i) {
+                const int row = min(w + r * kWaves, a.M - 1), t = lane + 64 * i;
+                ssq_pre[r][i] = t < a.NT_in ? a.ssq_in[(size_t)row * a.NT_in + t] : 0.f;
+            }
+    }
     load_x(k0);
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) load_a(ring[dd], k0 + dd * KC);
-    const int n_outer = (k1 - k0 + XKT - 1) / XKT;
-    for (int it = 0; it < n_outer; ++it) {
-        const int kx = k0 + it * XKT;
-        lds_barrier();                                    // the previous chunk is no longer read
-        store_x(kx);
-        lds_barrier();
-        load_x(kx + XKT);
+    if (ssq_early) {
 #pragma unroll
-        for (int gq = 0; gq < XG; ++gq) {
-            constexpr int kRing = D;                       // XG is a multiple of D: slot = gq % D
-            const int dd = gq % kRing;
-            const int kc = kx + gq * KC;
+        for (int r = 0; r < kSsqRows; ++r) {
+            float ssum = 0.f;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                bf16x8 bh[TM], bl[TM];
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-                    bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
-                    bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
-                }
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) {
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
-                    }
-            }
-            load_a(ring[dd], kc + D * KC);                // refill this slot D groups ahead (clamped)
+            for (int i = 0; i < kSsqPer; ++i) ssum += ssq_pre[r][i];       // same order as the late path
+            ssum = wave_reduce_sum(ssum);
+            const int row = w + r * kWaves;
+            if (lane == 0 && row < a.M) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
         }
     }
-    if (EPI != EPI_RESID && a.ssq_in != nullptr) {
+    constexpr int OU = S::OU;
+    const int n_outer = (k1 - k0 + OU * XKT - 1) / (OU * XKT);
+    for (int it = 0; it < n_outer; ++it) {
+#pragma unroll
+        for (int oc = 0; oc < OU; ++oc) {
+            const int kx = k0 + (it * OU + oc) * XKT;
+            lds_barrier();                                // the previous chunk is no longer read
+            store_x(kx);
+            lds_barrier();
+            load_x(kx + XKT);
+#pragma unroll
+            for (int gq = 0; gq < XG; ++gq) {
+                constexpr int kRing = D;                   // OU * XG is a multiple of D: the slot is static
+                const int dd = (oc * XG + gq) % kRing;
+                const int kc = kx + gq * KC;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    bf16x8 bh[TM], bl[TM];
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
+                        bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
+                    }
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
+                        }
+                }
+                load_a(ring[dd], kc + D * KC);            // refill this slot D groups ahead (clamped)
+            }
+        }
+    }
+    if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
         // 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order
         // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
         for (int row = w; row < a.M; row += kWaves) {
@@ -234,7 +286,6 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
 
     // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
-    const int g = lane >> 4, rlow = lane & 15;
     const int ld_part = a.NT * 16;
     if (a.SK > 1) {
         // split-K across workgroups: publish the partial, then the last workgroup of this column group sums
@@ -300,13 +351,17 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                 const bool tile_ok = nt0 + tn <= nt_last;
                 if (valid && tile_ok) {
                     float *xp2 = a.x + (size_t)row * ld_part + col;
-                    f32x4 xv = *reinterpret_cast<f32x4 *>(xp2) + acc[tn][tm];
+                    f32x4 xv = (kPre ? x_pre[tn][tm] : *reinterpret_cast<f32x4 *>(xp2)) + acc[tn][tm];
                     *reinterpret_cast<f32x4 *>(xp2) = xv;
+                    const uint2 gw = kPre ? gain_pre[tn]
+                                          : *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                    const float gv[4] = {bf2f((uint16_t)(gw.x & 0xffff)), bf2f((uint16_t)(gw.x >> 16)),
+                                         bf2f((uint16_t)(gw.y & 0xffff)), bf2f((uint16_t)(gw.y >> 16))};
                     float v[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         ss += xv[i] * xv[i];
-                        v[i] = xv[i] * bf2f(reinterpret_cast<const uint16_t *>(a.gain)[col + i]);
+                        v[i] = xv[i] * gv[i];
                     }
                     store_act4(a.act_out, row, col, a.KT_out, v);
                 }
@@ -355,7 +410,7 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         set_error("gemm: workgroup shape %dx%d does not fit %d row tiles", WN, WK, TM);
         return SEED_E_CAPACITY;
     } else {
-        constexpr int KC = S::XG * S::KC;                  // splits cover whole staged chunks
+        constexpr int KC = S::OU * S::XG * S::KC;          // splits cover whole unrolled rounds of staged chunks
         GemmArgs b = a;
         b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
         b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
