@@ -16,8 +16,15 @@
 //   O^T += V^T . P^T       A = V^T fragment (16 dims x 32 keys; V is cached transposed so this is one
 //                          16-byte load per lane), B = P^T built in registers from the S^T accumulators
 // (q and P are carried as hi/lo bf16 pairs, two MFMAs each, so that rounding them does not dominate the
-// error of the attention output) and writes an unnormalised partial (max, sum, O) per (row, head, key range); a small merge kernel
-// combines the partials by log-sum-exp and emits the bf16 activation tile of the O projection.
+// error of the attention output); the four wavefronts of a workgroup interleave the chunks of one task and
+// leave ONE unnormalised partial (max, sum, O) per (row, head, key range).  The partials of a (row, head) are
+// combined by log-sum-exp into the hi/lo bf16 activation tile of the O projection.
+//
+// Verify / decode steps run everything in ONE launch: the tasks read q, k, v straight from the fp32 output
+// of the QKV projection and apply the rotary embedding on the fly (the in-flight tasks also append the
+// rotated keys and the values to the private cache), and the workgroup that finishes last for a head
+// (a per-head arrival counter) merges that head's partials.  The shared-prefix prefill keeps the three-launch
+// form (rotary + cache append, partials, merge): its rows read the keys of their own chunk from the cache.
 //
 // The two S^T tiles of a 32-key chunk use the key order key = 8*(i/4) + (i%4) (+4 for the second tile),
 // which makes lane group g hold exactly keys 8g..8g+7 -- the B-operand layout the P.V MFMA wants.
@@ -39,19 +46,79 @@ struct AttnParams {
     const float *v_new;       // [M][H*DH] fp32: values of this step's rows
     float *o_part;            // [P][Mq][H][DH]
     float *ml_part;           // [P][Mq][H][2]
+    // single-launch form only:
+    const float *qkv;         // [M][3*H*DH] fp32: q | k | v of this step's rows, before the rotary embedding
+    const float *rope;        // [pos][DH/2][cos, sin]
+    uint16_t *k_priv_w, *vt_priv_w;   // the private cache again, for the append
+    int *counters;            // [H] arrival counters, zero on entry and left zero
+    uint16_t *act;            // merged output, fragment-packed hi/lo activation of the O projection
+    int32_t *status;
+    int Mp, n_inflight_wgs;
+    int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
     int prefill_shared;       // rows additionally see shared keys S .. S+j (their own chunk, causal)
     int cap_s, cap_p, max_private;
-    int n_groups;             // ceil(Mq / 32): query-row groups of the shared pass
+    int n_groups;             // query-row groups of the shared pass (32 rows each; 16 when M <= 16)
     int ks_shared;            // key ranges of the shared pass
     int keys_per_range;       // multiple of 32
     int ks_priv;              // key ranges of the private pass (0 in prefill)
-    int groups_priv;          // ceil(T / 32)
+    int groups_priv;          // row groups of one branch
     float scale_log2e;
 };
 
+// Position and validity of query row r in a verify / decode step: branch b = r / T continues its private
+// context, so the row sits at S + private_len[b] + j.  An out-of-range length is clamped (and flagged by the
+// in-flight task, which then drops the cache append).
+__device__ __forceinline__ int clamped_private_len(const AttnParams &P, int b) {
+    return min(max(P.private_len[b], 0), P.max_private);
+}
+
+// Query fragments (B operand, hi/lo) of row r, head h from the fp32 QKV output with the rotary embedding
+// applied: lane group g holds dims ks*32 + 8g .. +8 of every k-step; a dim below DH/2 pairs with dim + DH/2,
+// i.e. k-step ks with ks + KS/2 at the same in-lane offsets.
 template <int DH>
+__device__ __forceinline__ void load_q_rotated(const AttnParams &P, int r, int h, int g, bf16x8 (&qf)[DH / 32][2]) {
+    constexpr int KS = DH / 32, HALF = DH / 2;
+    const int b = r / P.T, j = r - b * P.T;
+    const int pos = P.S + clamped_private_len(P, b) + j;
+    const float *row = P.qkv + (size_t)r * 3 * P.H * DH + h * DH;
+    const float *tb = P.rope + (size_t)pos * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS / 2; ++ks) {
+        const int d0 = ks * 32 + 8 * g;
+        float a[8], bb[8], cs[16];
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            *reinterpret_cast<f32x4 *>(&a[4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + 4 * v);
+            *reinterpret_cast<f32x4 *>(&bb[4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + HALF + 4 * v);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            *reinterpret_cast<f32x4 *>(&cs[4 * v]) = *reinterpret_cast<const f32x4 *>(tb + 2 * d0 + 4 * v);
+        u32x4 ah, al, bh, bl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint16_t h0, l0, h1, l1;
+            split_bf16(a[2 * e] * cs[4 * e] - bb[2 * e] * cs[4 * e + 1], h0, l0);
+            split_bf16(a[2 * e + 1] * cs[4 * e + 2] - bb[2 * e + 1] * cs[4 * e + 3], h1, l1);
+            ah[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            al[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            split_bf16(bb[2 * e] * cs[4 * e] + a[2 * e] * cs[4 * e + 1], h0, l0);
+            split_bf16(bb[2 * e + 1] * cs[4 * e + 2] + a[2 * e + 1] * cs[4 * e + 3], h1, l1);
+            bh[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            bl[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        qf[ks][0] = *reinterpret_cast<bf16x8 *>(&ah);
+        qf[ks][1] = *reinterpret_cast<bf16x8 *>(&al);
+        qf[ks + KS / 2][0] = *reinterpret_cast<bf16x8 *>(&bh);
+        qf[ks + KS / 2][1] = *reinterpret_cast<bf16x8 *>(&bl);
+    }
+}
+
+// RT = 16-row tiles of queries per task (1 when the step has at most 16 rows: half the registers, so two
+// workgroups share a CU).
+template <int DH, bool FUSED, int RT>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part) {
@@ -60,55 +127,90 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
     const int HD = P.H * DH;
 
-    // query fragments: B operand, lane holds Q[row0 + t*16 + col][h*DH + ks*32 + 8g .. +8]
-    bf16x8 qf[2][KS][2];
+    // K and V^T fragments of a 32-key chunk (A operands): K rows in the key order described above, two
+    // 16-key tiles x KS k-steps; V^T[d = dt*16 + col][keys c + 8g .. +8].  The first chunk is requested before
+    // anything else and chunk i+1 while chunk i is computed: their addresses depend on nothing loaded here.
+    const int krow = 8 * (col >> 2) + (col & 3);   // key (within the chunk) of A-operand row `col`, tile 0
+    const int wv = threadIdx.x >> 6;               // the 4 wavefronts of the workgroup interleave chunks
+    auto load_kv = [&](int c, bf16x8 (&kf)[2][KS], bf16x8 (&vf)[DT]) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const uint16_t *qp = P.q + (size_t)min(row0 + t * 16 + col, P.Mq - 1) * HD + h * DH + ks * 32 + 8 * g;
-            qf[t][ks][0] = *reinterpret_cast<const bf16x8 *>(qp);
-            qf[t][ks][1] = *reinterpret_cast<const bf16x8 *>(qp + P.q_plane);
-        }
+            for (int ks = 0; ks < KS; ++ks)
+                kf[kt][ks] = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)(c + krow + 4 * kt) * DH + 8 * g + ks * 32);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
+    };
+    const int c0 = kbeg + 32 * wv;
+    bf16x8 kf[2][KS], vf[DT];
+    load_kv(c0 < kend ? c0 : 0, kf, vf);           // (a wavefront without a chunk reads chunk 0 and drops it)
 
-    int limit[2];
+    // query fragments: B operand, lane holds Q[row0 + t*16 + col][h*DH + ks*32 + 8g .. +8]
+    bf16x8 qf[RT][KS][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < RT; ++t) {
+        if (FUSED) {
+            if (row0 + t * 16 < rows_hi) {               // (uniform) a row tile past the task's rows is masked anyway
+                load_q_rotated<DH>(P, min(row0 + t * 16 + col, P.M - 1), h, g, qf[t]);
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const u32x4 z = {0u, 0u, 0u, 0u};
+                    qf[t][ks][0] = qf[t][ks][1] = *reinterpret_cast<const bf16x8 *>(&z);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint16_t *qp = P.q + (size_t)min(row0 + t * 16 + col, P.Mq - 1) * HD + h * DH + ks * 32 + 8 * g;
+                qf[t][ks][0] = *reinterpret_cast<const bf16x8 *>(qp);
+                qf[t][ks][1] = *reinterpret_cast<const bf16x8 *>(qp + P.q_plane);
+            }
+        }
+    }
+
+    int limit[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
         const int r = row0 + t * 16 + col;
         limit[t] = (r < rows_hi) ? lim0 + inc * (r - row_ref) : 0;
     }
 
-    f32x4 o[DT][2];
+    f32x4 o[DT][RT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) o[dt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+        for (int t = 0; t < RT; ++t) o[dt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_run[RT], l_run[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        m_run[t] = -INFINITY;
+        l_run[t] = 0.f;
+    }
 
-    const int krow = 8 * (col >> 2) + (col & 3);   // key (within the chunk) of A-operand row `col`, tile 0
-    const int wv = threadIdx.x >> 6;                      // the 4 wavefronts of the workgroup interleave chunks
-    for (int c = kbeg + 32 * wv; c < kend; c += 128) {
-        f32x4 s[2][2];                              // [key tile][row tile]
+    for (int c = c0; c < kend; c += 128) {
+        // one row tile: the next chunk is requested while this one is computed (two row tiles have no
+        // registers to spare for that at two workgroups per CU)
+        bf16x8 kf_next[2][KS], vf_next[DT];
+        if (RT == 1) load_kv(c + 128 < kend ? c + 128 : c, kf_next, vf_next);
+        f32x4 s[2][RT];                             // [key tile][row tile]
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
-            const uint16_t *kp = kbase + (size_t)(c + krow + 4 * kt) * DH + 8 * g;
-            bf16x8 kf[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(kp + ks * 32);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < RT; ++t) {
                 f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[t][ks][1], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[t][ks][0], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][1], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][0], acc, 0, 0, 0);
                 }
                 s[kt][t] = acc;
             }
         }
-        bf16x8 pf[2][2];   // [row tile][hi|lo]
+        bf16x8 pf[RT][2];  // [row tile][hi|lo]
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < RT; ++t) {
             // lane holds keys c + 8g + {0..3} (tile 0) and c + 8g + {4..7} (tile 1) of query row `col`
             float sv[8];
             float mx = -INFINITY;
@@ -150,22 +252,29 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            // A operand: V^T[d = dt*16 + col][keys c + 8g .. +8]
-            const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][1], o[dt][t], 0, 0, 0);
-                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][0], o[dt][t], 0, 0, 0);
+            for (int t = 0; t < RT; ++t) {
+                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][1], o[dt][t], 0, 0, 0);
+                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
             }
+        }
+        if (RT != 1 && c + 128 < kend) load_kv(c + 128, kf_next, vf_next);
+        if (RT == 1 || c + 128 < kend) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kf_next[kt][ks];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vf[dt] = vf_next[dt];
         }
     }
     // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
     // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
-    __shared__ float sm_m[4][32], sm_l[4][32];
-    __shared__ float sm_o[4][32][DH + 4];
-    float scale[2];
+    __shared__ float sm_m[4][16 * RT], sm_l[4][16 * RT];
+    __shared__ float sm_o[4][16 * RT][DH + 4];
+    float scale[RT];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < RT; ++t) {
         float l = l_run[t];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
@@ -176,7 +285,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     }
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < RT; ++t) {
         const int rr = t * 16 + col;
         float mstar = sm_m[0][rr];
 #pragma unroll
@@ -189,9 +298,9 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         }
     }
     __syncthreads();
-    // wavefront wv finishes rows wv*8 .. wv*8+7: lanes own DH/64 consecutive dims
+    // wavefront wv finishes 4*RT of the rows: lanes own DH/64 consecutive dims
     constexpr int PERD = DH / 64;
-    for (int rr = wv * 8; rr < wv * 8 + 8; ++rr) {
+    for (int rr = wv * 4 * RT; rr < (wv + 1) * 4 * RT; ++rr) {
         const int r = row0 + rr;
         if (r >= rows_hi) continue;
         float mstar = sm_m[0][rr];
@@ -205,19 +314,19 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 #pragma unroll
         for (int i = 0; i < PERD; ++i) {
             const int d = lane * PERD + i;
-            op[i] = ((sm_o[0][rr][d] + sm_o[1][rr][d]) + sm_o[2][rr][d]) + sm_o[3][rr][d];
+            store_agent(op + i, ((sm_o[0][rr][d] + sm_o[1][rr][d]) + sm_o[2][rr][d]) + sm_o[3][rr][d]);
         }
         if (lane == 0) {
             float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
-            mp[0] = mstar;
-            mp[1] = L;
+            store_agent(mp, mstar);
+            store_agent(mp + 1, L);
         }
     }
 }
 
 // In-flight segment: row j of a branch against rows 0..j of the same branch (the causal part of the tree
-// mask).  At most T keys per row, so it runs in plain fp32 on the vector ALUs from an fp32 side copy of the
-// new keys / values: the rows of one step see each other unrounded, while the cache keeps bf16.
+// mask).  At most T keys per row, so it runs in plain fp32 on the vector ALUs from unrounded keys / values:
+// the rows of one step see each other unrounded, while the cache keeps bf16.
 // One wavefront per (row, head); lanes own DH/64 dims; dot products are wavefront-shuffle reductions.
 template <int DH>
 __device__ void inflight_task(const AttnParams &P, int itask) {
@@ -259,89 +368,222 @@ __device__ void inflight_task(const AttnParams &P, int itask) {
     }
 }
 
+// The same segment in the single-launch form: q and the keys are rotated on the fly from the fp32 QKV
+// output, and the wavefront of row r appends that row's rotated key and its value to the private cache.
 template <int DH>
+__device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
+    constexpr int PER = DH / 64, HALF = DH / 2;
+    const int lane = threadIdx.x & 63;
+    if (r >= P.M) return;
+    const int b = r / P.T, j = r - b * P.T;
+    const int HD = P.H * DH;
+    int pl = P.private_len[b];
+    bool store_kv = true;
+    if (pl < 0 || pl > P.max_private) {              // capacity overflow: drop the append, flag it
+        if (lane == 0 && h == 0) atomicOr(P.status, 1);
+        pl = min(max(pl, 0), P.max_private);
+        store_kv = false;
+    }
+    // lane's dims d = lane*PER + i; the rotation partner of d is d ^ HALF, the angle index d % HALF
+    int dl[PER];
+    bool upper[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int d = lane * PER + i;
+        dl[i] = d & (HALF - 1);
+        upper[i] = d >= HALF;
+    }
+    auto rotated = [&](const float *vec, const float *tb, int i) {
+        const int d = lane * PER + i;
+        const float x = vec[d], y = vec[d ^ HALF], c = tb[2 * dl[i]], s_ = tb[2 * dl[i] + 1];
+        return upper[i] ? x * c + y * s_ : x * c - y * s_;
+    };
+    const float *tb0 = P.rope + (size_t)(P.S + pl) * DH;
+    float qv[PER], o[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        qv[i] = rotated(P.qkv + (size_t)r * 3 * HD + h * DH, tb0 + (size_t)j * DH, i);
+        o[i] = 0.f;
+    }
+    float m = -INFINITY, l = 0.f;
+    for (int j0 = 0; j0 <= j; j0 += 4) {                // four keys per pass: their loads overlap
+        float kk[4][PER], vv[4][PER], sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int jj = min(j0 + u, j);
+            const float *krow = P.qkv + (size_t)(b * P.T + jj) * 3 * HD + HD + h * DH;
+            sc[u] = 0.f;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                kk[u][i] = rotated(krow, tb0 + (size_t)jj * DH, i);
+                vv[u][i] = krow[HD + lane * PER + i];
+                sc[u] = fmaf(qv[i], kk[u][i], sc[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (j0 + u > j) continue;
+            const float s = wave_reduce_sum(sc[u]) * P.scale_log2e;
+            const float m_new = fmaxf(m, s);
+            const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
+            l = l * alpha + p;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) o[i] = o[i] * alpha + p * vv[u][i];
+            m = m_new;
+            if (j0 + u == j && store_kv) {              // this row's own key / value: append to the cache
+                const size_t head = (size_t)b * P.H + h;
+                const int idx = pl + j;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    const int d = lane * PER + i;
+                    P.k_priv_w[(head * P.cap_p + idx) * DH + d] = f2bf(kk[u][i]);
+                    P.vt_priv_w[(head * DH + d) * P.cap_p + idx] = f2bf(vv[u][i]);
+                }
+            }
+        }
+    }
+    const int part = P.ks_shared + P.ks_priv;
+    float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
+    if (lane == 0) {
+        float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
+        store_agent(mp, m);
+        store_agent(mp + 1, l);
+    }
+}
+
+// Combine the np partials of head h for the RB rows r0, r0 + rstep, ... by log-sum-exp and write the hi/lo bf16
+// activation (fragment-packed, K = H*DH) that feeds the O projection; rows >= M of the tile are zero.  One
+// wavefront; the loads of all RB rows and of up to eight partials are issued before the first is used (a
+// load that crosses workgroups costs a trip to memory).
+// ACROSS: the partials were written by other workgroups of the same launch (agent-scope loads).
+template <int DH, bool ACROSS, int RB>
+__device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_part, uint16_t *act, int r0, int rstep,
+                                           int h, int M, int Mp, int Mq, int H, int np) {
+    const int lane = threadIdx.x & 63;
+    const int KT = (H * DH) >> 5;
+    constexpr int PER = DH / 64;     // output dims per lane
+    constexpr int NPB = 8;
+    auto ld = [](const float *p) { return ACROSS ? load_agent(p) : *p; };
+    float mrun[RB], Lrun[RB], acc[RB][PER];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        mrun[i] = -INFINITY;
+        Lrun[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) acc[i][e] = 0.f;
+    }
+    for (int p0 = 0; p0 < np; p0 += NPB) {
+        float m[RB][NPB], l[RB][NPB], v[RB][NPB][PER];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            const int r = min(r0 + i * rstep, M - 1);
+#pragma unroll
+            for (int k = 0; k < NPB; ++k) {
+                const size_t base = ((size_t)min(p0 + k, np - 1) * Mq + r) * H + h;
+                m[i][k] = ld(ml_part + base * 2);
+                l[i][k] = ld(ml_part + base * 2 + 1);
+#pragma unroll
+                for (int e = 0; e < PER; ++e) v[i][k][e] = ld(o_part + base * DH + lane * PER + e);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            float mx = mrun[i];
+#pragma unroll
+            for (int k = 0; k < NPB; ++k)
+                if (p0 + k < np && l[i][k] != 0.f) mx = fmaxf(mx, m[i][k]);
+            const float sc = (mrun[i] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mrun[i] - mx);
+            Lrun[i] *= sc;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[i][e] *= sc;
+#pragma unroll
+            for (int k = 0; k < NPB; ++k) {
+                if (p0 + k >= np || l[i][k] == 0.f) continue;     // past the end / empty key range
+                const float wgt = __builtin_amdgcn_exp2f(m[i][k] - mx);
+                Lrun[i] += l[i][k] * wgt;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) acc[i][e] += v[i][k][e] * wgt;
+            }
+            mrun[i] = mx;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int r = r0 + i * rstep;
+        if (r >= Mp) continue;
+        const float inv = (r < M && Lrun[i] > 0.f) ? 1.0f / Lrun[i] : 0.f;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const size_t o = packed_offset(r, h * DH + lane * PER + e, KT);
+            split_bf16(acc[i][e] * inv, act[o], act[o + kActLoOffset]);
+        }
+    }
+}
+
+template <int DH, bool FUSED, int RT>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
     // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
-    // then four in-flight (row, head) wavefront tasks per workgroup
+    // then in-flight tasks, one (row, head) per wavefront
     const int task = blockIdx.x;
     const int n_shared = P.H * P.n_groups * P.ks_shared;
+    const int n_priv = P.prefill_shared ? 0 : P.N * P.H * P.groups_priv * P.ks_priv;
+    int h;
     if (task < n_shared) {
         const int ks = task % P.ks_shared;
         const int grp = (task / P.ks_shared) % P.n_groups;
-        const int h = task / (P.ks_shared * P.n_groups);
+        h = task / (P.ks_shared * P.n_groups);
         const int total = P.prefill_shared ? P.S + P.M : P.S;
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
-        attn_task<DH>(P, h, grp * 32, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
-                      P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
-                      P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
-        return;
+        attn_task<DH, FUSED, RT>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+                             P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
+                             P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
+    } else if (task - n_shared < n_priv) {
+        const int ptask = task - n_shared;
+        const int ks = ptask % P.ks_priv;
+        const int grp = (ptask / P.ks_priv) % P.groups_priv;
+        h = (ptask / (P.ks_priv * P.groups_priv)) % P.H;
+        const int b = ptask / (P.ks_priv * P.groups_priv * P.H);
+        const int pl = clamped_private_len(P, b);       // committed private context; in-flight rows are separate
+        const int kbeg = ks * P.keys_per_range;
+        const int kend = min(pl, kbeg + P.keys_per_range);
+        const int row_first = b * P.T;
+        // every row of the branch sees all pl committed private keys
+        attn_task<DH, FUSED, RT>(P, h, row_first + grp * 16 * RT, row_first + P.T,
+                             P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
+                             P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend), pl,
+                             row_first, 0, P.ks_shared + ks);
+    } else {
+        const int itask = task - n_shared - n_priv;
+        if (FUSED) {                                      // workgroup = (head, four consecutive rows)
+            h = itask % P.H;
+            inflight_task_fused<DH>(P, h, (itask / P.H) * 4 + (threadIdx.x >> 6));
+        } else {
+            h = 0;
+            if (!P.prefill_shared) inflight_task<DH>(P, itask * 4 + (threadIdx.x >> 6));
+        }
     }
-    const int ptask = task - n_shared;
-    const int n_priv = P.prefill_shared ? 0 : P.N * P.H * P.groups_priv * P.ks_priv;
-    if (ptask >= n_priv) {
-        if (!P.prefill_shared) inflight_task<DH>(P, (ptask - n_priv) * 4 + (threadIdx.x >> 6));
-        return;
+    if (FUSED && P.merge_in_launch) {
+        // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
+        __shared__ int s_last;
+        const int expected = P.n_groups * P.ks_shared + P.N * P.groups_priv * P.ks_priv + P.n_inflight_wgs;
+        if (!arrive_last(P.counters + h, expected, &s_last)) return;
+        const int np = P.ks_shared + P.ks_priv + 1;
+        for (int r = threadIdx.x >> 6; r < P.Mp; r += 16)     // rows r, r+4, r+8, r+12 per pass
+            merge_rows<DH, true, 4>(P.o_part, P.ml_part, P.act, r, 4, h, P.M, P.Mp, P.Mq, P.H, np);
     }
-    const int ks = ptask % P.ks_priv;
-    const int grp = (ptask / P.ks_priv) % P.groups_priv;
-    const int h = (ptask / (P.ks_priv * P.groups_priv)) % P.H;
-    const int b = ptask / (P.ks_priv * P.groups_priv * P.H);
-    const int pl = min(max(P.private_len[b], 0), P.max_private);
-    const int total = pl;                             // committed private context; in-flight rows are separate
-    const int kbeg = ks * P.keys_per_range;
-    const int kend = min(total, kbeg + P.keys_per_range);
-    const int row_first = b * P.T;
-    // every row of the branch sees all pl committed private keys
-    attn_task<DH>(P, h, row_first + grp * 32, row_first + P.T,
-                  P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH, P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p,
-                  P.cap_p, kbeg, max(kbeg, kend), pl, row_first, 0, P.ks_shared + ks);
 }
 
-// Combine the partials of one (row, head) by log-sum-exp and write the bf16 activation (fragment-packed,
-// K = H*DH) that feeds the O projection.  One wavefront per (row, head).
+// Merge as a launch of its own (shared-prefix prefill).  One wavefront per (row, head).
 template <int DH>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, const float *ml_part, uint16_t *act,
-                                                         int M, int Mq, int Mp, int H, int n_part_shared,
-                                                         int n_part_total, int prefill_shared) {
+                                                         int M, int Mq, int Mp, int H, int np) {
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
     if (w >= Mp * H) return;
-    const int r = w / H, h = w - r * H;
-    const int KT = (H * DH) >> 5;
-    constexpr int PER = DH / 64;     // output dims per lane
-    if (r >= M) {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const size_t o = packed_offset(r, h * DH + lane * PER + i, KT);
-            act[o] = 0;
-            act[o + kActLoOffset] = 0;
-        }
-        return;
-    }
-    const int np = prefill_shared ? n_part_shared : n_part_total;
-    float mmax = -INFINITY;
-    for (int p = 0; p < np; ++p) mmax = fmaxf(mmax, ml_part[(((size_t)p * Mq + r) * H + h) * 2]);
-    float acc[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
-    float L = 0.f;
-    for (int p = 0; p < np; ++p) {
-        const size_t base = ((size_t)p * Mq + r) * H + h;
-        const float m = ml_part[base * 2], l = ml_part[base * 2 + 1];
-        if (l == 0.f) continue;                       // empty key range
-        const float wgt = __builtin_amdgcn_exp2f(m - mmax);
-        L += l * wgt;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] += o_part[base * DH + lane * PER + i] * wgt;
-    }
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const size_t o = packed_offset(r, h * DH + lane * PER + i, KT);
-        split_bf16(acc[i] * inv, act[o], act[o + kActLoOffset]);
-    }
+    merge_rows<DH, false, 1>(o_part, ml_part, act, w / H, 1, w % H, M, Mp, Mq, H, np);
 }
 
 }  // namespace
@@ -368,46 +610,65 @@ void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_
     (void)T;
 }
 
-int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared, const void *vt_shared, const void *k_priv,
-                     const void *vt_priv, const int32_t *private_len, const float *k_new, const float *v_new,
-                     float *o_part, float *ml_part, void *act,
-                     int M, int Mp, int Mq, int N, int T, int H, int S, int prefill_shared, int cap_s, int cap_p,
-                     int max_private, int ks_shared, int keys_per_range, int ks_priv, hipStream_t st) {
-    AttnParams P;
-    P.q = (const uint16_t *)q;
-    P.q_plane = q_plane;
-    P.k_shared = (const uint16_t *)k_shared;
-    P.vt_shared = (const uint16_t *)vt_shared;
-    P.k_priv = (const uint16_t *)k_priv;
-    P.vt_priv = (const uint16_t *)vt_priv;
-    P.private_len = private_len;
-    P.k_new = k_new;
-    P.v_new = v_new;
-    P.o_part = o_part;
-    P.ml_part = ml_part;
-    P.M = M; P.Mq = Mq; P.N = N; P.T = T; P.H = H; P.S = S;
-    P.prefill_shared = prefill_shared;
-    P.cap_s = cap_s; P.cap_p = cap_p; P.max_private = max_private;
-    P.n_groups = (Mq + 31) / 32;
-    P.ks_shared = ks_shared;
-    P.keys_per_range = keys_per_range;
-    P.ks_priv = ks_priv;
-    P.groups_priv = (T + 31) / 32;
-    P.scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-    const int blocks = H * P.n_groups * ks_shared + (prefill_shared ? 0 : N * H * P.groups_priv * ks_priv + (M * H + 3) / 4);
-    const int n_total = ks_shared + ks_priv + 1;      // + the in-flight slot
-    if (dh == 128) {
-        hipLaunchKernelGGL(attn_partial_kernel<128>, dim3(blocks), dim3(256), 0, st, P);
-        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((Mp * H + 3) / 4), dim3(256), 0, st, o_part, ml_part,
-                           (uint16_t *)act, M, Mq, Mp, H, ks_shared, n_total, prefill_shared);
-    } else if (dh == 64) {
-        hipLaunchKernelGGL(attn_partial_kernel<64>, dim3(blocks), dim3(256), 0, st, P);
-        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((Mp * H + 3) / 4), dim3(256), 0, st, o_part, ml_part,
-                           (uint16_t *)act, M, Mq, Mp, H, ks_shared, n_total, prefill_shared);
-    } else {
-        set_error("bf16 attention supports head_dim 64 or 128, got %d", dh);
+int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
+    AttnParams P{};
+    P.q = (const uint16_t *)a.q;
+    P.q_plane = a.q_plane;
+    P.k_shared = (const uint16_t *)a.k_shared;
+    P.vt_shared = (const uint16_t *)a.vt_shared;
+    P.k_priv = (const uint16_t *)a.k_priv;
+    P.vt_priv = (const uint16_t *)a.vt_priv;
+    P.k_priv_w = (uint16_t *)a.k_priv;
+    P.vt_priv_w = (uint16_t *)a.vt_priv;
+    P.private_len = a.private_len;
+    P.k_new = a.k_new;
+    P.v_new = a.v_new;
+    P.o_part = a.o_part;
+    P.ml_part = a.ml_part;
+    P.qkv = a.qkv;
+    P.rope = a.rope;
+    P.counters = a.counters;
+    P.act = (uint16_t *)a.act;
+    P.status = a.status;
+    P.M = a.M; P.Mp = a.Mp; P.Mq = a.Mq; P.N = a.N; P.T = a.T; P.H = a.H; P.S = a.S;
+    P.prefill_shared = a.prefill_shared;
+    P.cap_s = a.cap_s; P.cap_p = a.cap_p; P.max_private = a.max_private;
+    const int rt = a.M <= 16 ? 1 : 2;                     // 16-row query tiles per task
+    P.n_groups = (a.M + 16 * rt - 1) / (16 * rt);
+    P.ks_shared = a.ks_shared;
+    P.keys_per_range = a.keys_per_range;
+    P.ks_priv = a.ks_priv;
+    P.groups_priv = (a.T + 16 * rt - 1) / (16 * rt);
+    P.scale_log2e = 1.4426950408889634f / sqrtf((float)a.dh);
+    const bool fused = !a.prefill_shared;
+    // in-flight workgroups: single launch (head, four rows); prefill has none
+    P.n_inflight_wgs = fused ? (a.M + 3) / 4 : 0;
+    const int blocks = a.H * P.n_groups * a.ks_shared +
+                       (fused ? a.N * a.H * P.groups_priv * a.ks_priv + P.n_inflight_wgs * a.H : 0);
+    if (a.dh != 128 && a.dh != 64) {
+        set_error("bf16 attention supports head_dim 64 or 128, got %d", a.dh);
         return SEED_E_SHAPE;
     }
+    // up to 32 rows the last workgroup of a head merges them in one or two passes; more rows would queue up
+    // behind its four wavefronts, so they get a merge launch with a wavefront per (row, head)
+    P.merge_in_launch = fused && a.Mp <= 32;
+    const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
+#define SEEDV_ATTN(DHv, FUSEDv, RTv) \
+    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, RTv>), dim3(blocks), dim3(256), 0, st, P)
+    if (a.dh == 128) {
+        if (fused) { if (rt == 1) SEEDV_ATTN(128, true, 1); else SEEDV_ATTN(128, true, 2); }
+        else { if (rt == 1) SEEDV_ATTN(128, false, 1); else SEEDV_ATTN(128, false, 2); }
+        if (!P.merge_in_launch)
+            hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
+                               a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);
+    } else {
+        if (fused) { if (rt == 1) SEEDV_ATTN(64, true, 1); else SEEDV_ATTN(64, true, 2); }
+        else { if (rt == 1) SEEDV_ATTN(64, false, 1); else SEEDV_ATTN(64, false, 2); }
+        if (!P.merge_in_launch)
+            hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
+                               a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);
+    }
+#undef SEEDV_ATTN
     return hip_fail(hipGetLastError(), "attention launch");
 }
 

@@ -41,4 +41,37 @@ __device__ __forceinline__ float wave_reduce_sum(float v) {
     return v;
 }
 
+// Data handed from one workgroup to another INSIDE a launch (split-K partials, per-tile sums of squares)
+// moves with agent-scope relaxed atomic stores / loads: they write through, resp. read around, the per-XCD
+// L2, so the hand-over needs no full-L2 write-back / invalidate fence (which costs ~100 us per launch when
+// every workgroup issues one); ordering is "wait for my stores, workgroup barrier, bump the counter".
+__device__ __forceinline__ void store_agent(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store4_agent(float *p, const f32x4 &v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 load4_agent(const float *p) {
+    f32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+// all of this workgroup's earlier stores have completed; returns true in the workgroup that arrives last
+__device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_flag) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (old == expected - 1);
+        if (*s_flag) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // re-arm
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
 }  // namespace seedv

@@ -29,6 +29,7 @@ namespace {
 
 constexpr int kMaxCounters = 4096;
 constexpr int kMaxAttnSlots = 128;
+constexpr int kMaxHeads = 1024;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
@@ -42,7 +43,7 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, rope, q, k_new, v_new, o_part, ml_part, logits, status;
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, k_new, v_new, o_part, ml_part, logits, status;
     int n_pos;
     size_t part_floats;
     size_t total;
@@ -73,6 +74,10 @@ int validate_cfg(const seed_model_cfg *c) {
         if (c->head_dim != 64 && c->head_dim != 128) {
             set_error("bf16 path supports head_dim 64 or 128");
             return SEED_E_SHAPE;
+        }
+        if (c->n_heads > kMaxHeads) {
+            set_error("bf16 path supports at most %d heads", kMaxHeads);
+            return SEED_E_CAPACITY;
         }
         if ((long)c->max_branches * c->max_rows_per_branch > 128) {
             set_error("bf16 path supports at most 128 rows per step (max_branches * max_rows_per_branch)");
@@ -144,6 +149,7 @@ Layout make_layout(const seed_model_cfg &c) {
     L.rinv = take((size_t)L.Mp_cap * 4);
     L.ssq = take((size_t)L.M_cap * (d / 16 + 1) * 4);
     L.counters = take(4096 * 4);
+    L.attn_counters = take(kMaxHeads * 4);
     L.n_pos = c.max_shared + c.max_private + c.max_rows_per_branch + 1;
     L.rope = take((size_t)L.n_pos * dh * 4);
     L.q = take((size_t)L.Mq_cap * HD * 4);   // bf16 path: hi and lo planes
@@ -303,14 +309,29 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         rc = gemm(EPI_STORE, layer_w(c, l, L.w_qkv), 3 * HD, d, at(c, L.act_d), a);
         if (rc) return rc;
         const KvPtrs kv = kv_layer(c, l);
-        rc = launch_rope_kv(true, (const float *)at(c, L.qkv), (const float *)at(c, L.rope), at(c, L.q), q_plane, kv.ks,
-                            kv.vs, kv.kp, kv.vp, (float *)at(c, L.k_new), (float *)at(c, L.v_new), private_len, M, Mq, T,
-                            H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private, status, st);
-        if (rc) return rc;
-        rc = launch_attn_bf16(dh, at(c, L.q), q_plane, kv.ks, kv.vs, kv.kp, kv.vp, private_len,
-                              (const float *)at(c, L.k_new), (const float *)at(c, L.v_new), (float *)at(c, L.o_part),
-                              (float *)at(c, L.ml_part), at(c, L.act_hd), M, Mp, Mq, N, T, H, S, prefill_shared, L.cap_s,
-                              L.cap_p, g.max_private, ks_shared, keys_per_range, ks_priv, st);
+        if (prefill_shared) {
+            rc = launch_rope_kv(true, (const float *)at(c, L.qkv), (const float *)at(c, L.rope), at(c, L.q), q_plane,
+                                kv.ks, kv.vs, kv.kp, kv.vp, (float *)at(c, L.k_new), (float *)at(c, L.v_new),
+                                private_len, M, Mq, T, H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private,
+                                status, st);
+            if (rc) return rc;
+        }
+        AttnBf16Args at_{};
+        at_.dh = dh;
+        at_.q = at(c, L.q); at_.q_plane = q_plane;
+        at_.qkv = (const float *)at(c, L.qkv); at_.rope = (const float *)at(c, L.rope);
+        at_.k_shared = kv.ks; at_.vt_shared = kv.vs; at_.k_priv = kv.kp; at_.vt_priv = kv.vp;
+        at_.private_len = private_len;
+        at_.k_new = (const float *)at(c, L.k_new); at_.v_new = (const float *)at(c, L.v_new);
+        at_.o_part = (float *)at(c, L.o_part); at_.ml_part = (float *)at(c, L.ml_part);
+        at_.counters = (int *)at(c, L.attn_counters);
+        at_.act = at(c, L.act_hd);
+        at_.status = status;
+        at_.M = M; at_.Mp = Mp; at_.Mq = Mq; at_.N = N; at_.T = T; at_.H = H; at_.S = S;
+        at_.prefill_shared = prefill_shared;
+        at_.cap_s = L.cap_s; at_.cap_p = L.cap_p; at_.max_private = g.max_private;
+        at_.ks_shared = ks_shared; at_.keys_per_range = keys_per_range; at_.ks_priv = ks_priv;
+        rc = launch_attn_bf16(at_, st);
         if (rc) return rc;
         GemmArgs o{};
         o.x = x;

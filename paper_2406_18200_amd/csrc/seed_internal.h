@@ -64,11 +64,24 @@ int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv);
-int launch_attn_bf16(int dh, const void *q, size_t q_plane, const void *k_shared, const void *vt_shared, const void *k_priv,
-                     const void *vt_priv, const int32_t *private_len, const float *k_new, const float *v_new,
-                     float *o_part, float *ml_part, void *act,
-                     int M, int Mp, int Mq, int N, int T, int H, int S, int prefill_shared, int cap_s, int cap_p,
-                     int max_private, int ks_shared, int keys_per_range, int ks_priv, hipStream_t st);
+// Verify / decode steps (prefill_shared == 0) run as one launch that reads qkv / rope directly, appends to the
+// private cache, sets status bit 0 on a private-length overflow and merges through `counters` (n_heads ints,
+// zero on entry, left zero); the shared-prefix prefill reads q (hi/lo planes) written by launch_rope_kv.
+struct AttnBf16Args {
+    int dh;
+    const void *q; size_t q_plane;
+    const float *qkv, *rope;
+    const void *k_shared, *vt_shared;
+    void *k_priv, *vt_priv;
+    const int32_t *private_len;
+    const float *k_new, *v_new;
+    float *o_part, *ml_part;
+    int *counters;
+    void *act;
+    int32_t *status;
+    int M, Mp, Mq, N, T, H, S, prefill_shared, cap_s, cap_p, max_private, ks_shared, keys_per_range, ks_priv;
+};
+int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st);
 // ---- fp32_path.hip -----------------------------------------------------------------------------------
 int launch_gemm_f32(const void *W, const void *X, float *Y, int M, int Nout, int K, int ldy, hipStream_t st);
 int launch_attn_f32(const void *q, const void *k_shared, const void *v_shared, const void *k_priv,
