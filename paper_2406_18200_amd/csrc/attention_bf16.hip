@@ -76,26 +76,43 @@ __device__ __forceinline__ int clamped_private_len(const AttnParams &P, int b) {
 
 // Query fragments (B operand, hi/lo) of row r, head h from the fp32 QKV output with the rotary embedding
 // applied: lane group g holds dims ks*32 + 8g .. +8 of every k-step; a dim below DH/2 pairs with dim + DH/2,
-// i.e. k-step ks with ks + KS/2 at the same in-lane offsets.
+// i.e. k-step ks with ks + KS/2 at the same in-lane offsets.  Two stages, so that the loads that depend on
+// nothing (the branch's private length, the raw q values) are in flight before the K / V chunk is requested
+// and only the angle table waits for the length.
 template <int DH>
-__device__ __forceinline__ void load_q_rotated(const AttnParams &P, int r, int h, int g, bf16x8 (&qf)[DH / 32][2]) {
+struct RawQ {
+    float lo[DH / 64][8], hi[DH / 64][8];   // dims d0 .. d0+8 and d0 + DH/2 .. of each k-step pair
+    int pl;                                  // private length of the row's branch, as loaded
+};
+template <int DH>
+__device__ __forceinline__ void load_q_raw(const AttnParams &P, int r, int h, int g, RawQ<DH> &q) {
     constexpr int KS = DH / 32, HALF = DH / 2;
-    const int b = r / P.T, j = r - b * P.T;
-    const int pos = P.S + clamped_private_len(P, b) + j;
     const float *row = P.qkv + (size_t)r * 3 * P.H * DH + h * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS / 2; ++ks) {
+        const int d0 = ks * 32 + 8 * g;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            *reinterpret_cast<f32x4 *>(&q.lo[ks][4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + 4 * v);
+            *reinterpret_cast<f32x4 *>(&q.hi[ks][4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + HALF + 4 * v);
+        }
+    }
+}
+template <int DH>
+__device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, const RawQ<DH> &q,
+                                         bf16x8 (&qf)[DH / 32][2]) {
+    constexpr int KS = DH / 32;
+    const int j = r % P.T;
+    const int pos = P.S + min(max(q.pl, 0), P.max_private) + j;
     const float *tb = P.rope + (size_t)pos * DH;
 #pragma unroll
     for (int ks = 0; ks < KS / 2; ++ks) {
         const int d0 = ks * 32 + 8 * g;
-        float a[8], bb[8], cs[16];
-#pragma unroll
-        for (int v = 0; v < 2; ++v) {
-            *reinterpret_cast<f32x4 *>(&a[4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + 4 * v);
-            *reinterpret_cast<f32x4 *>(&bb[4 * v]) = *reinterpret_cast<const f32x4 *>(row + d0 + HALF + 4 * v);
-        }
+        float cs[16];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             *reinterpret_cast<f32x4 *>(&cs[4 * v]) = *reinterpret_cast<const f32x4 *>(tb + 2 * d0 + 4 * v);
+        const float *a = q.lo[ks], *bb = q.hi[ks];
         u32x4 ah, al, bh, bl;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -143,23 +160,28 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
     };
     const int c0 = kbeg + 32 * wv;
+    // Issue order: the private lengths (oldest, so they can be waited for alone), the K / V chunk, the raw q
+    // values; straight-line code, or the compiler drains the load queue at the join of a branch.  Rows past the
+    // task's rows are clamped to a valid row and masked later.
+    RawQ<DH> qraw[RT];
+    if (FUSED) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) qraw[t].pl = P.private_len[min(row0 + t * 16 + col, P.M - 1) / P.T];
+    }
     bf16x8 kf[2][KS], vf[DT];
     load_kv(c0 < kend ? c0 : 0, kf, vf);           // (a wavefront without a chunk reads chunk 0 and drops it)
+    if (FUSED) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) load_q_raw<DH>(P, min(row0 + t * 16 + col, P.M - 1), h, g, qraw[t]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     // query fragments: B operand, lane holds Q[row0 + t*16 + col][h*DH + ks*32 + 8g .. +8]
     bf16x8 qf[RT][KS][2];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
         if (FUSED) {
-            if (row0 + t * 16 < rows_hi) {               // (uniform) a row tile past the task's rows is masked anyway
-                load_q_rotated<DH>(P, min(row0 + t * 16 + col, P.M - 1), h, g, qf[t]);
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const u32x4 z = {0u, 0u, 0u, 0u};
-                    qf[t][ks][0] = qf[t][ks][1] = *reinterpret_cast<const bf16x8 *>(&z);
-                }
-            }
+            rotate_q<DH>(P, min(row0 + t * 16 + col, P.M - 1), g, qraw[t], qf[t]);
         } else {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -188,12 +210,12 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         m_run[t] = -INFINITY;
         l_run[t] = 0.f;
     }
-
     for (int c = c0; c < kend; c += 128) {
         // one row tile: the next chunk is requested while this one is computed (two row tiles have no
         // registers to spare for that at two workgroups per CU)
         bf16x8 kf_next[2][KS], vf_next[DT];
-        if (RT == 1) load_kv(c + 128 < kend ? c + 128 : c, kf_next, vf_next);
+        const bool more = c + 128 < kend;             // (uniform)
+        if (RT == 1 && more) load_kv(c + 128, kf_next, vf_next);
         f32x4 s[2][RT];                             // [key tile][row tile]
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
@@ -258,8 +280,8 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
                 o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
             }
         }
-        if (RT != 1 && c + 128 < kend) load_kv(c + 128, kf_next, vf_next);
-        if (RT == 1 || c + 128 < kend) {
+        if (RT != 1 && more) load_kv(c + 128, kf_next, vf_next);
+        if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -298,28 +320,41 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         }
     }
     __syncthreads();
-    // wavefront wv finishes 4*RT of the rows: lanes own DH/64 consecutive dims
-    constexpr int PERD = DH / 64;
-    for (int rr = wv * 4 * RT; rr < (wv + 1) * 4 * RT; ++rr) {
-        const int r = row0 + rr;
-        if (r >= rows_hi) continue;
-        float mstar = sm_m[0][rr];
+    // wavefront wv finishes 4*RT of the rows: lanes own DH/64 consecutive dims.  All LDS reads first, no
+    // branch but the one around the stores (a wavefront is alone on its SIMD here: every dependent wait shows).
+    constexpr int PERD = DH / 64, RW = 4 * RT;
+    float mm[RW][4], ll[RW][4], ov[RW][PERD];
 #pragma unroll
-        for (int i = 1; i < 4; ++i) mstar = fmaxf(mstar, sm_m[i][rr]);
+    for (int q = 0; q < RW; ++q) {
+        const int rr = wv * RW + q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            mm[q][i] = sm_m[i][rr];
+            ll[q][i] = sm_l[i][rr];
+        }
+#pragma unroll
+        for (int e = 0; e < PERD; ++e) {
+            const int d = lane * PERD + e;
+            ov[q][e] = ((sm_o[0][rr][d] + sm_o[1][rr][d]) + sm_o[2][rr][d]) + sm_o[3][rr][d];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < RW; ++q) {
+        const int r = row0 + wv * RW + q;
+        const float mstar = fmaxf(fmaxf(mm[q][0], mm[q][1]), fmaxf(mm[q][2], mm[q][3]));
+        const float mu = (mstar == -INFINITY) ? 0.f : mstar;       // an empty wavefront has l = 0 and m = -inf
         float L = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            L += (sm_m[i][rr] == -INFINITY) ? 0.f : sm_l[i][rr] * __builtin_amdgcn_exp2f(sm_m[i][rr] - mstar);
-        float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PERD;
+        for (int i = 0; i < 4; ++i) L += ll[q][i] * __builtin_amdgcn_exp2f(mm[q][i] - mu);
+        if (r < rows_hi) {
+            float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PERD;
+            if (PERD == 2) {
+                store2_agent(op, ov[q][0], ov[q][PERD - 1]);
+            } else {
 #pragma unroll
-        for (int i = 0; i < PERD; ++i) {
-            const int d = lane * PERD + i;
-            store_agent(op + i, ((sm_o[0][rr][d] + sm_o[1][rr][d]) + sm_o[2][rr][d]) + sm_o[3][rr][d]);
-        }
-        if (lane == 0) {
-            float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
-            store_agent(mp, mstar);
-            store_agent(mp + 1, L);
+                for (int e = 0; e < PERD; ++e) store_agent(op + e, ov[q][e]);
+            }
+            if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2, mstar, L);
         }
     }
 }
@@ -446,11 +481,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
 #pragma unroll
     for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
-    if (lane == 0) {
-        float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
-        store_agent(mp, m);
-        store_agent(mp + 1, l);
-    }
+    if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2, m, l);
 }
 
 // Combine the np partials of head h for the RB rows r0, r0 + rstep, ... by log-sum-exp and write the hi/lo bf16
@@ -466,6 +497,15 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
     constexpr int PER = DH / 64;     // output dims per lane
     constexpr int NPB = 8;
     auto ld = [](const float *p) { return ACROSS ? load_agent(p) : *p; };
+    auto ld2 = [](const float *p, float &x, float &y) {      // two adjacent floats, 8-byte aligned
+        if (ACROSS) {
+            load2_agent(p, x, y);
+        } else {
+            const float2 w = *reinterpret_cast<const float2 *>(p);
+            x = w.x;
+            y = w.y;
+        }
+    };
     float mrun[RB], Lrun[RB], acc[RB][PER];
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
@@ -477,15 +517,19 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
     for (int p0 = 0; p0 < np; p0 += NPB) {
         float m[RB][NPB], l[RB][NPB], v[RB][NPB][PER];
 #pragma unroll
-        for (int i = 0; i < RB; ++i) {
-            const int r = min(r0 + i * rstep, M - 1);
+        for (int k = 0; k < NPB; ++k) {
+            if (p0 + k >= np) break;                      // (uniform)
 #pragma unroll
-            for (int k = 0; k < NPB; ++k) {
-                const size_t base = ((size_t)min(p0 + k, np - 1) * Mq + r) * H + h;
-                m[i][k] = ld(ml_part + base * 2);
-                l[i][k] = ld(ml_part + base * 2 + 1);
+            for (int i = 0; i < RB; ++i) {
+                const int r = min(r0 + i * rstep, M - 1);
+                const size_t base = ((size_t)(p0 + k) * Mq + r) * H + h;
+                ld2(ml_part + base * 2, m[i][k], l[i][k]);
+                if (PER == 2) {
+                    ld2(o_part + base * DH + lane * 2, v[i][k][0], v[i][k][PER - 1]);
+                } else {
 #pragma unroll
-                for (int e = 0; e < PER; ++e) v[i][k][e] = ld(o_part + base * DH + lane * PER + e);
+                    for (int e = 0; e < PER; ++e) v[i][k][e] = ld(o_part + base * DH + lane * PER + e);
+                }
             }
         }
 #pragma unroll
@@ -526,6 +570,14 @@ template <int DH, bool FUSED, int RT>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
     // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
     // then in-flight tasks, one (row, head) per wavefront
+    // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
+    asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
+                 "s"(P.private_len), "s"(P.k_new), "s"(P.v_new), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
+                 "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
+    asm volatile("" ::"s"(P.Mp), "s"(P.n_inflight_wgs), "s"(P.merge_in_launch), "s"(P.M), "s"(P.Mq), "s"(P.N),
+                 "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
+                 "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.ks_priv), "s"(P.groups_priv),
+                 "s"(P.scale_log2e));
     const int task = blockIdx.x;
     const int n_shared = P.H * P.n_groups * P.ks_shared;
     const int n_priv = P.prefill_shared ? 0 : P.N * P.H * P.groups_priv * P.ks_priv;

@@ -51,6 +51,17 @@ __device__ __forceinline__ void store_agent(float *p, float v) {
 __device__ __forceinline__ float load_agent(const float *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// two adjacent floats (8-byte aligned) as one 64-bit access
+__device__ __forceinline__ void store2_agent(float *p, float x, float y) {
+    const unsigned long long w = (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void load2_agent(const float *p, float &x, float &y) {
+    const unsigned long long w = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    x = __uint_as_float((uint32_t)w);
+    y = __uint_as_float((uint32_t)(w >> 32));
+}
 __device__ __forceinline__ void store4_agent(float *p, const f32x4 &v) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
