@@ -15,6 +15,7 @@ namespace {
 
 constexpr int kBlock = 1024;
 constexpr int kWaves = kBlock / 64;
+constexpr int kMaxSlices = 16;
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -139,6 +140,10 @@ __device__ __forceinline__ unsigned long long weight_fixed(const TargetRow &row,
 
 // Fixed-point inverse CDF over [0, V): token = min{v : sum_{w<=v} k_w > (m * Z) >> 24}, u = m 2^-24.
 // Returns -1 if every weight truncates to zero.  Uniform control flow: every thread of the block calls.
+// The integer sums make the result independent of the order of summation, so the two phases are free to
+// use different ones: totals per wavefront segment with coalesced strided loads, then the one wavefront whose
+// segment holds the target walks it in blocks of 2048 tokens, 32 CONSECUTIVE tokens per lane (one batch of
+// loads, one wavefront scan over the lane sums, a register walk in the lane that holds the target).
 template <int RESIDUAL>
 __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, Shared &sm) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -146,7 +151,7 @@ __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, 
     const int base = wave * per;
     const int end = min(V, base + per);
     unsigned long long local = 0;
-#pragma unroll 8
+#pragma unroll 16
     for (int v = base + lane; v < end; v += 64) local += weight_fixed<RESIDUAL>(row, q, v);
     local = wave_sum_u64(local);
     __syncthreads();
@@ -167,18 +172,36 @@ __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, 
         run = nx;
     }
     if (wave == target) {
-        for (int i = base; i < end; i += 64) {
-            int v = i + lane;
-            unsigned long long k = v < end ? weight_fixed<RESIDUAL>(row, q, v) : 0ull;
-            unsigned long long incl = k;
+        constexpr int kPerLane = 32;
+        for (int blk = base; blk < end; blk += 64 * kPerLane) {
+            const int v0 = blk + lane * kPerLane;
+            unsigned long long k[kPerLane];
+            unsigned long long mine = 0;
+#pragma unroll
+            for (int e = 0; e < kPerLane; ++e) {
+                const int v = v0 + e;
+                k[e] = v < end ? weight_fixed<RESIDUAL>(row, q, min(v, end - 1)) : 0ull;
+                mine += k[e];
+            }
+            unsigned long long incl = mine;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 unsigned long long o = __shfl_up(incl, off);
                 if (lane >= off) incl += o;
             }
-            unsigned long long hit = __ballot(run + incl > t);
+            const unsigned long long hit = __ballot(run + incl > t);
             if (hit) {
-                if (lane == 0) sm.tok = i + (__ffsll((long long)hit) - 1);
+                const int src = __ffsll((long long)hit) - 1;          // first lane whose prefix passes t
+                if (lane == src) {
+                    unsigned long long c = run + incl - mine;
+                    int tok = v0;
+#pragma unroll
+                    for (int e = 0; e < kPerLane; ++e) {
+                        c += k[e];
+                        if (c > t) { tok = v0 + e; break; }
+                    }
+                    sm.tok = tok;
+                }
                 break;
             }
             run += __shfl(incl, 63);
@@ -186,6 +209,66 @@ __device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, 
     }
     __syncthreads();
     return sm.tok;
+}
+
+// Statistics of one slice of a row of logits, written by row_stats_kernel: the maximum, its lowest index, and
+// the sum of exp((x - that maximum) / temperature) over the slice.
+struct SliceStats {
+    float mx;
+    int idx;
+    float sum;
+    int pad;
+};
+
+// Softmax statistics of every target row, spread over the whole chip: grid (rows, slices), 256 threads.  The
+// accept kernel has one workgroup per BRANCH (the accept chain is sequential within a branch), far too few
+// to read N*T rows of V logits quickly; here each workgroup reads V / slices of them.
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits, int V, int per, float inv_temp,
+                                                        SliceStats *stats) {
+    __shared__ float s_m[4];
+    __shared__ int s_i[4];
+    __shared__ float s_s[4];
+    const int row = blockIdx.x, sl = blockIdx.y;
+    const float *src = logits + (size_t)row * V;
+    const int base = sl * per, end = min(V, base + per);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float mv = -INFINITY;
+    int mi = 0x7fffffff;
+#pragma unroll 8
+    for (int v = base + threadIdx.x; v < end; v += 256) {
+        const float x = src[v];
+        if (x > mv) { mv = x; mi = v; }                     // ascending per thread: first maximum kept
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(mv, off);
+        const int oi = __shfl_xor(mi, off);
+        if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+    }
+    if (lane == 0) { s_m[wave] = mv; s_i[wave] = mi; }
+    __syncthreads();
+    mv = s_m[0];
+    mi = s_i[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) {
+        const float ov = s_m[i];
+        const int oi = s_i[i];
+        if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+    }
+    float sv = 0.f;
+#pragma unroll 8
+    for (int v = base + threadIdx.x; v < end; v += 256) sv += exp_scaled(src[v], mv, inv_temp);   // (L2 hits)
+    sv = wave_sum(sv);
+    if (lane == 0) s_s[wave] = sv;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        SliceStats o;
+        o.mx = mv;
+        o.idx = mi;
+        o.sum = ((s_s[0] + s_s[1]) + s_s[2]) + s_s[3];
+        o.pad = 0;
+        stats[(size_t)row * gridDim.y + sl] = o;
+    }
 }
 
 // Per-row results of the parallel first phase
@@ -199,7 +282,8 @@ struct RowInfo {
 // One workgroup per branch.  Phase 1: the (up to 16) target rows of the branch are handled concurrently, each
 // by a group of 16 / rows wavefronts: softmax statistics (or argmax in greedy mode), p(x) and the accept test.
 // Phase 2: the whole workgroup draws the replacement / bonus token for the one row that needs it.
-__global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a) {
+__global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a, const SliceStats *stats,
+                                                                int n_slices) {
     __shared__ Shared sm;
     __shared__ RowInfo ri;
     const int b = blockIdx.x;
@@ -219,7 +303,14 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         // pass 1: maximum (and its lowest index) of the row
         float mv = -INFINITY;
         int mi = 0x7fffffff;
-        if (has_row && (is_logits || a.greedy)) {
+        if (stats != nullptr) {
+            // the slices' statistics are there already: slices ascend, so the first maximum has the lowest index
+            if (has_row) {
+                const SliceStats *st = stats + ((size_t)b * Tp + r0 + r) * n_slices;
+                for (int i = 0; i < n_slices; ++i)
+                    if (st[i].mx > mv) { mv = st[i].mx; mi = st[i].idx; }
+            }
+        } else if (has_row && (is_logits || a.greedy)) {
 #pragma unroll 8
             for (int v = sub * 64 + lane; v < V; v += wpr * 64) {
                 const float x = src[v];
@@ -246,7 +337,13 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         __syncthreads();
         // pass 2: sum of exp((x - max) / temperature)
         float sv = 0.f;
-        if (has_row && is_logits && !a.greedy) {
+        if (stats != nullptr) {
+            if (has_row && sub == 0 && is_logits && !a.greedy) {
+                const SliceStats *st = stats + ((size_t)b * Tp + r0 + r) * n_slices;
+                const float inv_t = 1.0f / a.temperature;
+                for (int i = 0; i < n_slices; ++i) sv += st[i].sum * exp_scaled(st[i].mx, mv, inv_t);   // fixed order
+            }
+        } else if (has_row && is_logits && !a.greedy) {
             const float inv_t = 1.0f / a.temperature;
 #pragma unroll 8
             for (int v = sub * 64 + lane; v < V; v += wpr * 64) sv += exp_scaled(src[v], mv, inv_t);
@@ -353,9 +450,26 @@ __global__ __launch_bounds__(kBlock) void sample_probs_kernel(const float *probs
 
 }  // namespace
 
-int launch_accept(const seed_accept_args &a, hipStream_t st) {
+size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices * sizeof(SliceStats); }
+
+// scratch (optional, accept_scratch_bytes(n_branches * n_target_rows) bytes): with it the softmax statistics
+// of the rows are computed by a launch that fills the chip; without it inside the one workgroup per branch.
+int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
     if (a.n_branches == 0) return SEED_OK;
-    hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a);
+    const bool need_stats = a.probs_kind == SEED_KIND_LOGITS || a.greedy;
+    SliceStats *stats = nullptr;
+    int n_slices = 0;
+    if (scratch != nullptr && need_stats) {
+        const int rows = a.n_branches * a.n_target_rows;
+        n_slices = rows <= 32 ? 16 : (rows <= 64 ? 8 : 4);
+        while (n_slices > 1 && a.vocab / n_slices < 256) n_slices /= 2;
+        const int per = (((a.vocab + n_slices - 1) / n_slices) + 63) & ~63;
+        n_slices = (a.vocab + per - 1) / per;
+        stats = (SliceStats *)scratch;
+        hipLaunchKernelGGL(row_stats_kernel, dim3(rows, n_slices), dim3(256), 0, st, a.p_or_logits, a.vocab, per,
+                           a.greedy ? 1.0f : 1.0f / a.temperature, stats);
+    }
+    hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, stats, n_slices);
     return hip_fail(hipGetLastError(), "accept_resample launch");
 }
 

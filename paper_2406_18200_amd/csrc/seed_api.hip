@@ -43,7 +43,7 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, k_new, v_new, o_part, ml_part, logits, status;
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, k_new, v_new, o_part, ml_part, logits, acc_stats, status;
     int n_pos;
     size_t part_floats;
     size_t total;
@@ -158,6 +158,7 @@ Layout make_layout(const seed_model_cfg &c) {
     L.o_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * HD * 4 : 256);
     L.ml_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * H * 2 * 4 : 256);
     L.logits = take((size_t)L.M_cap * V * 4);
+    L.acc_stats = take(accept_scratch_bytes(L.M_cap));
     L.status = take(256);
     L.total = off;
     return L;
@@ -540,7 +541,7 @@ int seed_verify_profile_read(seed_ctx *c, int64_t *launches, double *total_ms, d
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     int rc = check_accept_args(args);
     if (rc) return rc;
-    return launch_accept(*args, (hipStream_t)hip_stream);
+    return launch_accept(*args, nullptr, (hipStream_t)hip_stream);
 }
 
 int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out, int32_t n_rows,
@@ -604,7 +605,7 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
     float *logits = want_logits ? (a->logits_out ? a->logits_out : (float *)at(c, c->L.logits)) : nullptr;
     int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, logits);
     if (rc) return rc;
-    if (a->accept != nullptr) return launch_accept(acc, c->stream);
+    if (a->accept != nullptr) return launch_accept(acc, at(c, c->L.acc_stats), c->stream);
     if (a->flags & SEED_STEP_COMMIT_ALL) return launch_add_len(a->private_len, N, T, c->stream);
     return SEED_OK;
 }

@@ -10,7 +10,8 @@ void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
 
 // ---- accept.hip ------------------------------------------------------------------------------
-int launch_accept(const seed_accept_args &a, hipStream_t st);
+size_t accept_scratch_bytes(int max_rows);
+int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st);   // scratch may be NULL
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, hipStream_t st);
