@@ -24,6 +24,7 @@
 //     both; emits the packed activation of the down projection).  The RMSNorm factor 1/rms of the input rows
 //     is applied AFTER the contraction: each consuming workgroup sums the producer's per-tile sums of squares
 //     in a fixed order at its start, while its first weight loads are already in flight.
+#include <type_traits>
 #include "seed_internal.h"
 #include "device_utils.h"
 
@@ -204,37 +205,46 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     }
     constexpr int OU = S::OU;
     const int n_outer = (k1 - k0 + OU * XKT - 1) / (OU * XKT);
-    for (int it = 0; it < n_outer; ++it) {
+    // one staged chunk: XG weight groups against the activations in LDS.  LAST (the final chunk of this
+    // workgroup's k range, peeled below) requests nothing that would never be used: the loads would only be
+    // waited for at the barrier after the loop.
+    auto chunk = [&](int kx, int oc, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
+        lds_barrier();                                    // the previous chunk is no longer read
+        store_x(kx);
+        lds_barrier();
+        if (!LAST) load_x(kx + XKT);
 #pragma unroll
-        for (int oc = 0; oc < OU; ++oc) {
-            const int kx = k0 + (it * OU + oc) * XKT;
-            lds_barrier();                                // the previous chunk is no longer read
-            store_x(kx);
-            lds_barrier();
-            load_x(kx + XKT);
+        for (int gq = 0; gq < XG; ++gq) {
+            const int dd = (oc * XG + gq) % D;            // OU * XG is a multiple of D: the slot is static
+            const int kc = kx + gq * KC;
+            if (LAST && kc >= k1) break;                  // (uniform) the k range ends inside this chunk
 #pragma unroll
-            for (int gq = 0; gq < XG; ++gq) {
-                constexpr int kRing = D;                   // OU * XG is a multiple of D: the slot is static
-                const int dd = (oc * XG + gq) % kRing;
-                const int kc = kx + gq * KC;
+            for (int u = 0; u < U; ++u) {
+                bf16x8 bh[TM], bl[TM];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    bf16x8 bh[TM], bl[TM];
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-                        bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
-                        bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
-                    }
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
-                        }
+                for (int tm = 0; tm < TM; ++tm) {
+                    bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
+                    bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
                 }
-                load_a(ring[dd], kc + D * KC);            // refill this slot D groups ahead (clamped)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
+                    }
             }
+            if (!LAST || gq + D < XG) load_a(ring[dd], kc + D * KC);   // refill this slot D groups ahead (clamped)
+        }
+    };
+    if constexpr (OU == 1) {
+        for (int it = 0; it < n_outer - 1; ++it) chunk(k0 + it * XKT, 0, std::false_type{});
+        if (n_outer > 0) chunk(k0 + (n_outer - 1) * XKT, 0, std::true_type{});
+    } else {
+        for (int it = 0; it < n_outer; ++it) {
+#pragma unroll
+            for (int oc = 0; oc < OU; ++oc) chunk(k0 + (it * OU + oc) * XKT, oc, std::false_type{});
         }
     }
     if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
@@ -398,7 +408,9 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         set_error("gemm: workgroup shape %dx%d does not fit %d row tiles", WN, WK, TM);
         return SEED_E_CAPACITY;
     } else {
-        constexpr int KC = S::OU * S::XG * S::KC;          // splits cover whole unrolled rounds of staged chunks
+        // splits are as even as k-tiles allow (a ragged last chunk stops at the first group past its range);
+        // only the unrolled-rounds form (a chunk smaller than the weight ring) needs whole rounds
+        constexpr int KC = S::OU > 1 ? S::OU * S::XG * S::KC : 1;
         GemmArgs b = a;
         b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
         b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
@@ -467,16 +479,18 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
     }
 }
 
-// Workgroup shape and split from a sweep on MI355X over the 7B / 13B projection shapes at 12, 40 and 96
-// rows: wide outputs share activation fragments across wavefronts (WN), narrow outputs split K inside the
-// workgroup (WK) and, when that still leaves CUs idle, across two or four workgroups.
+// Workgroup shape and split from sweeps on MI355X over the 7B / 13B projection shapes at 12, 24, 40 and 96
+// rows: wide outputs share activation fragments across wavefronts (WN); narrow outputs split K inside the
+// workgroup (WK), over all eight wavefronts when that gives one workgroup per CU without a split across
+// workgroups (no partials to exchange), else over four with two workgroups along K.
 void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk) {
     *sk = 1;
     if (m_tiles <= 2) {
-        *tn = epi == EPI_SWIGLU ? 2 : 1;
+        *tn = (epi == EPI_SWIGLU || (NT >= 1300 && NT % 2 == 0)) ? 2 : 1;
         const int units = NT / *tn;                        // n-tile groups a wavefront owns one of
         if (units >= 600) { *wn = 4; *wk = 2; }
-        else { *wn = 2; *wk = 4; *sk = 2; }
+        else if (m_tiles == 1 && NT <= 256) { *wn = 1; *wk = 8; }
+        else { *wn = 2; *wk = 4; *sk = NT <= 256 ? 2 : 1; }
     } else {
         *tn = 2;
         if (NT >= 1300) { *wn = 4; *wk = 2; }
