@@ -42,8 +42,6 @@ struct AttnParams {
     const uint16_t *k_priv;   // [Nmax][H][cap_p][DH]
     const uint16_t *vt_priv;  // [Nmax][H][DH][cap_p]
     const int32_t *private_len;
-    const float *k_new;       // [M][H*DH] fp32: rotated keys of this step's rows (in flight)
-    const float *v_new;       // [M][H*DH] fp32: values of this step's rows
     float *o_part;            // [P][Mq][H][DH]
     float *ml_part;           // [P][Mq][H][2]
     // single-launch form only:
@@ -53,7 +51,7 @@ struct AttnParams {
     int *counters;            // [H] arrival counters, zero on entry and left zero
     uint16_t *act;            // merged output, fragment-packed hi/lo activation of the O projection
     int32_t *status;
-    int Mp, n_inflight_wgs;
+    int Mp;
     int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
@@ -361,50 +359,10 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 
 // In-flight segment: row j of a branch against rows 0..j of the same branch (the causal part of the tree
 // mask).  At most T keys per row, so it runs in plain fp32 on the vector ALUs from unrounded keys / values:
-// the rows of one step see each other unrounded, while the cache keeps bf16.
-// One wavefront per (row, head); lanes own DH/64 dims; dot products are wavefront-shuffle reductions.
-template <int DH>
-__device__ void inflight_task(const AttnParams &P, int itask) {
-    constexpr int PER = DH / 64;
-    const int lane = threadIdx.x & 63;
-    const int r = itask / P.H, h = itask - r * P.H;
-    if (r >= P.M) return;
-    const int b = r / P.T, j = r - b * P.T;
-    const int HD = P.H * DH;
-    float qv[PER], o[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const size_t e = (size_t)r * HD + h * DH + lane * PER + i;
-        qv[i] = bf2f(P.q[e]) + bf2f(P.q[e + P.q_plane]);
-        o[i] = 0.f;
-    }
-    float m = -INFINITY, l = 0.f;
-    for (int jj = 0; jj <= j; ++jj) {
-        const size_t e = (size_t)(b * P.T + jj) * HD + h * DH + lane * PER;
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) s = fmaf(qv[i], P.k_new[e + i], s);
-        s = wave_reduce_sum(s) * P.scale_log2e;
-        const float m_new = fmaxf(m, s);
-        const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
-        l = l * alpha + p;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) o[i] = o[i] * alpha + p * P.v_new[e + i];
-        m = m_new;
-    }
-    const int part = P.ks_shared + P.ks_priv;
-    float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) op[i] = o[i];
-    if (lane == 0) {
-        float *mp = P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2;
-        mp[0] = m;
-        mp[1] = l;
-    }
-}
-
-// The same segment in the single-launch form: q and the keys are rotated on the fly from the fp32 QKV
-// output, and the wavefront of row r appends that row's rotated key and its value to the private cache.
+// the rows of one step see each other unrounded, while the cache keeps bf16.  One wavefront per (row, head);
+// lanes own DH/64 dims; dot products are wavefront-shuffle reductions.  q and the keys are rotated on the
+// fly from the fp32 QKV output, and the wavefront of row r appends that row's rotated key and its value to
+// the private cache.
 template <int DH>
 __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     constexpr int PER = DH / 64, HALF = DH / 2;
@@ -495,7 +453,7 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
     const int lane = threadIdx.x & 63;
     const int KT = (H * DH) >> 5;
     constexpr int PER = DH / 64;     // output dims per lane
-    constexpr int NPB = 8;
+    constexpr int NPB = 6;                               // partials per pass (register budget of the fused kernel)
     auto ld = [](const float *p) { return ACROSS ? load_agent(p) : *p; };
     auto ld2 = [](const float *p, float &x, float &y) {      // two adjacent floats, 8-byte aligned
         if (ACROSS) {
@@ -567,20 +525,20 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
 }
 
 template <int DH, bool FUSED, int RT>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
+__global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
     // then in-flight tasks, one (row, head) per wavefront
     // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
-                 "s"(P.private_len), "s"(P.k_new), "s"(P.v_new), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
+                 "s"(P.private_len), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
                  "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
-    asm volatile("" ::"s"(P.Mp), "s"(P.n_inflight_wgs), "s"(P.merge_in_launch), "s"(P.M), "s"(P.Mq), "s"(P.N),
+    asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.M), "s"(P.Mq), "s"(P.N),
                  "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
                  "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.ks_priv), "s"(P.groups_priv),
                  "s"(P.scale_log2e));
     const int task = blockIdx.x;
     const int n_shared = P.H * P.n_groups * P.ks_shared;
-    const int n_priv = P.prefill_shared ? 0 : P.N * P.H * P.groups_priv * P.ks_priv;
+    const int wv = threadIdx.x >> 6;
     int h;
     if (task < n_shared) {
         const int ks = task % P.ks_shared;
@@ -593,35 +551,32 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnParams P) {
         attn_task<DH, FUSED, RT>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                              P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
-    } else if (task - n_shared < n_priv) {
-        const int ptask = task - n_shared;
-        const int ks = ptask % P.ks_priv;
-        const int grp = (ptask / P.ks_priv) % P.groups_priv;
-        h = (ptask / (P.ks_priv * P.groups_priv)) % P.H;
-        const int b = ptask / (P.ks_priv * P.groups_priv * P.H);
-        const int pl = clamped_private_len(P, b);       // committed private context; in-flight rows are separate
-        const int kbeg = ks * P.keys_per_range;
-        const int kend = min(pl, kbeg + P.keys_per_range);
-        const int row_first = b * P.T;
-        // every row of the branch sees all pl committed private keys
-        attn_task<DH, FUSED, RT>(P, h, row_first + grp * 16 * RT, row_first + P.T,
-                             P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
-                             P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend), pl,
-                             row_first, 0, P.ks_shared + ks);
     } else {
-        const int itask = task - n_shared - n_priv;
-        if (FUSED) {                                      // workgroup = (head, four consecutive rows)
-            h = itask % P.H;
-            inflight_task_fused<DH>(P, h, (itask / P.H) * 4 + (threadIdx.x >> 6));
-        } else {
-            h = 0;
-            if (!P.prefill_shared) inflight_task<DH>(P, itask * 4 + (threadIdx.x >> 6));
+        // branch task (verify / decode only): one key range of the branch's private context for one group of
+        // its rows; the task of range 0 also runs the in-flight segment of those rows, a wavefront per row
+        const int ptask = task - n_shared;
+        const int nr = max(P.ks_priv, 1);
+        const int ks = ptask % nr;
+        const int grp = (ptask / nr) % P.groups_priv;
+        h = (ptask / (nr * P.groups_priv)) % P.H;
+        const int b = ptask / (nr * P.groups_priv * P.H);
+        const int row_first = b * P.T + grp * 16 * RT, row_end = min((b + 1) * P.T, row_first + 16 * RT);
+        if (P.ks_priv > 0) {
+            const int pl = clamped_private_len(P, b);   // committed private context
+            const int kbeg = ks * P.keys_per_range;
+            const int kend = min(pl, kbeg + P.keys_per_range);
+            // every row of the branch sees all pl committed private keys
+            attn_task<DH, FUSED, RT>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
+                                 P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
+                                 pl, b * P.T, 0, P.ks_shared + ks);
         }
+        if (FUSED && ks == 0)
+            for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH>(P, h, r);
     }
-    if (FUSED && P.merge_in_launch) {
+    if constexpr (FUSED && RT == 1) {
         // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
         __shared__ int s_last;
-        const int expected = P.n_groups * P.ks_shared + P.N * P.groups_priv * P.ks_priv + P.n_inflight_wgs;
+        const int expected = P.n_groups * P.ks_shared + P.N * P.groups_priv * max(P.ks_priv, 1);
         if (!arrive_last(P.counters + h, expected, &s_last)) return;
         const int np = P.ks_shared + P.ks_priv + 1;
         for (int r = threadIdx.x >> 6; r < P.Mp; r += 16)     // rows r, r+4, r+8, r+12 per pass
@@ -673,8 +628,6 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.k_priv_w = (uint16_t *)a.k_priv;
     P.vt_priv_w = (uint16_t *)a.vt_priv;
     P.private_len = a.private_len;
-    P.k_new = a.k_new;
-    P.v_new = a.v_new;
     P.o_part = a.o_part;
     P.ml_part = a.ml_part;
     P.qkv = a.qkv;
@@ -693,17 +646,16 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.groups_priv = (a.T + 16 * rt - 1) / (16 * rt);
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)a.dh);
     const bool fused = !a.prefill_shared;
-    // in-flight workgroups: single launch (head, four rows); prefill has none
-    P.n_inflight_wgs = fused ? (a.M + 3) / 4 : 0;
     const int blocks = a.H * P.n_groups * a.ks_shared +
-                       (fused ? a.N * a.H * P.groups_priv * a.ks_priv + P.n_inflight_wgs * a.H : 0);
+                       (fused ? a.N * a.H * P.groups_priv * (a.ks_priv > 0 ? a.ks_priv : 1) : 0);
     if (a.dh != 128 && a.dh != 64) {
         set_error("bf16 attention supports head_dim 64 or 128, got %d", a.dh);
         return SEED_E_SHAPE;
     }
-    // up to 32 rows the last workgroup of a head merges them in one or two passes; more rows would queue up
-    // behind its four wavefronts, so they get a merge launch with a wavefront per (row, head)
-    P.merge_in_launch = fused && a.Mp <= 32;
+    // up to 16 rows the last workgroup of a head merges them in one pass; more rows would queue up behind its
+    // four wavefronts (and the merge's registers would cost the two-row-tile kernel its second workgroup per
+    // CU), so they get a merge launch with a wavefront per (row, head)
+    P.merge_in_launch = fused && rt == 1;
     const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
 #define SEEDV_ATTN(DHv, FUSEDv, RTv) \
     hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, RTv>), dim3(blocks), dim3(256), 0, st, P)

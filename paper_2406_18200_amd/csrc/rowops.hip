@@ -143,7 +143,7 @@ __global__ void rope_table_kernel(float *table, int n_pos, int half, int dh, flo
 template <bool BF16>
 __global__ __launch_bounds__(64) void rope_kv_kernel(const float *__restrict__ qkv, const float *__restrict__ table,
                                                      void *q_out, size_t q_plane, void *k_shared, void *v_shared,
-                                                     void *k_priv, void *v_priv, float *k_new, float *v_new,
+                                                     void *k_priv, void *v_priv,
                                                      const int32_t *private_len, int M, int T, int H, int dh, int S,
                                                      int prefill_shared, int cap_shared, int cap_priv,
                                                      int max_private, int32_t *status) {
@@ -193,12 +193,6 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(const float *__restrict__ q
             uint16_t *q16 = reinterpret_cast<uint16_t *>(q_out);
             split_bf16(qa, q16[qo], q16[qo + q_plane]);              // q = hi + lo planes
             split_bf16(qb, q16[qo + half], q16[qo + half + q_plane]);
-            if (!prefill_shared) {                                   // unrounded copy for the in-flight segment
-                k_new[qo] = ka;
-                k_new[qo + half] = kb;
-                v_new[qo] = v1;
-                v_new[qo + half] = v2;
-            }
             if (store_kv) {
                 uint16_t *kc = reinterpret_cast<uint16_t *>(prefill_shared ? k_shared : k_priv);
                 uint16_t *vc = reinterpret_cast<uint16_t *>(prefill_shared ? v_shared : v_priv);
@@ -297,16 +291,16 @@ int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, vo
 }
 
 int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
-                   void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
+                   void *k_shared, void *v_shared, void *k_priv, void *v_priv,
                    const int32_t *private_len, int M, int Mq, int T, int H, int dh, int S, int prefill_shared,
                    int cap_shared, int cap_priv, int max_private, int32_t *status, hipStream_t st) {
     if (bf16)
         hipLaunchKernelGGL(rope_kv_kernel<true>, dim3(Mq, H), dim3(64), 0, st, qkv, rope_table, q_out, q_plane,
-                           k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S,
+                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S,
                            prefill_shared, cap_shared, cap_priv, max_private, status);
     else
         hipLaunchKernelGGL(rope_kv_kernel<false>, dim3(Mq, H), dim3(64), 0, st, qkv, rope_table, q_out, q_plane,
-                           k_shared, v_shared, k_priv, v_priv, k_new, v_new, private_len, M, T, H, dh, S,
+                           k_shared, v_shared, k_priv, v_priv, private_len, M, T, H, dh, S,
                            prefill_shared, cap_shared, cap_priv, max_private, status);
     return hip_fail(hipGetLastError(), "rope_kv launch");
 }

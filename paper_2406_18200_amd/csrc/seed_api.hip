@@ -43,7 +43,7 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, k_new, v_new, o_part, ml_part, logits, acc_stats, status;
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, o_part, ml_part, logits, acc_stats, status;
     int n_pos;
     size_t part_floats;
     size_t total;
@@ -153,8 +153,6 @@ Layout make_layout(const seed_model_cfg &c) {
     L.n_pos = c.max_shared + c.max_private + c.max_rows_per_branch + 1;
     L.rope = take((size_t)L.n_pos * dh * 4);
     L.q = take((size_t)L.Mq_cap * HD * 4);   // bf16 path: hi and lo planes
-    L.k_new = take((size_t)L.M_cap * HD * 4);
-    L.v_new = take((size_t)L.M_cap * HD * 4);
     L.o_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * HD * 4 : 256);
     L.ml_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * H * 2 * 4 : 256);
     L.logits = take((size_t)L.M_cap * V * 4);
@@ -312,9 +310,8 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         const KvPtrs kv = kv_layer(c, l);
         if (prefill_shared) {
             rc = launch_rope_kv(true, (const float *)at(c, L.qkv), (const float *)at(c, L.rope), at(c, L.q), q_plane,
-                                kv.ks, kv.vs, kv.kp, kv.vp, (float *)at(c, L.k_new), (float *)at(c, L.v_new),
-                                private_len, M, Mq, T, H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private,
-                                status, st);
+                                kv.ks, kv.vs, kv.kp, kv.vp, private_len, M, Mq, T, H, dh, S, prefill_shared, L.cap_s,
+                                L.cap_p, g.max_private, status, st);
             if (rc) return rc;
         }
         AttnBf16Args at_{};
@@ -323,7 +320,6 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         at_.qkv = (const float *)at(c, L.qkv); at_.rope = (const float *)at(c, L.rope);
         at_.k_shared = kv.ks; at_.vt_shared = kv.vs; at_.k_priv = kv.kp; at_.vt_priv = kv.vp;
         at_.private_len = private_len;
-        at_.k_new = (const float *)at(c, L.k_new); at_.v_new = (const float *)at(c, L.v_new);
         at_.o_part = (float *)at(c, L.o_part); at_.ml_part = (float *)at(c, L.ml_part);
         at_.counters = (int *)at(c, L.attn_counters);
         at_.act = at(c, L.act_hd);
@@ -389,8 +385,8 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
         rc = gemm(layer_w(c, l, L.w_qkv), 3 * HD, d, act_d, part, 3 * HD);
         if (rc) return rc;
         const KvPtrs kv = kv_layer(c, l);
-        rc = launch_rope_kv(false, part, (const float *)at(c, L.rope), at(c, L.q), 0, kv.ks, kv.vs, kv.kp, kv.vp, nullptr,
-                            nullptr, private_len, M, M, T, H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private,
+        rc = launch_rope_kv(false, part, (const float *)at(c, L.rope), at(c, L.q), 0, kv.ks, kv.vs, kv.kp, kv.vp,
+                            private_len, M, M, T, H, dh, S, prefill_shared, L.cap_s, L.cap_p, g.max_private,
                             status, st);
         if (rc) return rc;
         rc = launch_attn_f32(at(c, L.q), kv.ks, kv.vs, kv.kp, kv.vp, private_len, (float *)act_hd, M, T, H, dh, S,

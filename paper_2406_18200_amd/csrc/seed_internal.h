@@ -55,7 +55,7 @@ int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void
                       float *ssq, int M, int d, hipStream_t st);
 int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t st);
 int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
-                   void *k_shared, void *v_shared, void *k_priv, void *v_priv, float *k_new, float *v_new,
+                   void *k_shared, void *v_shared, void *k_priv, void *v_priv,
                    const int32_t *private_len, int M, int Mq,
                    int T, int H, int dh, int S, int prefill_shared, int cap_shared, int cap_priv,
                    int max_private, int32_t *status, hipStream_t st);
@@ -75,7 +75,6 @@ struct AttnBf16Args {
     const void *k_shared, *vt_shared;
     void *k_priv, *vt_priv;
     const int32_t *private_len;
-    const float *k_new, *v_new;
     float *o_part, *ml_part;
     int *counters;
     void *act;
