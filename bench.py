@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per projection launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy
 # kernel of known size); see profiles/.  None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c3": 107.2e6}     # profiles/gemm_kernel_c3.md: 2 x 51,707 KiB fetched + 1,265 KiB written
+MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6}     # profiles/gemm_kernel_c3.md: 2 x 51,667 KiB fetched + 521 KiB written
 
 
 def algorithmic_bytes(w):
@@ -222,7 +222,7 @@ def main():
                  "useful_tflops": flops / (ms_per_step * 1e-3) / 1e12,
                  "mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                  "accepted_tokens": accepted, "wall_ms_per_step": wall_ms / args.steps},
-        "roofline": {"bound": "hbm", "kernel": "gemm_ws_kernel (weight-streaming projection)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming projection)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                      "launches_per_step": launches / args.steps,
