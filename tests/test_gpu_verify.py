@@ -22,11 +22,23 @@ def test_c1_greedy():
     Case(wl.get_workload("c1"), greedy=True).run_oracle().run_gpu().compare()
 
 
-@pytest.mark.parametrize("N,gamma,S,R", [(3, 4, 100, 0), (5, 3, 70, 9), (16, 6, 257, 40), (1, 1, 33, 0)])
+@pytest.mark.parametrize("N,gamma,S,R", [(3, 4, 100, 0), (5, 3, 70, 9), (16, 6, 257, 40), (1, 1, 33, 0),
+                                         (2, 5, 1100, 300),   # <= 16 rows, 13 partials: in-launch merge in passes
+                                         (1, 40, 64, 20),     # one branch of 40 rows: two row groups per branch
+                                         (3, 7, 200, 150)])   # 21 rows (two row tiles), two private key ranges
 def test_small_bf16_synthetic_kv(N, gamma, S, R):
-    """Small bf16 model (2 layers, d=256, 4 heads of 64): several MFMA tiles, ragged tails in rows and keys."""
+    """Small bf16 model (2 layers, d=256, 4 heads of 64): several MFMA tiles, ragged tails in rows and keys,
+    and every shape of the attention launch (one / two row tiles, merge inside / after the launch, several
+    key ranges in the shared and the private segment, several row groups per branch)."""
     w = wl.get_workload("c3").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
                                      N=N, gamma=gamma, S=S, R=R, seed=77 + N)
+    Case(w).run_oracle().run_gpu().compare()
+
+
+def test_small_bf16_head128_long_private_context():
+    """head_dim 128, 12 rows against 1000 shared and 260 private keys (three private key ranges)."""
+    w = wl.get_workload("c3").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,
+                                     N=3, gamma=4, S=1000, R=260, seed=93)
     Case(w).run_oracle().run_gpu().compare()
 
 
