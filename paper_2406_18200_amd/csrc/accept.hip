@@ -303,12 +303,30 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         // pass 1: maximum (and its lowest index) of the row
         float mv = -INFINITY;
         int mi = 0x7fffffff;
+        float slice_sum = 0.f;
         if (stats != nullptr) {
-            // the slices' statistics are there already: slices ascend, so the first maximum has the lowest index
+            // the slices' statistics are there already: lane i takes slice i (one load per lane instead of a
+            // chain of them); slices ascend, so the lowest lane holding the maximum has the lowest index
             if (has_row) {
                 const SliceStats *st = stats + ((size_t)b * Tp + r0 + r) * n_slices;
-                for (int i = 0; i < n_slices; ++i)
-                    if (st[i].mx > mv) { mv = st[i].mx; mi = st[i].idx; }
+                float lm = -INFINITY;
+                int li = 0x7fffffff;
+                if (lane < n_slices) {
+                    const SliceStats e = st[lane];
+                    lm = e.mx;
+                    li = e.idx;
+                    slice_sum = e.sum;
+                }
+                mv = lm;
+                mi = li;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const float ov = __shfl_xor(mv, off);
+                    const int oi = __shfl_xor(mi, off);
+                    if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+                }
+                // this lane's slice, rescaled to the row maximum (0 for lanes without a slice)
+                slice_sum = lane < n_slices ? slice_sum * exp_scaled(lm, mv, a.greedy ? 1.0f : 1.0f / a.temperature) : 0.f;
             }
         } else if (has_row && (is_logits || a.greedy)) {
 #pragma unroll 8
@@ -338,11 +356,8 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
         // pass 2: sum of exp((x - max) / temperature)
         float sv = 0.f;
         if (stats != nullptr) {
-            if (has_row && sub == 0 && is_logits && !a.greedy) {
-                const SliceStats *st = stats + ((size_t)b * Tp + r0 + r) * n_slices;
-                const float inv_t = 1.0f / a.temperature;
-                for (int i = 0; i < n_slices; ++i) sv += st[i].sum * exp_scaled(st[i].mx, mv, inv_t);   // fixed order
-            }
+            if (has_row && sub == 0 && is_logits && !a.greedy)
+                for (int i = 0; i < n_slices; ++i) sv += __shfl(slice_sum, i);          // fixed order
         } else if (has_row && is_logits && !a.greedy) {
             const float inv_t = 1.0f / a.temperature;
 #pragma unroll 8
