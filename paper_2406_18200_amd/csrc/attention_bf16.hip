@@ -52,6 +52,7 @@ struct AttnParams {
     uint16_t *act;            // merged output, fragment-packed hi/lo activation of the O projection
     int32_t *status;
     int Mp;
+    int wave_tasks;           // shared tasks are per wavefront (several row groups), see attn_task
     int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
@@ -59,7 +60,8 @@ struct AttnParams {
     int cap_s, cap_p, max_private;
     int n_groups;             // query-row groups of the shared pass (32 rows each; 16 when M <= 16)
     int ks_shared;            // key ranges of the shared pass
-    int keys_per_range;       // multiple of 32
+    int keys_per_range;       // shared ranges: multiple of 32
+    int keys_per_range_priv;  // private ranges: multiple of 128
     int ks_priv;              // key ranges of the private pass (0 in prefill)
     int groups_priv;          // row groups of one branch
     float scale_log2e;
@@ -131,9 +133,14 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
     }
 }
 
-// RT = 16-row tiles of queries per task (1 when the step has at most 16 rows: half the registers, so two
-// workgroups share a CU).
-template <int DH, bool FUSED, int RT>
+// One task: RT 16-row tiles of queries against the keys [kbeg, kend) of one segment.
+//   WAVE = false: the four wavefronts of the workgroup interleave the 32-key chunks of the range and merge
+//                 through LDS into one partial (every barrier is reached by all four).
+//   WAVE = true:  the calling wavefront walks the whole range alone and writes its partial straight from the
+//                 MFMA accumulators (no LDS, no barrier): used when a step has several row groups, where the
+//                 wavefronts of a workgroup take different row groups of the SAME key range, so that the range
+//                 comes from HBM once and from the CU's L1 for the others.
+template <int DH, bool FUSED, int RT, bool WAVE>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part) {
@@ -146,7 +153,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     // 16-key tiles x KS k-steps; V^T[d = dt*16 + col][keys c + 8g .. +8].  The first chunk is requested before
     // anything else and chunk i+1 while chunk i is computed: their addresses depend on nothing loaded here.
     const int krow = 8 * (col >> 2) + (col & 3);   // key (within the chunk) of A-operand row `col`, tile 0
-    const int wv = threadIdx.x >> 6;               // the 4 wavefronts of the workgroup interleave chunks
+    const int wv = threadIdx.x >> 6;               // (WAVE = false) the 4 wavefronts interleave chunks
     auto load_kv = [&](int c, bf16x8 (&kf)[2][KS], bf16x8 (&vf)[DT]) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -157,7 +164,8 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         for (int dt = 0; dt < DT; ++dt)
             vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
     };
-    const int c0 = kbeg + 32 * wv;
+    const int c0 = WAVE ? kbeg : kbeg + 32 * wv;
+    constexpr int CSTEP = WAVE ? 32 : 128;
     // Issue order: the private lengths (oldest, so they can be waited for alone), the K / V chunk, the raw q
     // values; straight-line code, or the compiler drains the load queue at the join of a branch.  Rows past the
     // task's rows are clamped to a valid row and masked later.
@@ -208,12 +216,12 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         m_run[t] = -INFINITY;
         l_run[t] = 0.f;
     }
-    for (int c = c0; c < kend; c += 128) {
+    for (int c = c0; c < kend; c += CSTEP) {
         // one row tile: the next chunk is requested while this one is computed (two row tiles have no
         // registers to spare for that at two workgroups per CU)
         bf16x8 kf_next[2][KS], vf_next[DT];
-        const bool more = c + 128 < kend;             // (uniform)
-        if (RT == 1 && more) load_kv(c + 128, kf_next, vf_next);
+        const bool more = c + CSTEP < kend;           // (uniform)
+        if (RT == 1 && more) load_kv(c + CSTEP, kf_next, vf_next);
         f32x4 s[2][RT];                             // [key tile][row tile]
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
@@ -278,7 +286,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
                 o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
             }
         }
-        if (RT != 1 && more) load_kv(c + 128, kf_next, vf_next);
+        if (RT != 1 && more) load_kv(c + CSTEP, kf_next, vf_next);
         if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -287,6 +295,25 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) vf[dt] = vf_next[dt];
         }
+    }
+    if constexpr (WAVE) {
+        // the wavefront's own partial, straight from the accumulators: lane (col, g) holds dims dt*16 + 4g .. +4
+        // of row t*16 + col.  (Plain stores: the merge is a later launch in this mode.)
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            float l = l_run[t];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const int r = row0 + t * 16 + col;
+            if (r < rows_hi) {
+                const size_t base = ((size_t)part * P.Mq + r) * P.H + h;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+                    *reinterpret_cast<f32x4 *>(P.o_part + base * DH + dt * 16 + 4 * g) = o[dt][t];
+                if (g == 0) *reinterpret_cast<float2 *>(P.ml_part + base * 2) = make_float2(m_run[t], l);
+            }
+        }
+        return;
     }
     // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
     // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
@@ -532,14 +559,32 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
                  "s"(P.private_len), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
                  "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
-    asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.M), "s"(P.Mq), "s"(P.N),
+    asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.wave_tasks), "s"(P.M), "s"(P.Mq), "s"(P.N),
                  "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
-                 "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.ks_priv), "s"(P.groups_priv),
+                 "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.keys_per_range_priv), "s"(P.ks_priv), "s"(P.groups_priv),
                  "s"(P.scale_log2e));
     const int task = blockIdx.x;
-    const int n_shared = P.H * P.n_groups * P.ks_shared;
     const int wv = threadIdx.x >> 6;
+    // shared segment: (head, row group, key range) tasks, one per workgroup, or, when the step has several
+    // row groups, one per WAVEFRONT with the row group fastest (neighbours share their key range)
+    const int n_shared_tasks = P.H * P.n_groups * P.ks_shared;
+    const int n_shared = P.wave_tasks ? (n_shared_tasks + 3) / 4 : n_shared_tasks;
     int h;
+    if (task < n_shared && P.wave_tasks) {
+        const int wt = task * 4 + wv;
+        if (wt < n_shared_tasks) {
+            const int grp = wt % P.n_groups;
+            const int ks = (wt / P.n_groups) % P.ks_shared;
+            h = wt / (P.n_groups * P.ks_shared);
+            const int total = P.prefill_shared ? P.S + P.M : P.S;
+            const int kbeg = ks * P.keys_per_range;
+            const int kend = min(total, kbeg + P.keys_per_range);
+            attn_task<DH, FUSED, RT, true>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+                                           P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
+                                           P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
+        }
+        return;                                           // (the merge is a launch of its own in this mode)
+    }
     if (task < n_shared) {
         const int ks = task % P.ks_shared;
         const int grp = (task / P.ks_shared) % P.n_groups;
@@ -548,7 +593,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
-        attn_task<DH, FUSED, RT>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+        attn_task<DH, FUSED, RT, false>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                              P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
     } else {
@@ -563,17 +608,17 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int row_first = b * P.T + grp * 16 * RT, row_end = min((b + 1) * P.T, row_first + 16 * RT);
         if (P.ks_priv > 0) {
             const int pl = clamped_private_len(P, b);   // committed private context
-            const int kbeg = ks * P.keys_per_range;
-            const int kend = min(pl, kbeg + P.keys_per_range);
+            const int kbeg = ks * P.keys_per_range_priv;
+            const int kend = min(pl, kbeg + P.keys_per_range_priv);
             // every row of the branch sees all pl committed private keys
-            attn_task<DH, FUSED, RT>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
+            attn_task<DH, FUSED, RT, false>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
                                  P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
                                  pl, b * P.T, 0, P.ks_shared + ks);
         }
         if (FUSED && ks == 0)
             for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH>(P, h, r);
     }
-    if constexpr (FUSED && RT == 1) {
+    if (FUSED && RT == 1 && P.merge_in_launch) {
         // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
         __shared__ int s_last;
         const int expected = P.n_groups * P.ks_shared + P.N * P.groups_priv * max(P.ks_priv, 1);
@@ -595,26 +640,37 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
 
 }  // namespace
 
-// Number of partial slots per (row, head) for a given configuration; also fills the split parameters.
-void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
-                    int *ks_shared, int *keys_per_range, int *ks_priv) {
-    // aim for ~512 workgroups of four wavefronts; a key range is a multiple of 128 keys (one 32-key chunk per
-    // wavefront and round), at least 128 keys
-    const int n_groups = (Mq + 31) / 32;
+// Key ranges of the shared and the private segment for a step of M rows (T per branch).
+// One row group (M <= 16): workgroup tasks, ranges of whole 128-key rounds (a 32-key chunk per wavefront and
+// round), about 512 workgroups.  Several row groups: wavefront tasks, ranges of whole 32-key chunks, about
+// 2048 of them (two workgroups of four per CU).  Private ranges are always walked by workgroups.
+void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
+                    int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv) {
+    const int n_groups = (M + 15) / 16;
+    const int unit = n_groups == 1 ? 128 : 32;
+    int units = (total_shared_keys + unit - 1) / unit;
+    if (units < 1) units = 1;
     const int base_tasks = H * n_groups;
-    const int want = (512 + base_tasks - 1) / base_tasks;
-    int rounds = (total_shared_keys + 127) / 128;      // 128-key rounds in the shared segment
-    if (rounds < 1) rounds = 1;
-    int ks = want < rounds ? want : rounds;
+    const int want = ((n_groups == 1 ? 512 : 2048) + base_tasks - 1) / base_tasks;
+    int ks = want < units ? want : units;
     if (ks < 1) ks = 1;
     if (ks > 32) ks = 32;
-    const int per = ((rounds + ks - 1) / ks) * 128;
-    ks = (rounds * 128 + per - 1) / per;
-    *ks_shared = ks;
-    *keys_per_range = per;
-    *ks_priv = (prefill_shared || cap_priv_keys <= 0) ? 0 : (cap_priv_keys + per - 1) / per;
-    (void)N;
-    (void)T;
+    const int per_units = (units + ks - 1) / ks;
+    *ks_shared = (units + per_units - 1) / per_units;
+    *keys_per_range = per_units * unit;
+    if (prefill_shared || cap_priv_keys <= 0) {
+        *ks_priv = 0;
+        *keys_per_range_priv = 128;
+    } else {
+        const int rounds = (cap_priv_keys + 127) / 128;
+        int kp = 512 / (N * H > 0 ? N * H : 1);
+        if (kp < 1) kp = 1;
+        if (kp > rounds) kp = rounds;
+        if (kp > 32) kp = 32;
+        const int per_rounds = (rounds + kp - 1) / kp;
+        *ks_priv = (rounds + per_rounds - 1) / per_rounds;
+        *keys_per_range_priv = per_rounds * 128;
+    }
 }
 
 int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
@@ -638,36 +694,36 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.M = a.M; P.Mp = a.Mp; P.Mq = a.Mq; P.N = a.N; P.T = a.T; P.H = a.H; P.S = a.S;
     P.prefill_shared = a.prefill_shared;
     P.cap_s = a.cap_s; P.cap_p = a.cap_p; P.max_private = a.max_private;
-    const int rt = a.M <= 16 ? 1 : 2;                     // 16-row query tiles per task
+    constexpr int rt = 1;                                 // 16-row query tiles per task
     P.n_groups = (a.M + 16 * rt - 1) / (16 * rt);
+    P.wave_tasks = P.n_groups > 1;
+    P.keys_per_range_priv = a.keys_per_range_priv;
     P.ks_shared = a.ks_shared;
     P.keys_per_range = a.keys_per_range;
     P.ks_priv = a.ks_priv;
     P.groups_priv = (a.T + 16 * rt - 1) / (16 * rt);
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)a.dh);
     const bool fused = !a.prefill_shared;
-    const int blocks = a.H * P.n_groups * a.ks_shared +
+    const int n_shared_tasks = a.H * P.n_groups * a.ks_shared;
+    const int blocks = (P.wave_tasks ? (n_shared_tasks + 3) / 4 : n_shared_tasks) +
                        (fused ? a.N * a.H * P.groups_priv * (a.ks_priv > 0 ? a.ks_priv : 1) : 0);
     if (a.dh != 128 && a.dh != 64) {
         set_error("bf16 attention supports head_dim 64 or 128, got %d", a.dh);
         return SEED_E_SHAPE;
     }
     // up to 16 rows the last workgroup of a head merges them in one pass; more rows would queue up behind its
-    // four wavefronts (and the merge's registers would cost the two-row-tile kernel its second workgroup per
-    // CU), so they get a merge launch with a wavefront per (row, head)
-    P.merge_in_launch = fused && rt == 1;
+    // four wavefronts, so they get a merge launch with a wavefront per (row, head)
+    P.merge_in_launch = fused && !P.wave_tasks;
     const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
-#define SEEDV_ATTN(DHv, FUSEDv, RTv) \
-    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, RTv>), dim3(blocks), dim3(256), 0, st, P)
+#define SEEDV_ATTN(DHv, FUSEDv) \
+    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, 1>), dim3(blocks), dim3(256), 0, st, P)
     if (a.dh == 128) {
-        if (fused) { if (rt == 1) SEEDV_ATTN(128, true, 1); else SEEDV_ATTN(128, true, 2); }
-        else { if (rt == 1) SEEDV_ATTN(128, false, 1); else SEEDV_ATTN(128, false, 2); }
+        if (fused) SEEDV_ATTN(128, true); else SEEDV_ATTN(128, false);
         if (!P.merge_in_launch)
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
                                a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);
     } else {
-        if (fused) { if (rt == 1) SEEDV_ATTN(64, true, 1); else SEEDV_ATTN(64, true, 2); }
-        else { if (rt == 1) SEEDV_ATTN(64, false, 1); else SEEDV_ATTN(64, false, 2); }
+        if (fused) SEEDV_ATTN(64, true); else SEEDV_ATTN(64, false);
         if (!P.merge_in_launch)
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
                                a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);

@@ -289,9 +289,9 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         return profiled(c, (double)Nout * K * 2.0, [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
     };
 
-    int ks_shared = 1, keys_per_range = 32, ks_priv = 0;
-    attn_bf16_plan(Mq, H, N, T, prefill_shared ? S + M : S, g.max_private, prefill_shared, &ks_shared, &keys_per_range,
-                   &ks_priv);
+    int ks_shared = 1, keys_per_range = 32, ks_priv = 0, keys_per_range_priv = 128;
+    attn_bf16_plan(M, H, N, prefill_shared ? S + M : S, g.max_private, prefill_shared, &ks_shared, &keys_per_range,
+                   &ks_priv, &keys_per_range_priv);
     if (ks_shared + ks_priv + 1 > kMaxAttnSlots) {
         set_error("attention plan needs %d partial slots (max %d)", ks_shared + ks_priv + 1, kMaxAttnSlots);
         return SEED_E_CAPACITY;
@@ -328,6 +328,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         at_.prefill_shared = prefill_shared;
         at_.cap_s = L.cap_s; at_.cap_p = L.cap_p; at_.max_private = g.max_private;
         at_.ks_shared = ks_shared; at_.keys_per_range = keys_per_range; at_.ks_priv = ks_priv;
+        at_.keys_per_range_priv = keys_per_range_priv;
         rc = launch_attn_bf16(at_, st);
         if (rc) return rc;
         GemmArgs o{};

@@ -63,8 +63,8 @@ int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int 
                      hipStream_t st);
 int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
-void attn_bf16_plan(int Mq, int H, int N, int T, int total_shared_keys, int cap_priv_keys, int prefill_shared,
-                    int *ks_shared, int *keys_per_range, int *ks_priv);
+void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
+                    int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv);
 // Verify / decode steps (prefill_shared == 0) run as one launch that reads qkv / rope directly, appends to the
 // private cache, sets status bit 0 on a private-length overflow and merges through `counters` (n_heads ints,
 // zero on entry, left zero); the shared-prefix prefill reads q (hi/lo planes) written by launch_rope_kv.
@@ -79,7 +79,8 @@ struct AttnBf16Args {
     int *counters;
     void *act;
     int32_t *status;
-    int M, Mp, Mq, N, T, H, S, prefill_shared, cap_s, cap_p, max_private, ks_shared, keys_per_range, ks_priv;
+    int M, Mp, Mq, N, T, H, S, prefill_shared, cap_s, cap_p, max_private, ks_shared, keys_per_range, ks_priv,
+        keys_per_range_priv;
 };
 int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st);
 // ---- fp32_path.hip -----------------------------------------------------------------------------------
