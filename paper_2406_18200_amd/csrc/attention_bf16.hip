@@ -38,9 +38,9 @@ struct AttnParams {
     const uint16_t *q;        // [2][Mq][H*DH] bf16: hi plane, then lo plane (q = hi + lo)
     size_t q_plane;           // elements between the planes
     const uint16_t *k_shared; // [H][cap_s][DH]
-    const uint16_t *vt_shared;// [H][DH][cap_s]
+    const uint16_t *vt_shared;// [H][cap_s/32][DH][32]  (vt_offset)
     const uint16_t *k_priv;   // [Nmax][H][cap_p][DH]
-    const uint16_t *vt_priv;  // [Nmax][H][DH][cap_p]
+    const uint16_t *vt_priv;  // [Nmax][H][cap_p/32][DH][32]
     const int32_t *private_len;
     float *o_part;            // [P][Mq][H][DH]
     float *ml_part;           // [P][Mq][H][2]
@@ -162,7 +162,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
                 kf[kt][ks] = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)(c + krow + 4 * kt) * DH + 8 * g + ks * 32);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(dt * 16 + col) * cap + c + 8 * g);
+            vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + vt_offset(dt * 16 + col, c + 8 * g, DH));
     };
     const int c0 = WAVE ? kbeg : kbeg + 32 * wv;
     constexpr int CSTEP = WAVE ? 32 : 128;
@@ -457,7 +457,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
                 for (int i = 0; i < PER; ++i) {
                     const int d = lane * PER + i;
                     P.k_priv_w[(head * P.cap_p + idx) * DH + d] = f2bf(kk[u][i]);
-                    P.vt_priv_w[(head * DH + d) * P.cap_p + idx] = f2bf(vv[u][i]);
+                    P.vt_priv_w[head * DH * P.cap_p + vt_offset(d, idx, DH)] = f2bf(vv[u][i]);
                 }
             }
         }

@@ -35,6 +35,14 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) 
     lo = f2bf(x - bf2f(hi));
 }
 
+// bf16 V cache of one head, "chunk-tiled transposed": [cap/32][dh][32 keys].  The attention kernel reads V^T
+// fragments (16 dims x 32 keys, 16 bytes per lane); with this order the 32-key chunk it works on is one
+// contiguous dh*64-byte block, like the matching K chunk ([cap][dh] row-major), instead of dh pieces of 64
+// bytes that lie 2*cap bytes apart.  cap is a multiple of 32.
+__device__ __host__ __forceinline__ size_t vt_offset(int d, int key, int dh) {
+    return ((size_t)(key >> 5) * dh + d) * 32 + (key & 31);
+}
+
 __device__ __forceinline__ float wave_reduce_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);

@@ -137,7 +137,8 @@ __global__ void rope_table_kernel(float *table, int n_pos, int half, int dh, flo
 
 // Rotate q and k of the new rows (pair (i, i + dh/2)), store q for the attention kernel and append k, v to
 // the KV cache.  One workgroup per (row, head).
-//   bf16: K cache [H][cap][dh], V cache transposed [H][dh][cap] (the attention kernel reads V^T fragments);
+//   bf16: K cache [H][cap][dh], V cache chunk-tiled transposed [H][cap/32][dh][32] (vt_offset: the attention
+//         kernel reads V^T fragments);
 //         q as hi/lo bf16 planes; an fp32 copy of the new k, v feeds the in-flight attention segment
 //   fp32: K and V caches [H][cap][dh], q fp32
 template <bool BF16>
@@ -199,8 +200,8 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(const float *__restrict__ q
                 const size_t head = prefill_shared ? (size_t)h : ((size_t)b * H + h);
                 kc[(head * cap + idx) * dh + i] = f2bf(ka);
                 kc[(head * cap + idx) * dh + i + half] = f2bf(kb);
-                vc[(head * dh + i) * cap + idx] = f2bf(v1);
-                vc[(head * dh + i + half) * cap + idx] = f2bf(v2);
+                vc[head * dh * cap + vt_offset(i, idx, dh)] = f2bf(v1);
+                vc[head * dh * cap + vt_offset(i + half, idx, dh)] = f2bf(v2);
             }
         } else {
             float *q32 = reinterpret_cast<float *>(q_out);
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t *__restri
 }
 
 // Import of externally produced KV: src [heads][len][dh] -> K cache [heads][cap][dh] and, for bf16,
-// V cache transposed [heads][dh][cap].
+// V cache chunk-tiled transposed [heads][cap/32][dh][32] (vt_offset).
 template <bool BF16, bool TRANSPOSE>
 __global__ void kv_import_kernel(const void *src, void *dst, int heads, int len, int dh, int cap) {
     const size_t n = (size_t)heads * len * dh;
@@ -255,7 +256,7 @@ __global__ void kv_import_kernel(const void *src, void *dst, int heads, int len,
         const size_t t = e / dh;
         const int tokn = t % len;
         const size_t h = t / len;
-        const size_t o = TRANSPOSE ? (h * dh + i) * cap + tokn : (h * cap + tokn) * dh + i;
+        const size_t o = TRANSPOSE ? h * dh * cap + vt_offset(i, tokn, dh) : (h * cap + tokn) * dh + i;
         if (BF16) reinterpret_cast<uint16_t *>(dst)[o] = reinterpret_cast<const uint16_t *>(src)[e];
         else reinterpret_cast<float *>(dst)[o] = reinterpret_cast<const float *>(src)[e];
     }
