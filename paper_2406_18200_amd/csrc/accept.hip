@@ -129,6 +129,14 @@ __device__ __forceinline__ unsigned long long to_fixed(float w) {
 
 // weight of token v: residual max(0, p - q) (one float32 subtraction) or p itself
 template <int RESIDUAL>
+__device__ __forceinline__ unsigned long long weight_of(float p, const float *q, int v) {
+    if (RESIDUAL) {
+        float r = __fsub_rn(p, q[v]);
+        return r > 0.f ? to_fixed(r) : 0ull;
+    }
+    return to_fixed(p);
+}
+template <int RESIDUAL>
 __device__ __forceinline__ unsigned long long weight_fixed(const TargetRow &row, const float *q, int v) {
     float p = row.p(v);
     if (RESIDUAL) {
@@ -144,15 +152,25 @@ __device__ __forceinline__ unsigned long long weight_fixed(const TargetRow &row,
 // use different ones: totals per wavefront segment with coalesced strided loads, then the one wavefront whose
 // segment holds the target walks it in blocks of 2048 tokens, 32 CONSECUTIVE tokens per lane (one batch of
 // loads, one wavefront scan over the lane sums, a register walk in the lane that holds the target).
+// store (optional): the row of probabilities is also written there, in the same pass that sums the weights.
 template <int RESIDUAL>
-__device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, Shared &sm) {
+__device__ int draw_fixed(const TargetRow &row, const float *q, float u, int V, Shared &sm, float *store = nullptr) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int per = (((V + kWaves - 1) / kWaves) + 63) & ~63;
     const int base = wave * per;
     const int end = min(V, base + per);
     unsigned long long local = 0;
+    if (store != nullptr) {
 #pragma unroll 16
-    for (int v = base + lane; v < end; v += 64) local += weight_fixed<RESIDUAL>(row, q, v);
+        for (int v = base + lane; v < end; v += 64) {
+            const float p = row.p(v);
+            store[v] = p;
+            local += weight_of<RESIDUAL>(p, q, v);
+        }
+    } else {
+#pragma unroll 16
+        for (int v = base + lane; v < end; v += 64) local += weight_fixed<RESIDUAL>(row, q, v);
+    }
     local = wave_sum_u64(local);
     __syncthreads();
     if (lane == 0) sm.tot[wave] = local;
@@ -434,20 +452,55 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
     }
 }
 
+// Draft side: q = softmax(logits / temperature) written out, one token drawn from it (or the argmax).
+// stats (optional): slice statistics of the rows from row_stats_kernel; without them the workgroup makes its
+// own two passes over the row.
 __global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
         const float *logits, int64_t logits_stride, float temperature, int greedy, const float *u,
-        float *q_out, int64_t q_stride, int32_t *tok_out, int64_t tok_stride, int32_t *private_len, int V) {
+        float *q_out, int64_t q_stride, int32_t *tok_out, int64_t tok_stride, int32_t *private_len, int V,
+        const SliceStats *stats, int n_slices) {
     __shared__ Shared sm;
     const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63;
     const float *src = logits + (size_t)b * logits_stride;
-    TargetRow row = make_row(src, 1, temperature, V, sm);
-    if (q_out != nullptr) {
-        float *dst = q_out + (size_t)b * q_stride;
-        for (int v = threadIdx.x; v < V; v += kBlock) dst[v] = row.p(v);
+    TargetRow row{src, 1, 0.f, 1.f, 1.f / temperature};
+    int best = -1;
+    if (stats != nullptr) {
+        // lane i takes slice i; slices ascend, so the lowest lane holding the maximum has the lowest index
+        float lm = -INFINITY, ls = 0.f;
+        int li = 0x7fffffff;
+        if (lane < n_slices) {
+            const SliceStats e = stats[(size_t)b * n_slices + lane];
+            lm = e.mx;
+            li = e.idx;
+            ls = e.sum;
+        }
+        float mv = lm;
+        int mi = li;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(mv, off);
+            const int oi = __shfl_xor(mi, off);
+            if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+        }
+        ls = lane < n_slices ? ls * exp_scaled(lm, mv, row.inv_temp) : 0.f;
+        float tot = 0.f;
+        for (int i = 0; i < n_slices; ++i) tot += __shfl(ls, i);          // fixed order
+        row.mx = mv;
+        row.inv_sum = 1.0f / tot;
+        best = mi;
+    } else {
+        row = make_row(src, 1, temperature, V, sm);
     }
+    float *dst = q_out != nullptr ? q_out + (size_t)b * q_stride : nullptr;
     int tok;
-    if (greedy) tok = block_argmax(src, V, sm);
-    else tok = draw_fixed<0>(row, nullptr, u[b], V, sm);
+    if (greedy) {
+        if (dst != nullptr)
+            for (int v = threadIdx.x; v < V; v += kBlock) dst[v] = row.p(v);
+        tok = best >= 0 ? best : block_argmax(src, V, sm);
+    } else {
+        tok = draw_fixed<0>(row, nullptr, u[b], V, sm, dst);
+    }
     if (threadIdx.x == 0) {
         tok_out[(size_t)b * tok_stride] = tok;
         if (private_len != nullptr) private_len[b] += 1;
@@ -465,6 +518,14 @@ __global__ __launch_bounds__(kBlock) void sample_probs_kernel(const float *probs
 
 }  // namespace
 
+// Number of vocabulary slices of the row statistics launch for a given number of rows, and a slice's length.
+static int stats_slices(int rows, int vocab, int *per) {
+    int n_slices = rows <= 32 ? 16 : (rows <= 64 ? 8 : 4);
+    while (n_slices > 1 && vocab / n_slices < 256) n_slices /= 2;
+    *per = (((vocab + n_slices - 1) / n_slices) + 63) & ~63;
+    return (vocab + *per - 1) / *per;
+}
+
 size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices * sizeof(SliceStats); }
 
 // scratch (optional, accept_scratch_bytes(n_branches * n_target_rows) bytes): with it the softmax statistics
@@ -476,10 +537,8 @@ int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
     int n_slices = 0;
     if (scratch != nullptr && need_stats) {
         const int rows = a.n_branches * a.n_target_rows;
-        n_slices = rows <= 32 ? 16 : (rows <= 64 ? 8 : 4);
-        while (n_slices > 1 && a.vocab / n_slices < 256) n_slices /= 2;
-        const int per = (((a.vocab + n_slices - 1) / n_slices) + 63) & ~63;
-        n_slices = (a.vocab + per - 1) / per;
+        int per;
+        n_slices = stats_slices(rows, a.vocab, &per);
         stats = (SliceStats *)scratch;
         hipLaunchKernelGGL(row_stats_kernel, dim3(rows, n_slices), dim3(256), 0, st, a.p_or_logits, a.vocab, per,
                            a.greedy ? 1.0f : 1.0f / a.temperature, stats);
@@ -488,12 +547,25 @@ int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
     return hip_fail(hipGetLastError(), "accept_resample launch");
 }
 
+// scratch (optional, accept_scratch_bytes(n_rows) bytes, rows contiguous: logits_stride == vocab): as in
+// launch_accept.
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
-                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, hipStream_t st) {
+                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
+                          hipStream_t st) {
     if (n_rows == 0) return SEED_OK;
+    SliceStats *stats = nullptr;
+    int n_slices = 0;
+    if (scratch != nullptr && logits_stride == vocab) {
+        int per;
+        n_slices = stats_slices(n_rows, vocab, &per);
+        stats = (SliceStats *)scratch;
+        hipLaunchKernelGGL(row_stats_kernel, dim3(n_rows, n_slices), dim3(256), 0, st, logits, vocab, per,
+                           1.0f / temperature, stats);
+    }
     hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_rows), dim3(kBlock), 0, st, logits, logits_stride,
-                       temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, vocab);
+                       temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, vocab, stats,
+                       n_slices);
     return hip_fail(hipGetLastError(), "softmax_sample launch");
 }
 

@@ -627,7 +627,7 @@ int seed_draft_step(seed_ctx *c, const seed_draft_args *a) {
     int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, logits);
     if (rc) return rc;
     return launch_softmax_sample(logits, g.vocab, a->temperature, greedy, a->u, a->q_out, a->q_stride, a->tok_out,
-                                 a->tok_stride, a->private_len, N, g.vocab, c->stream);
+                                 a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats), c->stream);
 }
 
 int seed_kv_load(seed_ctx *c, int32_t layer, const void *k_shared, const void *v_shared, int32_t shared_len,

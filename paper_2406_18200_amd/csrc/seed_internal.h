@@ -14,7 +14,8 @@ size_t accept_scratch_bytes(int max_rows);
 int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st);   // scratch may be NULL
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
-                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, hipStream_t st);
+                          int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
+                          hipStream_t st);   // scratch may be NULL
 int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
                         int n_rows, int vocab, hipStream_t st);
 
