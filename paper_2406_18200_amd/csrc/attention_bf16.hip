@@ -34,6 +34,8 @@
 namespace seedv {
 namespace {
 
+constexpr int kRowTiles = 1;   // 16-row query tiles per task
+
 struct AttnParams {
     const uint16_t *q;        // [2][Mq][H*DH] bf16: hi plane, then lo plane (q = hi + lo)
     size_t q_plane;           // elements between the planes
@@ -133,17 +135,20 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
     }
 }
 
-// One task: RT 16-row tiles of queries against the keys [kbeg, kend) of one segment.
+// One task: a tile of 16 query rows against the keys [kbeg, kend) of one segment.  (The loops over RT row
+// tiles are kept general; 32-row tasks were measured no faster: they leave no registers for the second K/V
+// buffer and halve the number of workgroups per CU.)
 //   WAVE = false: the four wavefronts of the workgroup interleave the 32-key chunks of the range and merge
 //                 through LDS into one partial (every barrier is reached by all four).
 //   WAVE = true:  the calling wavefront walks the whole range alone and writes its partial straight from the
 //                 MFMA accumulators (no LDS, no barrier): used when a step has several row groups, where the
 //                 wavefronts of a workgroup take different row groups of the SAME key range, so that the range
 //                 comes from HBM once and from the CU's L1 for the others.
-template <int DH, bool FUSED, int RT, bool WAVE>
+template <int DH, bool FUSED, bool WAVE>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part) {
+    constexpr int RT = kRowTiles;
     constexpr int KS = DH / 32;   // k-steps of the QK^T contraction
     constexpr int DT = DH / 16;   // d-tiles of the output
     const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
@@ -217,11 +222,10 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         l_run[t] = 0.f;
     }
     for (int c = c0; c < kend; c += CSTEP) {
-        // one row tile: the next chunk is requested while this one is computed (two row tiles have no
-        // registers to spare for that at two workgroups per CU)
+        // the next chunk is requested while this one is computed
         bf16x8 kf_next[2][KS], vf_next[DT];
         const bool more = c + CSTEP < kend;           // (uniform)
-        if (RT == 1 && more) load_kv(c + CSTEP, kf_next, vf_next);
+        if (more) load_kv(c + CSTEP, kf_next, vf_next);
         f32x4 s[2][RT];                             // [key tile][row tile]
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
@@ -286,7 +290,6 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
                 o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
             }
         }
-        if (RT != 1 && more) load_kv(c + CSTEP, kf_next, vf_next);
         if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -551,8 +554,9 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
     }
 }
 
-template <int DH, bool FUSED, int RT>
+template <int DH, bool FUSED>
 __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
+    constexpr int RT = kRowTiles;
     // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
     // then in-flight tasks, one (row, head) per wavefront
     // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
@@ -579,7 +583,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             const int total = P.prefill_shared ? P.S + P.M : P.S;
             const int kbeg = ks * P.keys_per_range;
             const int kend = min(total, kbeg + P.keys_per_range);
-            attn_task<DH, FUSED, RT, true>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+            attn_task<DH, FUSED, true>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                                            P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                                            P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
         }
@@ -593,7 +597,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
-        attn_task<DH, FUSED, RT, false>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+        attn_task<DH, FUSED, false>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                              P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
     } else {
@@ -611,14 +615,14 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             const int kbeg = ks * P.keys_per_range_priv;
             const int kend = min(pl, kbeg + P.keys_per_range_priv);
             // every row of the branch sees all pl committed private keys
-            attn_task<DH, FUSED, RT, false>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
+            attn_task<DH, FUSED, false>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
                                  P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
                                  pl, b * P.T, 0, P.ks_shared + ks);
         }
         if (FUSED && ks == 0)
             for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH>(P, h, r);
     }
-    if (FUSED && RT == 1 && P.merge_in_launch) {
+    if (FUSED && P.merge_in_launch) {
         // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
         __shared__ int s_last;
         const int expected = P.n_groups * P.ks_shared + P.N * P.groups_priv * max(P.ks_priv, 1);
@@ -694,7 +698,7 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.M = a.M; P.Mp = a.Mp; P.Mq = a.Mq; P.N = a.N; P.T = a.T; P.H = a.H; P.S = a.S;
     P.prefill_shared = a.prefill_shared;
     P.cap_s = a.cap_s; P.cap_p = a.cap_p; P.max_private = a.max_private;
-    constexpr int rt = 1;                                 // 16-row query tiles per task
+    constexpr int rt = kRowTiles;
     P.n_groups = (a.M + 16 * rt - 1) / (16 * rt);
     P.wave_tasks = P.n_groups > 1;
     P.keys_per_range_priv = a.keys_per_range_priv;
@@ -716,7 +720,7 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.merge_in_launch = fused && !P.wave_tasks;
     const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
 #define SEEDV_ATTN(DHv, FUSEDv) \
-    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, 1>), dim3(blocks), dim3(256), 0, st, P)
+    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv>), dim3(blocks), dim3(256), 0, st, P)
     if (a.dh == 128) {
         if (fused) SEEDV_ATTN(128, true); else SEEDV_ATTN(128, false);
         if (!P.merge_in_launch)
