@@ -40,8 +40,8 @@ template <int TM, int TN, int WN, int WK>
 struct Shape {
     static constexpr int kWaves = WN * WK;
     // k-tiles of staged activations (2 KiB per k-tile and row tile) that fit the LDS budget: 64 KiB for one or
-    // two row tiles, 96 KiB above (at most a workgroup or two per CU are resident anyway)
-    static constexpr int kBudget = TM <= 2 ? 32 / TM : 48 / TM;
+    // two row tiles (and for three or four with WK <= 2, measured: two workgroups per CU pay there), 96 KiB above
+    static constexpr int kBudget = (TM <= 2 || (WK <= 2 && TM <= 4)) ? 32 / TM : 48 / TM;
     static constexpr int kWant = TM <= 2 ? 4 : 2;                        // k-tiles per wavefront and group
     // largest U <= kWant that still lets two weight groups (prefetch depth 2) fit the staged chunk
     static constexpr int U = (2 * WK * kWant <= kBudget) ? kWant : ((2 * WK * 2 <= kBudget && kWant >= 2) ? 2 : 1);
@@ -495,7 +495,7 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
         *tn = 2;
         if (NT >= 1300) { *wn = 4; *wk = 2; }
         else if (NT >= 600) { *wn = 2; *wk = 4; }
-        else { *wn = 2; *wk = 4; *sk = m_tiles <= 4 ? 2 : 4; }
+        else { *wn = 2; *wk = 4; *sk = m_tiles <= 3 ? 2 : 4; }
     }
     if (KT < 64) *sk = 1;
 }
