@@ -54,7 +54,8 @@ struct AttnParams {
     uint16_t *act;            // merged output, fragment-packed hi/lo activation of the O projection
     int32_t *status;
     int Mp;
-    int wave_tasks;           // shared tasks are per wavefront (several row groups), see attn_task
+    int wave_tasks;           // several row groups: shared tasks are attn_task_lds workgroups
+    int gpw, n_quads;         // row groups per such workgroup (<= 4), workgroups per (head, key range)
     int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
@@ -135,6 +136,107 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
     }
 }
 
+// One 32-key chunk for the RT row tiles of a task: S^T = K.Q^T, online softmax, O^T += V^T.P^T.
+// kf / vf are the chunk's A operands (any source), c its first key.
+template <int DH>
+__device__ __forceinline__ void chunk_update(const bf16x8 (&kf)[2][DH / 32], const bf16x8 (&vf)[DH / 16],
+                                             const bf16x8 (&qf)[kRowTiles][DH / 32][2],
+                                             f32x4 (&o)[DH / 16][kRowTiles], float (&m_run)[kRowTiles],
+                                             float (&l_run)[kRowTiles], const int (&limit)[kRowTiles], int c,
+                                             int kend, float scale_log2e) {
+    constexpr int RT = kRowTiles, KS = DH / 32, DT = DH / 16;
+    const int g = (threadIdx.x & 63) >> 4;
+    f32x4 s[2][RT];                             // [key tile][row tile]
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][0], acc, 0, 0, 0);
+            }
+            s[kt][t] = acc;
+        }
+    }
+    bf16x8 pf[RT][2];  // [row tile][hi|lo]
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        // lane holds keys c + 8g + {0..3} (tile 0) and c + 8g + {4..7} (tile 1) of query row `col`
+        float sv[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int key = c + 8 * g + i;
+            float v = s[i >> 2][t][i & 3] * scale_log2e;
+            v = (key < limit[t] && key < kend) ? v : -INFINITY;
+            sv[i] = v;
+            mx = fmaxf(mx, v);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[t], mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
+        float psum = 0.f;
+        float pv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            pv[i] = __builtin_amdgcn_exp2f(sv[i] - m_use);
+            psum += pv[i];
+        }
+        l_run[t] = l_run[t] * alpha + psum;      // per-lane partial sum; groups are combined at the end
+        m_run[t] = m_new;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;
+        u32x4 wh, wl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint16_t h0, l0, h1, l1;
+            split_bf16(pv[2 * i], h0, l0);
+            split_bf16(pv[2 * i + 1], h1, l1);
+            wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        pf[t][0] = *reinterpret_cast<bf16x8 *>(&wh);
+        pf[t][1] = *reinterpret_cast<bf16x8 *>(&wl);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][1], o[dt][t], 0, 0, 0);
+            o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
+        }
+    }
+}
+
+// A wavefront's own partial, straight from the accumulators: lane (col, g) holds dims dt*16 + 4g .. +4 of row
+// t*16 + col.  (Plain stores: the merge is a later launch whenever this is used.)
+template <int DH>
+__device__ __forceinline__ void store_partial_direct(const AttnParams &P, int h, int row0, int rows_hi, int part,
+                                                     const f32x4 (&o)[DH / 16][kRowTiles],
+                                                     const float (&m_run)[kRowTiles],
+                                                     const float (&l_run)[kRowTiles]) {
+    constexpr int RT = kRowTiles, DT = DH / 16;
+    const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        float l = l_run[t];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int r = row0 + t * 16 + col;
+        if (r < rows_hi) {
+            const size_t base = ((size_t)part * P.Mq + r) * P.H + h;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                *reinterpret_cast<f32x4 *>(P.o_part + base * DH + dt * 16 + 4 * g) = o[dt][t];
+            if (g == 0) *reinterpret_cast<float2 *>(P.ml_part + base * 2) = make_float2(m_run[t], l);
+        }
+    }
+}
+
 // One task: a tile of 16 query rows against the keys [kbeg, kend) of one segment.  (The loops over RT row
 // tiles are kept general; 32-row tasks were measured no faster: they leave no registers for the second K/V
 // buffer and halve the number of workgroups per CU.)
@@ -147,7 +249,7 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
 template <int DH, bool FUSED, bool WAVE>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
-                          int inc, int part) {
+                          int inc, int part, char *smem) {
     constexpr int RT = kRowTiles;
     constexpr int KS = DH / 32;   // k-steps of the QK^T contraction
     constexpr int DT = DH / 16;   // d-tiles of the output
@@ -226,70 +328,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         bf16x8 kf_next[2][KS], vf_next[DT];
         const bool more = c + CSTEP < kend;           // (uniform)
         if (more) load_kv(c + CSTEP, kf_next, vf_next);
-        f32x4 s[2][RT];                             // [key tile][row tile]
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-            for (int t = 0; t < RT; ++t) {
-                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][1], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][ks], qf[t][ks][0], acc, 0, 0, 0);
-                }
-                s[kt][t] = acc;
-            }
-        }
-        bf16x8 pf[RT][2];  // [row tile][hi|lo]
-#pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            // lane holds keys c + 8g + {0..3} (tile 0) and c + 8g + {4..7} (tile 1) of query row `col`
-            float sv[8];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int key = c + 8 * g + i;
-                float v = s[i >> 2][t][i & 3] * P.scale_log2e;
-                v = (key < limit[t] && key < kend) ? v : -INFINITY;
-                sv[i] = v;
-                mx = fmaxf(mx, v);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[t], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
-            float psum = 0.f;
-            float pv[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                pv[i] = __builtin_amdgcn_exp2f(sv[i] - m_use);
-                psum += pv[i];
-            }
-            l_run[t] = l_run[t] * alpha + psum;      // per-lane partial sum; groups are combined at the end
-            m_run[t] = m_new;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;
-            u32x4 wh, wl;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint16_t h0, l0, h1, l1;
-                split_bf16(pv[2 * i], h0, l0);
-                split_bf16(pv[2 * i + 1], h1, l1);
-                wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-            }
-            pf[t][0] = *reinterpret_cast<bf16x8 *>(&wh);
-            pf[t][1] = *reinterpret_cast<bf16x8 *>(&wl);
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-            for (int t = 0; t < RT; ++t) {
-                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][1], o[dt][t], 0, 0, 0);
-                o[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[t][0], o[dt][t], 0, 0, 0);
-            }
-        }
+        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e);
         if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -300,28 +339,14 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         }
     }
     if constexpr (WAVE) {
-        // the wavefront's own partial, straight from the accumulators: lane (col, g) holds dims dt*16 + 4g .. +4
-        // of row t*16 + col.  (Plain stores: the merge is a later launch in this mode.)
-#pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            float l = l_run[t];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
-            const int r = row0 + t * 16 + col;
-            if (r < rows_hi) {
-                const size_t base = ((size_t)part * P.Mq + r) * P.H + h;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-                    *reinterpret_cast<f32x4 *>(P.o_part + base * DH + dt * 16 + 4 * g) = o[dt][t];
-                if (g == 0) *reinterpret_cast<float2 *>(P.ml_part + base * 2) = make_float2(m_run[t], l);
-            }
-        }
+        store_partial_direct<DH>(P, h, row0, rows_hi, part, o, m_run, l_run);
         return;
     }
     // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
     // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
-    __shared__ float sm_m[4][16 * RT], sm_l[4][16 * RT];
-    __shared__ float sm_o[4][16 * RT][DH + 4];
+    float (*sm_m)[16 * RT] = reinterpret_cast<float (*)[16 * RT]>(smem);
+    float (*sm_l)[16 * RT] = sm_m + 4;
+    float (*sm_o)[16 * RT][DH + 4] = reinterpret_cast<float (*)[16 * RT][DH + 4]>(sm_l + 4);
     float scale[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
@@ -385,6 +410,111 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
             if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2, mstar, L);
         }
     }
+}
+
+// Shared-segment task of a step with SEVERAL row groups: the workgroup walks one key range for up to four
+// row groups at once, a wavefront per group.  Every 32-key chunk is fetched from global memory ONCE per
+// workgroup (each thread a few 16-byte pieces, two chunks ahead in registers), stored to LDS in MFMA-fragment
+// order (two stages) and read from there by all wavefronts; one barrier per chunk.  The wavefronts write
+// their partials straight from the accumulators.  Wavefronts without a row group (n_grp < 4) only help load.
+template <int DH, bool FUSED>
+__device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, const uint16_t *kbase,
+                              const uint16_t *vtbase, int kbeg, int kend, int lim0, int inc, int part,
+                              char *smem) {
+    constexpr int RT = kRowTiles, KS = DH / 32, DT = DH / 16;
+    constexpr int PPT = (32 * DH / 8) / 256;       // 16-byte pieces of a K (or V) chunk per thread
+    static_assert(RT == 1 && PPT >= 1, "one row tile per wavefront; head_dim >= 64");
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, g = lane >> 4, col = lane & 15;
+    const bool active = wv < n_grp;
+    const int row0 = (grp0 + (active ? wv : 0)) * 16;
+    const int HD = P.H * DH;
+    bf16x8 (*kst)[2 * KS * 64] = reinterpret_cast<bf16x8 (*)[2 * KS * 64]>(smem);                       // [2]
+    bf16x8 (*vst)[DT * 64] = reinterpret_cast<bf16x8 (*)[DT * 64]>(smem + 2 * sizeof(bf16x8) * 2 * KS * 64);
+
+    // this thread's pieces: where they come from in the chunk and which fragment slot they fill.
+    // K chunk [32 keys][DH]: piece (key, dp) is lane (col, g) of fragment (kt, ks) with key = 8*(col/4) + col%4
+    // + 4*kt, dp = 4*ks + g.  V chunk [DH][32 keys] (chunk-tiled cache): piece (d, kp) is lane (d%16, kp) of
+    // fragment dt = d/16.
+    int k_src[PPT], k_dst[PPT], v_src[PPT], v_dst[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+        const int j = tid + 256 * i;
+        const int key = j / (DH / 8), dp = j % (DH / 8);
+        k_src[i] = key * DH + dp * 8;
+        k_dst[i] = ((((key >> 2) & 1) * KS + (dp >> 2)) * 64) + (dp & 3) * 16 + (((key >> 3) << 2) | (key & 3));
+        const int d = j >> 2, kp = j & 3;
+        v_src[i] = d * 32 + kp * 8;
+        v_dst[i] = (d >> 4) * 64 + kp * 16 + (d & 15);
+    }
+    const int nch = (kend - kbeg + 31) >> 5;        // chunks of the range
+    auto gload = [&](int i, bf16x8 (&kr)[PPT], bf16x8 (&vr)[PPT]) {
+        const int c = kbeg + 32 * max(min(i, nch - 1), 0);     // past the end: the last chunk again (dropped)
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            kr[u] = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)c * DH + k_src[u]);
+            vr[u] = *reinterpret_cast<const bf16x8 *>(vtbase + (size_t)(c >> 5) * DH * 32 + v_src[u]);
+        }
+    };
+    auto lstore = [&](int stage, const bf16x8 (&kr)[PPT], const bf16x8 (&vr)[PPT]) {
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            kst[stage][k_dst[u]] = kr[u];
+            vst[stage][v_dst[u]] = vr[u];
+        }
+    };
+
+    // issue order as in attn_task: private lengths, the first two chunks, the raw q values; no branches
+    const int qrow = min(row0 + col, P.M - 1);
+    RawQ<DH> qraw;
+    if (FUSED) qraw.pl = P.private_len[qrow / P.T];
+    bf16x8 kr0[PPT], vr0[PPT], kr1[PPT], vr1[PPT];
+    gload(0, kr0, vr0);
+    gload(1, kr1, vr1);
+    bf16x8 qf[RT][KS][2];
+    if (FUSED) {
+        load_q_raw<DH>(P, qrow, h, g, qraw);
+        __builtin_amdgcn_sched_barrier(0);
+        rotate_q<DH>(P, qrow, g, qraw, qf[0]);
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint16_t *qp = P.q + (size_t)min(row0 + col, P.Mq - 1) * HD + h * DH + ks * 32 + 8 * g;
+            qf[0][ks][0] = *reinterpret_cast<const bf16x8 *>(qp);
+            qf[0][ks][1] = *reinterpret_cast<const bf16x8 *>(qp + P.q_plane);
+        }
+    }
+    int limit[RT];
+    limit[0] = (active && row0 + col < P.M) ? lim0 + inc * (row0 + col) : 0;
+    f32x4 o[DT][RT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_run[RT] = {-INFINITY}, l_run[RT] = {0.f};
+
+    auto compute = [&](int stage, int c) {
+        bf16x8 kf[2][KS], vf[DT];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kst[stage][(kt * KS + ks) * 64 + lane];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = vst[stage][dt * 64 + lane];
+        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e);
+    };
+
+    lstore(0, kr0, vr0);
+    gload(2, kr0, vr0);
+    lds_barrier();
+    for (int i = 0; i < nch; i += 2) {
+        if (active) compute(0, kbeg + 32 * i);
+        lstore(1, kr1, vr1);                         // chunk i+1 (stage 1 was last read before the previous barrier)
+        gload(i + 3, kr1, vr1);
+        lds_barrier();
+        if (active && i + 1 < nch) compute(1, kbeg + 32 * (i + 1));
+        lstore(0, kr0, vr0);                         // chunk i+2
+        gload(i + 4, kr0, vr0);
+        lds_barrier();
+    }
+    if (active) store_partial_direct<DH>(P, h, row0, P.M, part, o, m_run, l_run);
 }
 
 // In-flight segment: row j of a branch against rows 0..j of the same branch (the causal part of the tree
@@ -563,30 +693,31 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
                  "s"(P.private_len), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
                  "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
-    asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.wave_tasks), "s"(P.M), "s"(P.Mq), "s"(P.N),
+    asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.wave_tasks), "s"(P.gpw), "s"(P.n_quads), "s"(P.M), "s"(P.Mq), "s"(P.N),
                  "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
                  "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.keys_per_range_priv), "s"(P.ks_priv), "s"(P.groups_priv),
                  "s"(P.scale_log2e));
+    // LDS: merge buffers of attn_task or the two K/V stages of attn_task_lds
+    constexpr int kMergeBytes = 2 * 4 * 16 * RT * 4 + 4 * 16 * RT * (DH + 4) * 4;
+    constexpr int kStageBytes = 2 * (2 * (DH / 32) + DH / 16) * 64 * 16;
+    __shared__ __attribute__((aligned(16))) char smem[kMergeBytes > kStageBytes ? kMergeBytes : kStageBytes];
     const int task = blockIdx.x;
     const int wv = threadIdx.x >> 6;
-    // shared segment: (head, row group, key range) tasks, one per workgroup, or, when the step has several
-    // row groups, one per WAVEFRONT with the row group fastest (neighbours share their key range)
-    const int n_shared_tasks = P.H * P.n_groups * P.ks_shared;
-    const int n_shared = P.wave_tasks ? (n_shared_tasks + 3) / 4 : n_shared_tasks;
+    // shared segment: (head, row group, key range) tasks, or, when the step has several row groups,
+    // (head, key range, up to four row groups) tasks that share the key range through LDS
+    const int n_shared = P.wave_tasks ? P.H * P.ks_shared * P.n_quads : P.H * P.n_groups * P.ks_shared;
     int h;
     if (task < n_shared && P.wave_tasks) {
-        const int wt = task * 4 + wv;
-        if (wt < n_shared_tasks) {
-            const int grp = wt % P.n_groups;
-            const int ks = (wt / P.n_groups) % P.ks_shared;
-            h = wt / (P.n_groups * P.ks_shared);
-            const int total = P.prefill_shared ? P.S + P.M : P.S;
-            const int kbeg = ks * P.keys_per_range;
-            const int kend = min(total, kbeg + P.keys_per_range);
-            attn_task<DH, FUSED, true>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
-                                           P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
-                                           P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
-        }
+        const int quad = task % P.n_quads;
+        const int ks = (task / P.n_quads) % P.ks_shared;
+        h = task / (P.n_quads * P.ks_shared);
+        const int total = P.prefill_shared ? P.S + P.M : P.S;
+        const int kbeg = ks * P.keys_per_range;
+        const int kend = min(total, kbeg + P.keys_per_range);
+        const int grp0 = quad * P.gpw;
+        attn_task_lds<DH, FUSED>(P, h, grp0, min(P.gpw, P.n_groups - grp0), P.k_shared + (size_t)h * P.cap_s * DH,
+                                 P.vt_shared + (size_t)h * DH * P.cap_s, kbeg, max(kbeg, kend),
+                                 P.prefill_shared ? P.S + 1 : P.S, P.prefill_shared ? 1 : 0, ks, smem);
         return;                                           // (the merge is a launch of its own in this mode)
     }
     if (task < n_shared) {
@@ -599,7 +730,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
         attn_task<DH, FUSED, false>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
-                             P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks);
+                             P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks, smem);
     } else {
         // branch task (verify / decode only): one key range of the branch's private context for one group of
         // its rows; the task of range 0 also runs the in-flight segment of those rows, a wavefront per row
@@ -617,7 +748,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             // every row of the branch sees all pl committed private keys
             attn_task<DH, FUSED, false>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
                                  P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
-                                 pl, b * P.T, 0, P.ks_shared + ks);
+                                 pl, b * P.T, 0, P.ks_shared + ks, smem);
         }
         if (FUSED && ks == 0)
             for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH>(P, h, r);
@@ -644,18 +775,20 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
 
 }  // namespace
 
-// Key ranges of the shared and the private segment for a step of M rows (T per branch).
-// One row group (M <= 16): workgroup tasks, ranges of whole 128-key rounds (a 32-key chunk per wavefront and
-// round), about 512 workgroups.  Several row groups: wavefront tasks, ranges of whole 32-key chunks, about
-// 2048 of them (two workgroups of four per CU).  Private ranges are always walked by workgroups.
+// Key ranges of the shared and the private segment for a step of M rows.
+// One row group (M <= 16): workgroup tasks whose four wavefronts interleave 32-key chunks: ranges of whole
+// 128-key rounds, about 512 workgroups.  Several row groups: workgroups that walk a range for up to four row
+// groups (attn_task_lds): ranges of an even number of 32-key chunks (chunks are processed in pairs), about 640
+// workgroups.  Private ranges are always of the first kind.
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv) {
     const int n_groups = (M + 15) / 16;
-    const int unit = n_groups == 1 ? 128 : 32;
+    const bool lds_tasks = n_groups > 1;
+    const int unit = lds_tasks ? 64 : 128;
     int units = (total_shared_keys + unit - 1) / unit;
     if (units < 1) units = 1;
-    const int base_tasks = H * n_groups;
-    const int want = ((n_groups == 1 ? 512 : 2048) + base_tasks - 1) / base_tasks;
+    const int base_tasks = lds_tasks ? H * ((n_groups + 3) / 4) : H;
+    const int want = ((lds_tasks ? 640 : 512) + base_tasks - 1) / base_tasks;
     int ks = want < units ? want : units;
     if (ks < 1) ks = 1;
     if (ks > 32) ks = 32;
@@ -701,6 +834,8 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     constexpr int rt = kRowTiles;
     P.n_groups = (a.M + 16 * rt - 1) / (16 * rt);
     P.wave_tasks = P.n_groups > 1;
+    P.n_quads = (P.n_groups + 3) / 4;
+    P.gpw = (P.n_groups + P.n_quads - 1) / P.n_quads;
     P.keys_per_range_priv = a.keys_per_range_priv;
     P.ks_shared = a.ks_shared;
     P.keys_per_range = a.keys_per_range;
@@ -708,8 +843,7 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.groups_priv = (a.T + 16 * rt - 1) / (16 * rt);
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)a.dh);
     const bool fused = !a.prefill_shared;
-    const int n_shared_tasks = a.H * P.n_groups * a.ks_shared;
-    const int blocks = (P.wave_tasks ? (n_shared_tasks + 3) / 4 : n_shared_tasks) +
+    const int blocks = (P.wave_tasks ? a.H * a.ks_shared * P.n_quads : a.H * P.n_groups * a.ks_shared) +
                        (fused ? a.N * a.H * P.groups_priv * (a.ks_priv > 0 ? a.ks_priv : 1) : 0);
     if (a.dh != 128 && a.dh != 64) {
         set_error("bf16 attention supports head_dim 64 or 128, got %d", a.dh);

@@ -93,4 +93,11 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_f
     return *s_flag != 0;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load of the wavefront (vmcnt(0)), which would drain a prefetch queue at each chunk; here only the LDS counter
+// is drained, global loads stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 }  // namespace seedv

@@ -65,13 +65,6 @@ __device__ __forceinline__ void pin_args(const GemmArgs &a) {
                  "s"(a.gain), "s"(a.act_out), "s"(a.KT_out), "s"(a.ssq), "s"(a.eps));
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
-// load of the wavefront (vmcnt(0)), which would drain the weight prefetch queue at each chunk; here only the
-// LDS counter is drained, the weight loads stay in flight across the barrier.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int KT, const float *v) {
     uint16_t hi[4], lo[4];
 #pragma unroll
