@@ -240,13 +240,10 @@ __device__ __forceinline__ void store_partial_direct(const AttnParams &P, int h,
 // One task: a tile of 16 query rows against the keys [kbeg, kend) of one segment.  (The loops over RT row
 // tiles are kept general; 32-row tasks were measured no faster: they leave no registers for the second K/V
 // buffer and halve the number of workgroups per CU.)
-//   WAVE = false: the four wavefronts of the workgroup interleave the 32-key chunks of the range and merge
-//                 through LDS into one partial (every barrier is reached by all four).
-//   WAVE = true:  the calling wavefront walks the whole range alone and writes its partial straight from the
-//                 MFMA accumulators (no LDS, no barrier): used when a step has several row groups, where the
-//                 wavefronts of a workgroup take different row groups of the SAME key range, so that the range
-//                 comes from HBM once and from the CU's L1 for the others.
-template <int DH, bool FUSED, bool WAVE>
+// The four wavefronts of the workgroup interleave the 32-key chunks of the range and merge through LDS into one
+// partial (every barrier is reached by all four).  Used for every task of a step with one row group and for
+// the private segment; the shared segment of steps with several row groups goes through attn_task_lds.
+template <int DH, bool FUSED>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part, char *smem) {
@@ -260,7 +257,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     // 16-key tiles x KS k-steps; V^T[d = dt*16 + col][keys c + 8g .. +8].  The first chunk is requested before
     // anything else and chunk i+1 while chunk i is computed: their addresses depend on nothing loaded here.
     const int krow = 8 * (col >> 2) + (col & 3);   // key (within the chunk) of A-operand row `col`, tile 0
-    const int wv = threadIdx.x >> 6;               // (WAVE = false) the 4 wavefronts interleave chunks
+    const int wv = threadIdx.x >> 6;               // the 4 wavefronts interleave chunks
     auto load_kv = [&](int c, bf16x8 (&kf)[2][KS], bf16x8 (&vf)[DT]) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -271,8 +268,8 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         for (int dt = 0; dt < DT; ++dt)
             vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + vt_offset(dt * 16 + col, c + 8 * g, DH));
     };
-    const int c0 = WAVE ? kbeg : kbeg + 32 * wv;
-    constexpr int CSTEP = WAVE ? 32 : 128;
+    const int c0 = kbeg + 32 * wv;
+    constexpr int CSTEP = 128;
     // Issue order: the private lengths (oldest, so they can be waited for alone), the K / V chunk, the raw q
     // values; straight-line code, or the compiler drains the load queue at the join of a branch.  Rows past the
     // task's rows are clamped to a valid row and masked later.
@@ -337,10 +334,6 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) vf[dt] = vf_next[dt];
         }
-    }
-    if constexpr (WAVE) {
-        store_partial_direct<DH>(P, h, row0, rows_hi, part, o, m_run, l_run);
-        return;
     }
     // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
     // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
@@ -728,7 +721,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
-        attn_task<DH, FUSED, false>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+        attn_task<DH, FUSED>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                              P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks, smem);
     } else {
@@ -746,7 +739,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             const int kbeg = ks * P.keys_per_range_priv;
             const int kend = min(pl, kbeg + P.keys_per_range_priv);
             // every row of the branch sees all pl committed private keys
-            attn_task<DH, FUSED, false>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
+            attn_task<DH, FUSED>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
                                  P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
                                  pl, b * P.T, 0, P.ks_shared + ks, smem);
         }
@@ -778,8 +771,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
 // Key ranges of the shared and the private segment for a step of M rows.
 // One row group (M <= 16): workgroup tasks whose four wavefronts interleave 32-key chunks: ranges of whole
 // 128-key rounds, about 512 workgroups.  Several row groups: workgroups that walk a range for up to four row
-// groups (attn_task_lds): ranges of an even number of 32-key chunks (chunks are processed in pairs), about 640
-// workgroups.  Private ranges are always of the first kind.
+// groups (attn_task_lds): ranges of an even number of 32-key chunks (chunks are processed in pairs), about 450
+// workgroups (flat between 256 and 640 in a sweep at the 7B / 13B shapes).  Private ranges are always of the first kind.
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv) {
     const int n_groups = (M + 15) / 16;
@@ -788,7 +781,7 @@ void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_key
     int units = (total_shared_keys + unit - 1) / unit;
     if (units < 1) units = 1;
     const int base_tasks = lds_tasks ? H * ((n_groups + 3) / 4) : H;
-    const int want = ((lds_tasks ? 640 : 512) + base_tasks - 1) / base_tasks;
+    const int want = ((lds_tasks ? 448 : 512) + base_tasks - 1) / base_tasks;
     int ks = want < units ? want : units;
     if (ks < 1) ks = 1;
     if (ks > 32) ks = 32;
