@@ -552,10 +552,11 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
         o[i] = 0.f;
     }
     float m = -INFINITY, l = 0.f;
-    for (int j0 = 0; j0 <= j; j0 += 4) {                // four keys per pass: their loads overlap
-        float kk[4][PER], vv[4][PER], sc[4];
+    constexpr int kB = 8;
+    for (int j0 = 0; j0 <= j; j0 += kB) {               // kB keys per pass: their loads overlap
+        float kk[kB][PER], vv[kB][PER], sc[kB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kB; ++u) {
             const int jj = min(j0 + u, j);
             const float *krow = P.qkv + (size_t)(b * P.T + jj) * 3 * HD + HD + h * DH;
             sc[u] = 0.f;
@@ -567,7 +568,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kB; ++u) {
             if (j0 + u > j) continue;
             const float s = wave_reduce_sum(sc[u]) * P.scale_log2e;
             const float m_new = fmaxf(m, s);
