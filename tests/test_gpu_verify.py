@@ -108,3 +108,88 @@ def test_empty_and_single_row_steps():
     assert c.ctx.step(empty, w.S, c.dev_plen) is None                   # N = 0: nothing launched, no error
     c.ctx.close()
     Case(w.scaled(N=1, gamma=1)).run_oracle().run_gpu().compare()
+
+
+def test_two_consecutive_steps_commit_and_reuse_the_cache():
+    """KV commit across steps (Algorithm 1: a branch's validated length grows by the accepted tokens plus the
+    replacement; the rows that verified them stay in its cache, the rejected rows are dead).  Step 1 is built so
+    that branch b accepts exactly b % (gamma + 1) drafts: q = the oracle's p with u = 0.5 where a draft is to be
+    accepted, q = one-hot on the draft with u = 0.999 where it is to be rejected.  Step 2 then feeds, per
+    branch, the token step 1 emitted last plus new drafts; its logits are checked against an oracle that
+    recomputes every branch from its TOKENS (prefix + private + the rows step 1 committed), so a wrong or stale
+    cache row, or a wrong committed length, shows up."""
+    import torch
+    import oracle
+    import workloads.device as D
+    from workloads import gen
+    from harness import check_logits
+    w = wl.get_workload("c2").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
+                                     N=7, gamma=4, S=90, R=5, seed=123)
+    m, G, N, T, dev = w.model, w.gamma, w.N, w.gamma, "cuda:0"
+    up = D.UploadingWeights(m, w.seed, dev, reuse_buffers=False)
+    prefix, private, pending = wl.prefix_tokens(w), gen.private_tokens(w), gen.pending_tokens(w)
+    rng = np.random.default_rng(5)
+    drafts1 = rng.integers(0, m.vocab, (N, G)).astype(np.int32)
+    rows1 = np.concatenate([pending[:, None], drafts1[:, :T - 1]], axis=1).astype(np.int32)
+    # oracle, step 1: context KV from tokens
+    _, ks, vs = oracle.decode_rows(m, up, prefix)
+    pk, pv = [], []
+    for b in range(N):
+        _, kb, vb = oracle.decode_rows(m, up, private[b], ctx_kv=lambda l: (ks[l], vs[l]), pos0=w.S)
+        pk.append(kb)
+        pv.append(vb)
+    ctx1 = lambda l: [(np.concatenate([ks[l], pk[b][l]], 1), np.concatenate([vs[l], pv[b][l]], 1)) for b in range(N)]
+    ref1 = oracle.verify_forward(m, up, rows1, ctx1, [w.S + w.R] * N)
+    p1 = oracle.softmax_temperature(ref1, w.temperature)
+    want_a = np.array([b % (G + 1) for b in range(N)])
+    q = np.zeros((N, G, m.vocab), np.float32)
+    u_acc = np.zeros((N, G), np.float32)
+    for b in range(N):
+        for j in range(G):
+            if j < want_a[b]:
+                q[b, j], u_acc[b, j] = p1[b, j], 0.5
+            else:
+                q[b, j, drafts1[b, j]], u_acc[b, j] = 1.0, 0.999
+    u_res = wl.uniform24(w.seed + 4, (N,), stream=1)
+    # library, step 1
+    ctx = D.make_context(m, up.upload_all(), max_branches=N, max_rows_per_branch=T, max_shared=w.S,
+                         max_private=w.R + 2 * T, device=dev)
+    plen = torch.zeros(N, dtype=torch.int32, device=dev)
+    ctx.prefill_shared(D.i32(prefix, dev))
+    for lo in range(0, w.R, T):
+        ctx.step(D.i32(private[:, lo:lo + T], dev).contiguous(), w.S, plen, flags=sv_flags().SEED_STEP_COMMIT_ALL)
+    acc = dict(q=D.f32(q, dev), draft_tok=D.i32(drafts1, dev), u_acc=D.f32(u_acc, dev), u_res=D.f32(u_res, dev),
+               temperature=w.temperature)
+    logits = torch.empty((N, T, m.vocab), dtype=torch.float32, device=dev)
+    a_g, out_g, n_g, _ = [o.cpu().numpy() for o in ctx.step(D.i32(rows1, dev), w.S, plen, logits_out=logits, accept=acc)]
+    worst, err = check_logits(logits.cpu().numpy(), ref1, m.dtype)
+    assert worst <= 1.0, (worst, err)
+    assert np.array_equal(a_g, want_a), (a_g, want_a)
+    commit = np.minimum(want_a + 1, T)
+    assert np.array_equal(plen.cpu().numpy(), w.R + commit)
+    # step 2: the pending token is the replacement (or, after gamma accepts, the last accepted draft)
+    pending2 = np.array([out_g[b, want_a[b]] if want_a[b] < G else drafts1[b, G - 1] for b in range(N)], np.int32)
+    assert (pending2 >= 0).all()
+    drafts2 = rng.integers(0, m.vocab, (N, G)).astype(np.int32)
+    rows2 = np.concatenate([pending2[:, None], drafts2[:, :T - 1]], axis=1).astype(np.int32)
+    logits2 = torch.empty((N, T, m.vocab), dtype=torch.float32, device=dev)
+    ctx.step(D.i32(rows2, dev), w.S, plen, logits_out=logits2)
+    torch.cuda.synchronize()
+    # oracle, step 2: each branch again from its tokens
+    pk2, pv2 = [], []
+    for b in range(N):
+        toks = np.concatenate([private[b], rows1[b, :commit[b]]])
+        _, kb, vb = oracle.decode_rows(m, up, toks, ctx_kv=lambda l: (ks[l], vs[l]), pos0=w.S)
+        pk2.append(kb)
+        pv2.append(vb)
+    ctx2 = lambda l: [(np.concatenate([ks[l], pk2[b][l]], 1), np.concatenate([vs[l], pv2[b][l]], 1)) for b in range(N)]
+    ref2 = oracle.verify_forward(m, up, rows2, ctx2, list(w.S + w.R + commit))
+    worst, err = check_logits(logits2.cpu().numpy(), ref2, m.dtype)
+    assert worst <= 1.0, (worst, err)
+    assert ctx.status() == 0
+    ctx.close()
+
+
+def sv_flags():
+    import paper_2406_18200_amd as sv
+    return sv.binding
