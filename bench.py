@@ -50,7 +50,7 @@ def useful_flops(w):
 
 
 def cpu_baseline(w, inp):
-    """Oracle on a bounded sample: same widths, N, gamma, S, R; 1 and 2 decoder layers; extrapolated."""
+    """Oracle on a bounded sample: same widths, N, gamma, S, R; 4 and 20 decoder layers; extrapolated."""
     import numpy as np
     import oracle
     import workloads as wl
@@ -59,33 +59,39 @@ def cpu_baseline(w, inp):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
+    # two depths of the same model (same widths, N, gamma, context), ~10 s of oracle arithmetic together
+    L_small, L_big = min(4, w.model.n_layers), min(20, w.model.n_layers)
+    wb = w.scaled(n_layers=L_big)
+    W = wl.Weights(wb.model, wb.seed)
+    cache = {"emb": W.tok_emb(), "nf": W.norm_final(), "lm": W.lm_head(),
+             "layers": [W.layer(l) for l in range(L_big)], "kv": [wl.synthetic_kv(wb, l) for l in range(L_big)]}
+
+    class Pre:       # pre-generated tensors: the timed region holds only the oracle's own arithmetic
+        tok_emb = staticmethod(lambda: cache["emb"])
+        norm_final = staticmethod(lambda: cache["nf"])
+        lm_head = staticmethod(lambda: cache["lm"])
+        layer = staticmethod(lambda l: cache["layers"][l])
+
+    def ctx(l):
+        k_s, v_s, k_p, v_p = cache["kv"][l]
+        return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in range(w.N)]
     times = {}
-    for L in (1, 2):
+    for L in sorted({L_small, L_big}):
         ws = w.scaled(n_layers=L)
-        W = wl.Weights(ws.model, ws.seed)
-        cache = {"emb": W.tok_emb(), "nf": W.norm_final(), "lm": W.lm_head(),
-                 "layers": [W.layer(l) for l in range(L)], "kv": [wl.synthetic_kv(ws, l) for l in range(L)]}
-
-        class Pre:       # pre-generated tensors: the timed region holds only the oracle's own arithmetic
-            tok_emb = staticmethod(lambda: cache["emb"])
-            norm_final = staticmethod(lambda: cache["nf"])
-            lm_head = staticmethod(lambda: cache["lm"])
-            layer = staticmethod(lambda l: cache["layers"][l])
-
-        def ctx(l):
-            k_s, v_s, k_p, v_p = cache["kv"][l]
-            return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in range(ws.N)]
         t0 = time.perf_counter()
         logits = oracle.verify_forward(ws.model, Pre, inp["row_tok"], ctx, [ws.S + ws.R] * ws.N)
         p = oracle.softmax_temperature(logits, ws.temperature)
         oracle.accept_resample(p, inp["q"], inp["drafts"], inp["u_acc"], inp["u_res"])
         times[L] = time.perf_counter() - t0
-    per_layer = max(times[2] - times[1], 1e-9)
-    fixed = max(times[1] - per_layer, 0.0)
+    if L_big > L_small:
+        per_layer = max((times[L_big] - times[L_small]) / (L_big - L_small), 1e-9)
+    else:
+        per_layer = times[L_big] / L_big
+    fixed = max(times[L_small] - per_layer * L_small, 0.0)
     full = fixed + per_layer * w.model.n_layers
     return {"value": w.N * w.gamma / full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"float64 numpy oracle, full widths/N/gamma/context, timed at 1 and 2 layers "
-                      f"({times[1]:.2f}s, {times[2]:.2f}s) + LM head + accept, extrapolated to "
+            "sample": f"float64 numpy oracle, full widths/N/gamma/context, timed at {L_small} and {L_big} layers "
+                      f"({times[L_small]:.2f}s, {times[L_big]:.2f}s) + LM head + accept, extrapolated to "
                       f"{w.model.n_layers} layers ({full:.1f}s per step)"}
 
 
