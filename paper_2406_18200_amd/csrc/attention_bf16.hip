@@ -6,25 +6,30 @@
 // and causally the in-flight rows 0..j of its own branch (the per-branch gamma-by-context causal mask;
 // the tree-attention idea of Section 2.2 / Appendix "Details of Tree Attention" at branch granularity).
 //
-// The shared segment is the bulk of the bytes; it is processed for ALL N*gamma rows of a head at once, so
+// The shared segment is the bulk of the bytes; it is processed for all N*gamma rows of a head together, so
 // each shared K/V byte is read from HBM once per step instead of once per branch.  Work is cut into
-// independent wavefront tasks (head, group of <= 32 query rows, key range); each task runs a
-// flash-decoding loop over 32-key chunks entirely in registers:
+// independent tasks (head, 16 query rows, key range of one segment); a task walks its range in 32-key chunks,
+// flash-decoding style, with everything but K and V in registers:
 //   S^T = K . Q^T          v_mfma_f32_16x16x32_bf16, A = K fragment (16 keys x 32 dims), B = Q fragment
 //   online softmax         per query row = per MFMA column: in-lane max/sum + two xor-shuffles across
 //                          the four 16-lane groups
-//   O^T += V^T . P^T       A = V^T fragment (16 dims x 32 keys; V is cached transposed so this is one
-//                          16-byte load per lane), B = P^T built in registers from the S^T accumulators
+//   O^T += V^T . P^T       A = V^T fragment (16 dims x 32 keys; V is cached transposed, chunk by chunk, so
+//                          this is one 16-byte load per lane), B = P^T built in registers from S^T
 // (q and P are carried as hi/lo bf16 pairs, two MFMAs each, so that rounding them does not dominate the
-// error of the attention output); the four wavefronts of a workgroup interleave the chunks of one task and
-// leave ONE unnormalised partial (max, sum, O) per (row, head, key range).  The partials of a (row, head) are
-// combined by log-sum-exp into the hi/lo bf16 activation tile of the O projection.
+// error of the attention output) and leaves an unnormalised partial (max, sum, O) per (row, head, key range);
+// the partials of a (row, head) are combined by log-sum-exp into the hi/lo bf16 activation tile of the O
+// projection.  Two forms of a task:
+//   attn_task      the four wavefronts of a workgroup interleave the chunks (K/V straight to registers, next
+//                  chunk in flight) and merge through LDS: steps of at most 16 rows, and every private segment;
+//   attn_task_lds  steps with several row groups: a workgroup walks one shared key range for up to four row
+//                  groups, a wavefront each; every chunk is fetched once, staged through LDS in fragment order.
 //
 // Verify / decode steps run everything in ONE launch: the tasks read q, k, v straight from the fp32 output
-// of the QKV projection and apply the rotary embedding on the fly (the in-flight tasks also append the
-// rotated keys and the values to the private cache), and the workgroup that finishes last for a head
-// (a per-head arrival counter) merges that head's partials.  The shared-prefix prefill keeps the three-launch
-// form (rotary + cache append, partials, merge): its rows read the keys of their own chunk from the cache.
+// of the QKV projection and apply the rotary embedding on the fly; the task of a branch's private segment
+// also runs its in-flight rows and appends their rotated keys and values to the private cache; with at most
+// 16 rows the workgroup that finishes last for a head (a per-head arrival counter) merges that head's
+// partials, otherwise a merge launch follows.  The shared-prefix prefill keeps the three-launch form (rotary
+// + cache append, partials, merge): its rows read the keys of their own chunk from the cache.
 //
 // The two S^T tiles of a 32-key chunk use the key order key = 8*(i/4) + (i%4) (+4 for the second tile),
 // which makes lane group g hold exactly keys 8g..8g+7 -- the B-operand layout the P.V MFMA wants.
@@ -681,8 +686,7 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
 template <int DH, bool FUSED>
 __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     constexpr int RT = kRowTiles;
-    // workgroup tasks: shared (head, row group, key range), private (branch, head, row group, key range);
-    // then in-flight tasks, one (row, head) per wavefront
+    // workgroup tasks: first the shared segment, then one per (branch, head, row group, private key range)
     // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
                  "s"(P.private_len), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),

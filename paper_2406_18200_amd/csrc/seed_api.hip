@@ -254,7 +254,8 @@ KvPtrs kv_layer(const seed_ctx *c, int l) {
             c->ws + L.vp + L.kp_stride * l};
 }
 
-// bf16 path: projections with fused epilogues (see gemm_bf16.hip); 7 launches per layer.
+// bf16 path: projections with fused epilogues (see gemm_bf16.hip); 5 launches per layer in a verify / decode
+// step (6 above 16 rows), 7 in the shared-prefix prefill.
 int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
                      const int32_t *private_len, float *logits) {
     const seed_model_cfg &g = c->cfg;
