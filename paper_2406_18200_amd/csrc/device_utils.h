@@ -70,14 +70,17 @@ __device__ __forceinline__ void load2_agent(const float *p, float &x, float &y) 
     x = __uint_as_float((uint32_t)w);
     y = __uint_as_float((uint32_t)(w >> 32));
 }
+// four adjacent floats (16-byte aligned) as two 64-bit accesses
 __device__ __forceinline__ void store4_agent(float *p, const f32x4 &v) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    store2_agent(p, v[0], v[1]);
+    store2_agent(p + 2, v[2], v[3]);
 }
 __device__ __forceinline__ f32x4 load4_agent(const float *p) {
     f32x4 v;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float a, b, c, e;
+    load2_agent(p, a, b);
+    load2_agent(p + 2, c, e);
+    v[0] = a; v[1] = b; v[2] = c; v[3] = e;
     return v;
 }
 // all of this workgroup's earlier stores have completed; returns true in the workgroup that arrives last
