@@ -596,8 +596,12 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     }
     const int part = P.ks_shared + P.ks_priv;
     float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
+    if (PER == 2) {
+        store2_agent(op, o[0], o[PER - 1]);
+    } else {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
+        for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
+    }
     if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2, m, l);
 }
 

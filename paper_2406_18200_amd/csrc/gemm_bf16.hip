@@ -407,6 +407,11 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         GemmArgs b = a;
         b.kt_per_split = ((a.KT + a.SK - 1) / a.SK + KC - 1) / KC * KC;
         b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
+        if (b.SK > 1 && (size_t)b.SK * a.M * a.NT * 16 > a.part_floats) {
+            set_error("gemm: %d-way split of %d x %d outputs exceeds the partial buffer (%zu floats)", b.SK, a.M,
+                      a.NT * 16, a.part_floats);
+            return SEED_E_CAPACITY;
+        }
         dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
         if (epi == EPI_SWIGLU) {
             if constexpr (TN >= 2) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);

@@ -277,6 +277,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.KT = K / 32;
         a.M = M;
         a.part = (float *)at(c, L.part);
+        a.part_floats = L.part_floats;
         a.counters = (int *)at(c, L.counters);
         a.eps = g.rms_eps;
         int wn, wk, tn, sk;

@@ -29,6 +29,7 @@ struct GemmArgs {
     const void *Xp;        // packed hi/lo bf16 activations [m-tile][KT][hi|lo][64][8]
     int NT, KT, kt_per_split, SK, M;
     float *part;           // [SK][M][NT*16] split-K partial sums (SK > 1)
+    size_t part_floats;    // capacity of `part` in floats (a split needs SK * M * NT * 16)
     int *counters;         // >= groups + 1 ints, zero on entry and left zero on exit
     float *out;            // STORE: out[row * ld_out + col]
     int ld_out;
