@@ -26,7 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per projection launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy
 # kernel of known size); see profiles/.  None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6}     # profiles/gemm_kernel_c3.md: 2 x 51,667 KiB fetched + 521 KiB written
+MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6,     # profiles/gemm_kernel_c3.md: 2 x 51,667 KiB fetched + 521 KiB written
+                          "c4": 135.7e6,     # profiles/verify_step_c4_c5.md: 2 x 61,251 KiB + 9,981 KiB
+                          "c5": 176.7e6}     # profiles/verify_step_c4_c5.md: 2 x 84,495 KiB + 3,602 KiB
 
 
 def algorithmic_bytes(w):
