@@ -131,6 +131,13 @@ typedef struct {
  *   position shared_len; private_len is ignored), SEED_STEP_GREEDY, SEED_STEP_COMMIT_ALL.
  *   accept (optional): its p_or_logits / probs_kind / n_target_rows / n_branches / vocab fields are
  *   filled in by the library from this step's logits; the remaining fields are the caller's.
+ *   branch_slot (optional, bf16 contexts): verify a SUBSET of the context's branches (Section 3.3: the
+ *   target verifies whichever drafts are waiting in the queue).  Branch b of the call then is the context's
+ *   branch branch_slot[b]: its private KV cache is slot branch_slot[b] (0 <= slot < max_branches, all
+ *   different within a call) and its length is private_len[branch_slot[b]], i.e. private_len is the
+ *   caller's array over ALL max_branches slots; row_tok, logits_out and the accept arrays stay dense over
+ *   the call's N branches.  NULL = branch b is slot b.  An out-of-range slot is clamped and sets bit 1 of
+ *   the status word.
  * Errors: SEED_E_CAPACITY if N, T or shared_len + T exceed what the context was created for.  A branch
  *   whose private_len would overflow max_private + max_rows_per_branch is detected on the device:
  *   its out-of-range rows are dropped and bit 0 of the status word is set (seed_verify_status).
@@ -144,6 +151,7 @@ typedef struct {
     int32_t *private_len;     /* [N] in (out if accept / COMMIT_ALL)              */
     float *logits_out;        /* [N][T][V] out, may be NULL                       */
     const seed_accept_args *accept; /* host pointer, may be NULL                  */
+    const int32_t *branch_slot; /* [N] device, may be NULL: see below              */
 } seed_step_args;
 
 /*
@@ -168,6 +176,8 @@ typedef struct {
     int32_t *tok_out;       /* N entries, stride tok_stride        */
     int64_t tok_stride;
     float *logits_out;      /* [N][V] out, may be NULL             */
+    const int32_t *branch_slot; /* [N] device, may be NULL: as in seed_step_args (private_len is then indexed
+                                   by slot; row_tok, u, q_out, tok_out, logits_out stay dense)  */
 } seed_draft_args;
 
 /* Bytes of device workspace a context needs: repacked weights + KV caches + activations. 0 on error. */

@@ -43,14 +43,14 @@ class AcceptArgsC(C.Structure):
 class StepArgsC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_branches", "rows_per_branch", "flags", "shared_len")] + \
                [("row_tok", C.c_void_p), ("private_len", C.c_void_p), ("logits_out", C.c_void_p),
-                ("accept", C.POINTER(AcceptArgsC))]
+                ("accept", C.POINTER(AcceptArgsC)), ("branch_slot", C.c_void_p)]
 
 
 class DraftArgsC(C.Structure):
     _fields_ = [("n_branches", C.c_int32), ("flags", C.c_int32), ("shared_len", C.c_int32),
                 ("temperature", C.c_float), ("row_tok", C.c_void_p), ("private_len", C.c_void_p),
                 ("u", C.c_void_p), ("q_out", C.c_void_p), ("q_stride", C.c_int64), ("tok_out", C.c_void_p),
-                ("tok_stride", C.c_int64), ("logits_out", C.c_void_p)]
+                ("tok_stride", C.c_int64), ("logits_out", C.c_void_p), ("branch_slot", C.c_void_p)]
 
 
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
@@ -223,9 +223,11 @@ class VerifyContext:
         _check(self.lib.seed_kv_load(self.handle, layer, _ptr(k_shared), _ptr(v_shared), S, _ptr(k_private),
                                      _ptr(v_private), n_b, R))
 
-    def step(self, row_tok, shared_len, private_len=None, *, flags=0, logits_out=None, accept=None):
+    def step(self, row_tok, shared_len, private_len=None, *, flags=0, logits_out=None, accept=None,
+             branch_slot=None):
         """seed_verify_step.  row_tok int32 [N][T].  `accept` = dict(q, draft_tok, u_acc, u_res, temperature,
-        greedy=False) -> returns (accept_len, out_tok, n_out, p_tok); otherwise returns None."""
+        greedy=False) -> returns (accept_len, out_tok, n_out, p_tok); otherwise returns None.  branch_slot:
+        int32 [N] cache slots of the call's branches (private_len is then indexed by slot)."""
         N, T = row_tok.shape
         acc_c, outs = None, None
         if accept is not None:
@@ -235,7 +237,7 @@ class VerifyContext:
                                    accept.get("temperature", 1.0), None, accept.get("q"), accept["draft_tok"],
                                    accept.get("u_acc"), accept.get("u_res"), *outs, None)
         a = StepArgsC(N, T, flags, int(shared_len), _ptr(row_tok), _ptr(private_len), _ptr(logits_out),
-                      C.pointer(acc_c) if acc_c is not None else None)
+                      C.pointer(acc_c) if acc_c is not None else None, _ptr(branch_slot))
         _check(self.lib.seed_verify_step(self.handle, C.byref(a)))
         return outs
 
@@ -250,7 +252,7 @@ class VerifyContext:
         return pos
 
     def draft_step(self, row_tok, shared_len, private_len, u, temperature, *, q_out=None, tok_out=None,
-                   q_stride=None, tok_stride=1, flags=0, logits_out=None):
+                   q_stride=None, tok_stride=1, flags=0, logits_out=None, branch_slot=None):
         """seed_draft_step: one autoregressive token per branch.  q_out / tok_out may be views into
         q[N][gamma][V] / draft_tok[N][gamma] columns (pass the strides of the branch dimension)."""
         import torch
@@ -260,7 +262,8 @@ class VerifyContext:
         if q_out is not None and q_stride is None:
             q_stride = q_out.stride(0)
         a = DraftArgsC(N, flags, int(shared_len), float(temperature), _ptr(row_tok), _ptr(private_len), _ptr(u),
-                       _ptr(q_out), int(q_stride or 0), _ptr(tok_out), int(tok_stride), _ptr(logits_out))
+                       _ptr(q_out), int(q_stride or 0), _ptr(tok_out), int(tok_stride), _ptr(logits_out),
+                       _ptr(branch_slot))
         _check(self.lib.seed_draft_step(self.handle, C.byref(a)))
         return tok_out
 

@@ -301,7 +301,7 @@ struct RowInfo {
 // by a group of 16 / rows wavefronts: softmax statistics (or argmax in greedy mode), p(x) and the accept test.
 // Phase 2: the whole workgroup draws the replacement / bonus token for the one row that needs it.
 __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a, const SliceStats *stats,
-                                                                int n_slices) {
+                                                                int n_slices, const int32_t *slot, int n_slots) {
     __shared__ Shared sm;
     __shared__ RowInfo ri;
     const int b = blockIdx.x;
@@ -448,7 +448,11 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
     if (threadIdx.x == 0) {
         a.accept_len[b] = acc;
         a.n_out[b] = acc + (new_tok >= 0 ? 1 : 0);
-        if (a.private_len != nullptr) a.private_len[b] += min(acc + 1, Tp);
+        if (a.private_len != nullptr) {
+            // (a verify step of a subset of branches keeps the lengths by cache slot)
+            const int sb = slot != nullptr ? min(max(slot[b], 0), n_slots - 1) : b;
+            a.private_len[sb] += min(acc + 1, Tp);
+        }
     }
 }
 
@@ -458,7 +462,7 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
 __global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
         const float *logits, int64_t logits_stride, float temperature, int greedy, const float *u,
         float *q_out, int64_t q_stride, int32_t *tok_out, int64_t tok_stride, int32_t *private_len, int V,
-        const SliceStats *stats, int n_slices) {
+        const SliceStats *stats, int n_slices, const int32_t *slot, int n_slots) {
     __shared__ Shared sm;
     const int b = blockIdx.x;
     const int lane = threadIdx.x & 63;
@@ -503,7 +507,7 @@ __global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
     }
     if (threadIdx.x == 0) {
         tok_out[(size_t)b * tok_stride] = tok;
-        if (private_len != nullptr) private_len[b] += 1;
+        if (private_len != nullptr) private_len[slot != nullptr ? min(max(slot[b], 0), n_slots - 1) : b] += 1;
     }
 }
 
@@ -530,7 +534,8 @@ size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices
 
 // scratch (optional, accept_scratch_bytes(n_branches * n_target_rows) bytes): with it the softmax statistics
 // of the rows are computed by a launch that fills the chip; without it inside the one workgroup per branch.
-int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
+int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
+                  hipStream_t st) {
     if (a.n_branches == 0) return SEED_OK;
     const bool need_stats = a.probs_kind == SEED_KIND_LOGITS || a.greedy;
     SliceStats *stats = nullptr;
@@ -543,7 +548,8 @@ int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
         hipLaunchKernelGGL(row_stats_kernel, dim3(rows, n_slices), dim3(256), 0, st, a.p_or_logits, a.vocab, per,
                            a.greedy ? 1.0f : 1.0f / a.temperature, stats);
     }
-    hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, stats, n_slices);
+    hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, stats, n_slices,
+                       branch_slot, n_slots);
     return hip_fail(hipGetLastError(), "accept_resample launch");
 }
 
@@ -552,7 +558,7 @@ int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st) {
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
-                          hipStream_t st) {
+                          const int32_t *branch_slot, int n_slots, hipStream_t st) {
     if (n_rows == 0) return SEED_OK;
     SliceStats *stats = nullptr;
     int n_slices = 0;
@@ -565,7 +571,7 @@ int launch_softmax_sample(const float *logits, int64_t logits_stride, float temp
     }
     hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_rows), dim3(kBlock), 0, st, logits, logits_stride,
                        temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, vocab, stats,
-                       n_slices);
+                       n_slices, branch_slot, n_slots);
     return hip_fail(hipGetLastError(), "softmax_sample launch");
 }
 

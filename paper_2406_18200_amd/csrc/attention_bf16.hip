@@ -49,6 +49,8 @@ struct AttnParams {
     const uint16_t *k_priv;   // [Nmax][H][cap_p][DH]
     const uint16_t *vt_priv;  // [Nmax][H][cap_p/32][DH][32]
     const int32_t *private_len;
+    const int32_t *slot;      // branch -> cache slot (NULL: identity); private_len is indexed by slot
+    int n_slots;
     float *o_part;            // [P][Mq][H][DH]
     float *ml_part;           // [P][Mq][H][2]
     // single-launch form only:
@@ -78,8 +80,12 @@ struct AttnParams {
 // Position and validity of query row r in a verify / decode step: branch b = r / T continues its private
 // context, so the row sits at S + private_len[b] + j.  An out-of-range length is clamped (and flagged by the
 // in-flight task, which then drops the cache append).
+// Cache slot of branch b of this call (an out-of-range entry is clamped; the in-flight task flags it).
+__device__ __forceinline__ int slot_of(const AttnParams &P, int b) {
+    return P.slot != nullptr ? min(max(P.slot[b], 0), P.n_slots - 1) : b;
+}
 __device__ __forceinline__ int clamped_private_len(const AttnParams &P, int b) {
-    return min(max(P.private_len[b], 0), P.max_private);
+    return min(max(P.private_len[slot_of(P, b)], 0), P.max_private);
 }
 
 // Query fragments (B operand, hi/lo) of row r, head h from the fp32 QKV output with the rotary embedding
@@ -281,7 +287,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
     RawQ<DH> qraw[RT];
     if (FUSED) {
 #pragma unroll
-        for (int t = 0; t < RT; ++t) qraw[t].pl = P.private_len[min(row0 + t * 16 + col, P.M - 1) / P.T];
+        for (int t = 0; t < RT; ++t) qraw[t].pl = P.private_len[slot_of(P, min(row0 + t * 16 + col, P.M - 1) / P.T)];
     }
     bf16x8 kf[2][KS], vf[DT];
     load_kv(c0 < kend ? c0 : 0, kf, vf);           // (a wavefront without a chunk reads chunk 0 and drops it)
@@ -464,7 +470,7 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
     // issue order as in attn_task: private lengths, the first two chunks, the raw q values; no branches
     const int qrow = min(row0 + col, P.M - 1);
     RawQ<DH> qraw;
-    if (FUSED) qraw.pl = P.private_len[qrow / P.T];
+    if (FUSED) qraw.pl = P.private_len[slot_of(P, qrow / P.T)];
     bf16x8 kr0[PPT], vr0[PPT], kr1[PPT], vr1[PPT];
     gload(0, kr0, vr0);
     gload(1, kr1, vr1);
@@ -528,7 +534,9 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     if (r >= P.M) return;
     const int b = r / P.T, j = r - b * P.T;
     const int HD = P.H * DH;
-    int pl = P.private_len[b];
+    const int sb = slot_of(P, b);
+    if (P.slot != nullptr && P.slot[b] != sb && lane == 0 && h == 0) atomicOr(P.status, 2);   // slot out of range
+    int pl = P.private_len[sb];
     bool store_kv = true;
     if (pl < 0 || pl > P.max_private) {              // capacity overflow: drop the append, flag it
         if (lane == 0 && h == 0) atomicOr(P.status, 1);
@@ -583,7 +591,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
             for (int i = 0; i < PER; ++i) o[i] = o[i] * alpha + p * vv[u][i];
             m = m_new;
             if (j0 + u == j && store_kv) {              // this row's own key / value: append to the cache
-                const size_t head = (size_t)b * P.H + h;
+                const size_t head = (size_t)sb * P.H + h;
                 const int idx = pl + j;
 #pragma unroll
                 for (int i = 0; i < PER; ++i) {
@@ -693,7 +701,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     // workgroup tasks: first the shared segment, then one per (branch, head, row group, private key range)
     // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
-                 "s"(P.private_len), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
+                 "s"(P.private_len), "s"(P.slot), "s"(P.n_slots), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
                  "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
     asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.wave_tasks), "s"(P.gpw), "s"(P.n_quads), "s"(P.M), "s"(P.Mq), "s"(P.N),
                  "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
@@ -748,8 +756,9 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             const int kbeg = ks * P.keys_per_range_priv;
             const int kend = min(pl, kbeg + P.keys_per_range_priv);
             // every row of the branch sees all pl committed private keys
-            attn_task<DH, FUSED>(P, h, row_first, row_end, P.k_priv + ((size_t)b * P.H + h) * P.cap_p * DH,
-                                 P.vt_priv + ((size_t)b * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
+            const size_t sb = (size_t)slot_of(P, b);
+            attn_task<DH, FUSED>(P, h, row_first, row_end, P.k_priv + (sb * P.H + h) * P.cap_p * DH,
+                                 P.vt_priv + (sb * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
                                  pl, b * P.T, 0, P.ks_shared + ks, smem);
         }
         if (FUSED && ks == 0)
@@ -823,6 +832,8 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.k_priv_w = (uint16_t *)a.k_priv;
     P.vt_priv_w = (uint16_t *)a.vt_priv;
     P.private_len = a.private_len;
+    P.slot = a.branch_slot;
+    P.n_slots = a.n_slots;
     P.o_part = a.o_part;
     P.ml_part = a.ml_part;
     P.qkv = a.qkv;

@@ -262,9 +262,9 @@ __global__ void kv_import_kernel(const void *src, void *dst, int heads, int len,
     }
 }
 
-__global__ void add_len_kernel(int32_t *len, int n, int delta) {
+__global__ void add_len_kernel(int32_t *len, int n, int delta, const int32_t *slot, int n_slots) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) len[i] += delta;
+    if (i < n) len[slot != nullptr ? min(max(slot[i], 0), n_slots - 1) : i] += delta;
 }
 
 }  // namespace
@@ -333,9 +333,9 @@ int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int 
     return hip_fail(hipGetLastError(), "kv_import launch");
 }
 
-int launch_add_len(int32_t *len, int n, int delta, hipStream_t st) {
+int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st) {
     if (n == 0) return SEED_OK;
-    hipLaunchKernelGGL(add_len_kernel, dim3((n + 63) / 64), dim3(64), 0, st, len, n, delta);
+    hipLaunchKernelGGL(add_len_kernel, dim3((n + 63) / 64), dim3(64), 0, st, len, n, delta, branch_slot, n_slots);
     return hip_fail(hipGetLastError(), "add_len launch");
 }
 

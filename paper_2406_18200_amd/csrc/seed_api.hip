@@ -257,7 +257,7 @@ KvPtrs kv_layer(const seed_ctx *c, int l) {
 // bf16 path: projections with fused epilogues (see gemm_bf16.hip); 5 launches per layer in a verify / decode
 // step (6 above 16 rows), 7 in the shared-prefix prefill.
 int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
-                     const int32_t *private_len, float *logits) {
+                     const int32_t *private_len, const int32_t *branch_slot, float *logits) {
     const seed_model_cfg &g = c->cfg;
     const Layout &L = c->L;
     hipStream_t st = c->stream;
@@ -322,6 +322,8 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         at_.qkv = (const float *)at(c, L.qkv); at_.rope = (const float *)at(c, L.rope);
         at_.k_shared = kv.ks; at_.vt_shared = kv.vs; at_.k_priv = kv.kp; at_.vt_priv = kv.vp;
         at_.private_len = private_len;
+        at_.branch_slot = branch_slot;
+        at_.n_slots = g.max_branches;
         at_.o_part = (float *)at(c, L.o_part); at_.ml_part = (float *)at(c, L.ml_part);
         at_.counters = (int *)at(c, L.attn_counters);
         at_.act = at(c, L.act_hd);
@@ -415,8 +417,12 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
 }
 
 int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
-                const int32_t *private_len, float *logits) {
-    return c->bf16 ? run_forward_bf16(c, N, T, S, prefill_shared, row_tok, private_len, logits)
+                const int32_t *private_len, const int32_t *branch_slot, float *logits) {
+    if (branch_slot != nullptr && (!c->bf16 || prefill_shared)) {
+        set_error("branch_slot needs a bf16 context and a verify / decode step");
+        return SEED_E_UNSUPPORTED_DTYPE;
+    }
+    return c->bf16 ? run_forward_bf16(c, N, T, S, prefill_shared, row_tok, private_len, branch_slot, logits)
                    : run_forward_f32(c, N, T, S, prefill_shared, row_tok, private_len, logits);
 }
 
@@ -540,7 +546,7 @@ int seed_verify_profile_read(seed_ctx *c, int64_t *launches, double *total_ms, d
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     int rc = check_accept_args(args);
     if (rc) return rc;
-    return launch_accept(*args, nullptr, (hipStream_t)hip_stream);
+    return launch_accept(*args, nullptr, nullptr, 0, (hipStream_t)hip_stream);
 }
 
 int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out, int32_t n_rows,
@@ -602,10 +608,12 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
     }
     const bool want_logits = a->logits_out != nullptr || a->accept != nullptr;
     float *logits = want_logits ? (a->logits_out ? a->logits_out : (float *)at(c, c->L.logits)) : nullptr;
-    int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, logits);
+    int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, a->branch_slot, logits);
     if (rc) return rc;
-    if (a->accept != nullptr) return launch_accept(acc, at(c, c->L.acc_stats), c->stream);
-    if (a->flags & SEED_STEP_COMMIT_ALL) return launch_add_len(a->private_len, N, T, c->stream);
+    if (a->accept != nullptr)
+        return launch_accept(acc, at(c, c->L.acc_stats), a->branch_slot, g.max_branches, c->stream);
+    if (a->flags & SEED_STEP_COMMIT_ALL)
+        return launch_add_len(a->private_len, N, T, a->branch_slot, g.max_branches, c->stream);
     return SEED_OK;
 }
 
@@ -626,10 +634,11 @@ int seed_draft_step(seed_ctx *c, const seed_draft_args *a) {
     if (a->q_out != nullptr && a->q_stride < g.vocab) { set_error("draft: q_stride < vocab"); return SEED_E_INVALID_ARG; }
     if (a->tok_stride < 1) { set_error("draft: tok_stride must be >= 1"); return SEED_E_INVALID_ARG; }
     float *logits = a->logits_out ? a->logits_out : (float *)at(c, c->L.logits);
-    int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, logits);
+    int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, a->branch_slot, logits);
     if (rc) return rc;
     return launch_softmax_sample(logits, g.vocab, a->temperature, greedy, a->u, a->q_out, a->q_stride, a->tok_out,
-                                 a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats), c->stream);
+                                 a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats), a->branch_slot,
+                                 g.max_branches, c->stream);
 }
 
 int seed_kv_load(seed_ctx *c, int32_t layer, const void *k_shared, const void *v_shared, int32_t shared_len,

@@ -11,11 +11,12 @@ int hip_fail(hipError_t e, const char *what);
 
 // ---- accept.hip ------------------------------------------------------------------------------
 size_t accept_scratch_bytes(int max_rows);
-int launch_accept(const seed_accept_args &a, void *scratch, hipStream_t st);   // scratch may be NULL
+int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
+                  hipStream_t st);   // scratch, branch_slot may be NULL
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
-                          hipStream_t st);   // scratch may be NULL
+                          const int32_t *branch_slot, int n_slots, hipStream_t st);   // scratch, slot may be NULL
 int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
                         int n_rows, int vocab, hipStream_t st);
 
@@ -63,7 +64,7 @@ int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q
                    int max_private, int32_t *status, hipStream_t st);
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
                      hipStream_t st);
-int launch_add_len(int32_t *len, int n, int delta, hipStream_t st);
+int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv);
@@ -77,6 +78,8 @@ struct AttnBf16Args {
     const void *k_shared, *vt_shared;
     void *k_priv, *vt_priv;
     const int32_t *private_len;
+    const int32_t *branch_slot;   // may be NULL; private_len and the private caches are indexed by slot
+    int n_slots;                  // max_branches of the context (slots are clamped to it)
     float *o_part, *ml_part;
     int *counters;
     void *act;

@@ -193,3 +193,97 @@ def test_two_consecutive_steps_commit_and_reuse_the_cache():
 def sv_flags():
     import paper_2406_18200_amd as sv
     return sv.binding
+
+
+def test_subsets_of_branches_by_cache_slot():
+    """Verify steps over SUBSETS of a context's branches (the target verifies whichever drafts are queued):
+    branch b of a call is cache slot branch_slot[b].  Six branches with private contexts; two calls verify
+    slots (4, 1, 5) and (0, 3); logits against the oracle's for exactly those branches, the accept step's
+    lengths land in the right slots, the untouched slot 2 keeps its length, and a later full step sees the
+    rows the subset steps committed."""
+    import torch
+    import oracle
+    import workloads.device as D
+    from workloads import gen
+    from harness import check_logits
+    w = wl.get_workload("c2").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
+                                     N=6, gamma=3, S=70, R=6, seed=321)
+    m, G, N, T, dev = w.model, w.gamma, w.N, w.gamma, "cuda:0"
+    up = D.UploadingWeights(m, w.seed, dev, reuse_buffers=False)
+    prefix, private, pending = wl.prefix_tokens(w), gen.private_tokens(w), gen.pending_tokens(w)
+    rng = np.random.default_rng(11)
+    _, ks, vs = oracle.decode_rows(m, up, prefix)
+    committed = [list(private[b]) for b in range(N)]            # tokens whose KV each branch has committed
+
+    def oracle_logits(slots, rows):
+        pk, pv = [], []
+        for b in slots:
+            _, kb, vb = oracle.decode_rows(m, up, np.array(committed[b]), ctx_kv=lambda l: (ks[l], vs[l]), pos0=w.S)
+            pk.append(kb)
+            pv.append(vb)
+        ctx = lambda l: [(np.concatenate([ks[l], pk[i][l]], 1), np.concatenate([vs[l], pv[i][l]], 1))
+                         for i in range(len(slots))]
+        return oracle.verify_forward(m, up, rows, ctx, [w.S + len(committed[b]) for b in slots])
+
+    ctx = D.make_context(m, up.upload_all(), max_branches=N, max_rows_per_branch=T, max_shared=w.S,
+                         max_private=w.R + 3 * T, device=dev)
+    plen = torch.zeros(N, dtype=torch.int32, device=dev)
+    ctx.prefill_shared(D.i32(prefix, dev))
+    for lo in range(0, w.R, T):
+        ctx.step(D.i32(private[:, lo:lo + T], dev).contiguous(), w.S, plen, flags=sv_flags().SEED_STEP_COMMIT_ALL)
+    for slots in ([4, 1, 5], [0, 3]):
+        n = len(slots)
+        drafts = rng.integers(0, m.vocab, (n, G)).astype(np.int32)
+        rows = np.concatenate([pending[slots][:, None], drafts[:, :T - 1]], axis=1).astype(np.int32)
+        ref = oracle_logits(slots, rows)
+        p = oracle.softmax_temperature(ref, w.temperature)
+        want_a = np.array([(s + 1) % (G + 1) for s in slots])
+        q = np.zeros((n, G, m.vocab), np.float32)
+        u_acc = np.zeros((n, G), np.float32)
+        for i in range(n):
+            for j in range(G):
+                if j < want_a[i]:
+                    q[i, j], u_acc[i, j] = p[i, j], 0.5
+                else:
+                    q[i, j, drafts[i, j]], u_acc[i, j] = 1.0, 0.999
+        acc = dict(q=D.f32(q, dev), draft_tok=D.i32(drafts, dev), u_acc=D.f32(u_acc, dev),
+                   u_res=D.f32(wl.uniform24(w.seed + n, (n,), stream=1), dev), temperature=w.temperature)
+        logits = torch.empty((n, T, m.vocab), dtype=torch.float32, device=dev)
+        before = plen.cpu().numpy().copy()
+        a_g, out_g, _, _ = [o.cpu().numpy() for o in ctx.step(D.i32(rows, dev), w.S, plen, logits_out=logits,
+                                                             accept=acc, branch_slot=D.i32(np.array(slots), dev))]
+        worst, err = check_logits(logits.cpu().numpy(), ref, m.dtype)
+        assert worst <= 1.0, (slots, worst, err)
+        assert np.array_equal(a_g, want_a), (slots, a_g, want_a)
+        after = plen.cpu().numpy()
+        commit = np.minimum(want_a + 1, T)
+        for b in range(N):
+            assert after[b] == before[b] + (commit[slots.index(b)] if b in slots else 0), (b, before, after)
+        for i, b in enumerate(slots):
+            committed[b] += list(rows[i, :commit[i]])
+            pending[b] = out_g[i, want_a[i]] if want_a[i] < G else drafts[i, G - 1]
+    # a full step over all six branches (identity slots) sees what the subset steps left in the caches
+    drafts = rng.integers(0, m.vocab, (N, G)).astype(np.int32)
+    rows = np.concatenate([pending[:, None], drafts[:, :T - 1]], axis=1).astype(np.int32)
+    logits = torch.empty((N, T, m.vocab), dtype=torch.float32, device=dev)
+    ctx.step(D.i32(rows, dev), w.S, plen, logits_out=logits)
+    torch.cuda.synchronize()
+    worst, err = check_logits(logits.cpu().numpy(), oracle_logits(list(range(N)), rows), m.dtype)
+    assert worst <= 1.0, (worst, err)
+    # an out-of-range slot is clamped and flagged, not fatal
+    ctx.step(D.i32(rows[:1], dev), w.S, plen, branch_slot=D.i32(np.array([N + 3]), dev))
+    torch.cuda.synchronize()
+    assert ctx.status() & 2
+    ctx.close()
+
+
+def test_branch_slots_are_refused_where_unsupported():
+    """fp32 contexts and the shared-prefix prefill take no branch_slot: an error code, nothing launched."""
+    import torch
+    import workloads.device as D
+    w = wl.get_workload("c1")
+    c = Case(w).run_oracle().run_gpu(keep_ctx=True)
+    slots = D.i32(np.arange(w.N))
+    with pytest.raises(RuntimeError, match="branch_slot"):
+        c.ctx.step(D.i32(c.inp["row_tok"]), w.S, c.dev_plen, branch_slot=slots)
+    c.ctx.close()
