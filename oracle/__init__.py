@@ -9,9 +9,11 @@ the benchmark's CPU-baseline leg.  The product path never routes through it.
 Pins (see tests/test_oracle_*.py): an independent library implementation of the same decoder
 architecture, closed-form acceptance probabilities, exact enumeration on tiny vocabularies, the
 chi-square losslessness test, and structural invariants (branch independence, relative-position
-invariance of rotary attention).  The paper prints no worked numeric example, so absolute logit
+invariance of rotary attention); for the rounds of Algorithm 1 (specdecode.py): with the draft model equal to
+the target every draft is accepted and the output must be plain autoregressive sampling.  The paper prints no worked numeric example, so absolute logit
 values are "parity unpinned" by the paper itself; they are pinned by the library implementation.
 """
 from .transformer import decode_rows, verify_forward, rms_norm, rope_rotate  # noqa: F401
 from .specsample import (softmax_temperature, accept_resample, fixed_point_draw,  # noqa: F401
                          sample_from_probs, commit_lengths)
+from .specdecode import speculative_rounds  # noqa: F401

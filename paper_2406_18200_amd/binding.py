@@ -53,9 +53,25 @@ class DraftArgsC(C.Structure):
                 ("tok_stride", C.c_int64), ("logits_out", C.c_void_p), ("branch_slot", C.c_void_p)]
 
 
+class SchedStatsC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("units", "draft_steps", "drafted", "accepted", "emitted")] + \
+               [("wall_ms", C.c_double)]
+
+
+class SchedArgsC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_branches", "gamma", "max_new", "unit_branches", "shared_len_target",
+                                         "shared_len_draft")] + \
+               [("temperature", C.c_float), ("first_tok", C.c_void_p), ("u_draft", C.c_void_p),
+                ("u_acc", C.c_void_p), ("u_res", C.c_void_p), ("u_stride", C.c_int32),
+                ("target_private_len", C.c_void_p), ("draft_private_len", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t), ("out_tok", C.c_void_p), ("out_len", C.c_void_p),
+                ("stats", C.POINTER(SchedStatsC))]
+
+
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
            "seed_accept_resample", "seed_sample_probs", "seed_kv_load", "seed_verify_status",
-           "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_destroy", "seed_last_error")
+           "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_destroy", "seed_last_error",
+           "seed_sched_workspace_bytes", "seed_sched_run")
 
 
 def library_path():
@@ -88,6 +104,9 @@ def load_library():
                                              C.POINTER(C.c_double)]
     lib.seed_verify_destroy.argtypes = [C.c_void_p]
     lib.seed_verify_destroy.restype = None
+    lib.seed_sched_workspace_bytes.restype = C.c_size_t
+    lib.seed_sched_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    lib.seed_sched_run.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(SchedArgsC)]
     _LIB = lib
     return lib
 
@@ -280,3 +299,32 @@ class VerifyContext:
         s = C.c_int32(0)
         _check(self.lib.seed_verify_status(self.handle, C.byref(s)))
         return s.value
+
+
+def sched_run(target, draft, first_tok, u_draft, u_acc, u_res, target_private_len, draft_private_len, *, gamma,
+              max_new, temperature, shared_len_target, shared_len_draft, unit_branches=0):
+    """seed_sched_run: Algorithm 1 over a target and a draft VerifyContext (create them on two different
+    torch streams for overlap).  first_tok: int sequence [n] (host); u_*: float32 device tensors [n][stride];
+    *_private_len: int32 device tensors over the contexts' slots.  Returns (tokens int32 numpy [n][max_new],
+    lengths [n], stats dict)."""
+    import numpy as np
+    import torch
+    lib = load_library()
+    n = len(first_tok)
+    V = target.shape.vocab
+    nbytes = lib.seed_sched_workspace_bytes(n, int(gamma), V)
+    if nbytes == 0:
+        raise SeedError(-1, "seed_sched_workspace_bytes: invalid n_branches / gamma / vocab")
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=u_draft.device)
+    base = (ws.data_ptr() + 255) // 256 * 256
+    first = np.ascontiguousarray(first_tok, dtype=np.int32)
+    out_tok = np.full((n, max_new), -1, np.int32)
+    out_len = np.zeros(n, np.int32)
+    stats = SchedStatsC()
+    a = SchedArgsC(n, int(gamma), int(max_new), int(unit_branches), int(shared_len_target), int(shared_len_draft),
+                   float(temperature), first.ctypes.data, _ptr(u_draft), _ptr(u_acc), _ptr(u_res),
+                   int(u_draft.stride(0)), _ptr(target_private_len), _ptr(draft_private_len), C.c_void_p(base),
+                   nbytes, out_tok.ctypes.data, out_len.ctypes.data, C.pointer(stats))
+    torch.cuda.synchronize()
+    _check(lib.seed_sched_run(target.handle, draft.handle, C.byref(a)))
+    return out_tok, out_len, {f: getattr(stats, f) for f, _ in SchedStatsC._fields_}

@@ -6,7 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libseed_verify.so")
-SOURCES = ["seed_api.hip", "accept.hip", "gemm_bf16.hip", "rowops.hip", "attention_bf16.hip", "fp32_path.hip"]
+SOURCES = ["seed_api.hip", "accept.hip", "gemm_bf16.hip", "rowops.hip", "attention_bf16.hip", "fp32_path.hip",
+           "sched.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

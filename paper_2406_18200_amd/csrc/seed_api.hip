@@ -180,6 +180,11 @@ struct seed_ctx {
     double prof_bytes = 0.0;
 };
 
+namespace seedv {
+hipStream_t seed_ctx_stream(const seed_ctx *c) { return c->stream; }
+const seed_model_cfg &seed_ctx_cfg(const seed_ctx *c) { return c->cfg; }
+}  // namespace seedv
+
 namespace {
 
 inline void *at(const seed_ctx *c, size_t off) { return c->ws + off; }

@@ -7,6 +7,12 @@
 namespace seedv {
 
 void set_error(const char *fmt, ...);
+}  // namespace seedv
+struct seed_ctx;
+namespace seedv {
+// what the scheduler needs of a context
+hipStream_t seed_ctx_stream(const seed_ctx *c);
+const seed_model_cfg &seed_ctx_cfg(const seed_ctx *c);
 int hip_fail(hipError_t e, const char *what);
 
 // ---- accept.hip ------------------------------------------------------------------------------

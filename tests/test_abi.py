@@ -21,7 +21,8 @@ def lib():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "seed_verify.h")).read()
+    import glob
+    text = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(seed_[a-z_]+)\s*\(", text)))
 
