@@ -97,6 +97,64 @@ def cpu_baseline(w, inp):
                       f"{w.model.n_layers} layers ({full:.1f}s per step)"}
 
 
+def scheduled(args):
+    """End-to-end rounds-scheduled execution (paper Section 3.3 / Algorithm 1) on synthetic models: target =
+    the workload's model, draft = the c2-shaped model with the same vocabulary, both random-init; for each
+    unit size (branches drafted and verified together) the validated tokens per second of the whole run."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from workloads import gen
+    from workloads.device import UploadingWeights, make_context, f32, i32
+    import paper_2406_18200_amd as sv
+    dev = "cuda:0"
+    wt = wl.get_workload(args.workload)
+    if args.layers:
+        wt = wt.scaled(n_layers=args.layers)
+    wd = wl.get_workload("c2").scaled(N=wt.N, gamma=wt.gamma, S=wt.S, vocab=wt.model.vocab)
+    n, G, L = wt.N, wt.gamma, args.scheduled
+    prefix = wl.prefix_tokens(wt)
+    first = gen.pending_tokens(wt)
+    u = wl.uniform24(wt.seed + 9, (3, n, L + G))
+    s_t, s_d = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(s_t):
+        up = UploadingWeights(wt.model, wt.seed, dev)
+        tctx = make_context(wt.model, up.upload_all(), max_branches=n, max_rows_per_branch=G, max_shared=wt.S,
+                            max_private=L + 2 * G, device=dev)
+        del up
+        torch.cuda.empty_cache()
+        tctx.prefill_shared(i32(prefix, dev))
+    with torch.cuda.stream(s_d):
+        upd = UploadingWeights(wd.model, wd.seed, dev, reuse_buffers=False)
+        dctx = make_context(wd.model, upd.upload_all(), max_branches=n, max_rows_per_branch=max(1, 128 // n),
+                            max_shared=wd.S, max_private=L + 2 * G, device=dev)
+        dctx.prefill_shared(i32(prefix, dev))
+    torch.cuda.synchronize()
+    ud, ua, ur = (f32(x, dev) for x in u)
+    units = sorted({n, max(1, (n + 1) // 2), 1}, reverse=True)
+    results, ref = {}, None
+    for unit in units:
+        best = None
+        for rep in range(3):                              # first repetition warms up
+            plen_t = torch.zeros(n, dtype=torch.int32, device=dev)
+            plen_d = torch.zeros(n, dtype=torch.int32, device=dev)
+            toks, lens, st = sv.sched_run(tctx, dctx, first, ud, ua, ur, plen_t, plen_d, gamma=G, max_new=L,
+                                          temperature=wt.temperature, shared_len_target=wt.S, shared_len_draft=wd.S,
+                                          unit_branches=unit)
+            assert (lens == L).all()
+            if rep and (best is None or st["wall_ms"] < best["wall_ms"]):
+                best = st
+        ref = toks if ref is None else ref
+        best["same_tokens_as_first_unit_size"] = bool(np.array_equal(toks, ref))
+        best["tokens_per_s"] = n * L / (best["wall_ms"] * 1e-3)
+        results[f"unit_{unit}"] = best
+    print(json.dumps({"metric": "validated tokens/s, rounds-scheduled execution (Algorithm 1), end to end",
+                      "unit": "tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"{wt.name} target + c2-shaped draft model, N={n} branches, gamma={G}, "
+                                             f"{L} validated tokens per branch, shared prefix S={wt.S}"},
+                      "results": results}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +168,10 @@ def main():
     ap.add_argument("--copy-probe-mb", type=int, default=0, help="also launch a plain device-to-device copy "
                     "of this many MiB (three times) before the timed region: the known-size kernel against "
                     "which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--scheduled", type=int, default=0, metavar="L",
+                    help="instead of the verify-step benchmark: run Algorithm 1 end to end (rounds-scheduled "
+                         "execution, L validated tokens per branch, draft model of the c2 shape) for several unit "
+                         "sizes and print one JSON line with validated tokens/s for each")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -121,6 +183,8 @@ def main():
     import workloads as wl
     from workloads import gen
     from workloads.device import UploadingWeights, make_context, f32, i32, to_device
+    if args.scheduled:
+        return scheduled(args)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
