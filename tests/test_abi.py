@@ -88,3 +88,15 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "HERE", str(tmp_path))
     with pytest.raises(RuntimeError, match="missing"):
         B.load_library()
+
+
+def test_scheduler_argument_validation_without_a_gpu(lib):
+    """seed_sched_run / seed_sched_workspace_bytes reject bad arguments before touching the GPU."""
+    assert lib.seed_sched_workspace_bytes(0, 4, 32000) == 0
+    assert lib.seed_sched_workspace_bytes(3, 0, 32000) == 0
+    assert lib.seed_sched_workspace_bytes(64, 4, 32000) == 0          # more than SEED_SCHED_MAX_BRANCHES
+    n = lib.seed_sched_workspace_bytes(3, 4, 32000)
+    assert n >= 3 * 3 * 4 * 32000 * 4                                   # q rows of the units in flight
+    a = B.SchedArgsC()
+    assert lib.seed_sched_run(None, None, C.byref(a)) == -6             # SEED_E_NOT_INIT
+    assert b"context" in lib.seed_last_error()

@@ -84,3 +84,34 @@ def test_scheduled_rounds_match_the_serial_oracle_for_every_unit_size():
         assert r["margin"].min() < 5e-2, (b, t, r)
     print(f"branches identical to the oracle: {exact}/{n}", flush=True)
     assert exact >= n - 1
+
+
+@pytest.mark.parametrize("n,gamma,max_new,unit", [(1, 1, 5, 0), (8, 2, 7, 3), (3, 4, 9, 2)])
+def test_scheduled_rounds_edge_shapes(n, gamma, max_new, unit):
+    """One branch with one draft per round; more branches than a unit with a ragged last unit; a validated
+    length that ends in the middle of a round.  Tokens against the serial oracle."""
+    wt, wd = _models()
+    wt, wd = wt.scaled(N=n, gamma=gamma, seed=301 + n), wd.scaled(N=n, gamma=gamma, seed=302 + n)
+    up_t = UploadingWeights(wt.model, wt.seed, "cuda:0", reuse_buffers=False)
+    up_d = UploadingWeights(wd.model, wd.seed, "cuda:0", reuse_buffers=False)
+    prefix = wl.prefix_tokens(wt)
+    first = gen.pending_tokens(wt)
+    u = wl.uniform24(wt.seed + 9, (3, n, max_new + gamma))
+    toks, lens, stats, _ = _run(wt, wd, up_t, up_d, prefix, first, u, max_new, unit)
+    assert (lens == max_new).all() and (toks >= 0).all()
+    _, ks_t, vs_t = oracle.decode_rows(wt.model, up_t, prefix)
+    _, ks_d, vs_d = oracle.decode_rows(wd.model, up_d, prefix)
+    ctx_t = [(ks_t[l], vs_t[l]) for l in range(wt.model.n_layers)]
+    ctx_d = [(ks_d[l], vs_d[l]) for l in range(wd.model.n_layers)]
+    exact = 0
+    for b in range(n):
+        want, rounds = oracle.speculative_rounds(wt.model, up_t, ctx_t, wt.S, wd.model, up_d, ctx_d, wd.S, first[b],
+                                                 gamma, max_new, wt.temperature, u[0][b], u[1][b], u[2][b])
+        got = toks[b].tolist()
+        if got == want:
+            exact += 1
+            continue
+        t = next(i for i in range(max_new) if got[i] != want[i])
+        r = next(r for r in rounds if r["start"] <= t < r["start"] + len(r["emitted"]))
+        assert r["margin"].min() < 5e-2, (b, t, r)
+    assert exact >= n - 1, (exact, n)
