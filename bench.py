@@ -31,13 +31,18 @@ MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6,     # profiles/gemm_kernel_c3.md: 2 x 5
                           "c5": 176.7e6}     # profiles/verify_step_c4_c5.md: 2 x 84,495 KiB + 3,602 KiB
 
 
+def wl_private_lens(w):
+    import workloads
+    return workloads.private_lens(w)
+
+
 def algorithmic_bytes(w):
     """Bytes one verify step must move: every weight once, the KV context once, logits and q once."""
     m = w.model
     es = 2 if m.dtype == "bf16" else 4
     weights = m.params * es
     kv_tok = 2 * m.n_heads * m.head_dim * es * m.n_layers
-    kv = (w.S + w.N * w.R) * kv_tok
+    kv = (w.S + int(wl_private_lens(w).sum())) * kv_tok
     M = w.N * w.gamma
     other = M * m.vocab * 4 * 2 + w.N * w.gamma * m.vocab * 4 + M * kv_tok   # logits w+r, q read, new KV
     return weights + kv + other, weights
@@ -47,7 +52,7 @@ def useful_flops(w):
     m = w.model
     M = w.N * w.gamma
     gemm = 2.0 * M * m.params
-    attn = 4.0 * M * (w.S + w.R + (w.gamma + 1) / 2) * m.n_heads * m.head_dim * m.n_layers
+    attn = 4.0 * w.gamma * float((w.S + wl_private_lens(w) + (w.gamma + 1) / 2).sum()) * m.n_heads * m.head_dim * m.n_layers
     return gemm + attn
 
 
@@ -76,12 +81,14 @@ def cpu_baseline(w, inp):
 
     def ctx(l):
         k_s, v_s, k_p, v_p = cache["kv"][l]
-        return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in range(w.N)]
+        return [(np.concatenate([k_s, k_p[b][:, :plens[b]]], 1), np.concatenate([v_s, v_p[b][:, :plens[b]]], 1))
+                for b in range(w.N)]
+    plens = wl.private_lens(w)
     times = {}
     for L in sorted({L_small, L_big}):
         ws = w.scaled(n_layers=L)
         t0 = time.perf_counter()
-        logits = oracle.verify_forward(ws.model, Pre, inp["row_tok"], ctx, [ws.S + ws.R] * ws.N)
+        logits = oracle.verify_forward(ws.model, Pre, inp["row_tok"], ctx, [ws.S + int(r) for r in plens])
         p = oracle.softmax_temperature(logits, ws.temperature)
         oracle.accept_resample(p, inp["q"], inp["drafts"], inp["u_acc"], inp["u_res"])
         times[L] = time.perf_counter() - t0
@@ -160,7 +167,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5", "c6"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; "
                     "the reported number is then NOT the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -200,7 +207,7 @@ def main():
     # ---- synthetic inputs, resident on the device -------------------------------------------------
     up = UploadingWeights(m, w.seed, dev)
     dw = up.upload_all()
-    ctx = make_context(m, dw, max_branches=N, max_rows_per_branch=T, max_shared=w.S, max_private=w.R, device=dev)
+    ctx = make_context(m, dw, max_branches=N, max_rows_per_branch=T, max_shared=max(w.S, 1), max_private=w.R, device=dev)
     del dw, up
     torch.cuda.empty_cache()
     for l in range(m.n_layers):
@@ -211,7 +218,7 @@ def main():
     else:
         q = wl.random_draft_q(w)
     pending = gen.pending_tokens(w)
-    plen0 = torch.full((N,), w.R, dtype=torch.int32, device=dev)
+    plen0 = i32(wl.private_lens(w), dev)        # all R, or ragged (state-evaluator shape)
     plen = plen0.clone()
     if q is None:
         # q_j = softmax((target logits_j + noise) / temp), drafts sampled autoregressively (timing run: the
@@ -288,7 +295,7 @@ def main():
         "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {m.n_layers}-layer d={m.d_model} H={m.n_heads} F={m.d_ff} V={m.vocab} "
                                f"decoder, N={N} branches x gamma={G} drafts, shared prefix S={w.S}, "
-                               f"private R={w.R}, temperature {w.temperature}" + (" (greedy)" if args.greedy else ""),
+                               f"private R={w.R}" + (f" (ragged, {w.R_min}..{w.R})" if w.R_min >= 0 else "") + f", temperature {w.temperature}" + (" (greedy)" if args.greedy else ""),
                    "global_batch": N * G, "seq_len": w.S + w.R + G, "parallelism": "single-gpu"},
         "step": {"algorithmic_bytes": total_bytes, "hbm_GBs": step_gbs, "hbm_frac": step_gbs / HBM_PEAK_GBS,
                  "useful_tflops": flops / (ms_per_step * 1e-3) / 1e12,

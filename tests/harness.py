@@ -93,6 +93,8 @@ class Case:
         self.w, self.bonus, self.greedy, self.device, self.log = w, bonus, greedy, device, log
         self.branches = list(range(w.N)) if branches is None else list(branches)
         self.inp = build_inputs(w, bonus, q_override)
+        self.plens = wl.private_lens(w)          # [N] valid private tokens per branch (ragged workloads: differ)
+        assert (self.plens == w.R).all() or w.kv_protocol == "synthetic"
 
     # ---------------------------------------------------------------- oracle side
     def run_oracle(self):
@@ -125,8 +127,9 @@ class Case:
             def ctx(l):
                 k_s, v_s, k_p, v_p = wl.synthetic_kv(w, l)
                 self.kv_dev.append(tuple(to_device(a, m, self.device) if a.size else None for a in (k_s, v_s, k_p, v_p)))
-                return [(np.concatenate([k_s, k_p[b]], 1), np.concatenate([v_s, v_p[b]], 1)) for b in sel]
-        pos0 = [w.S + w.R] * len(sel)
+                return [(np.concatenate([k_s, k_p[b][:, :self.plens[b]]], 1),
+                         np.concatenate([v_s, v_p[b][:, :self.plens[b]]], 1)) for b in sel]
+        pos0 = [w.S + int(self.plens[b]) for b in sel]
         self.ref_logits = oracle.verify_forward(m, W, inp["row_tok"][sel], ctx, pos0)
         G = w.gamma
         if self.greedy:
@@ -157,7 +160,7 @@ class Case:
         else:
             for l, (k_s, v_s, k_p, v_p) in enumerate(self.kv_dev):
                 ctx.kv_load(l, k_s, v_s, k_p, v_p)
-            plen += w.R
+            plen += i32(self.plens, self.device)   # a shorter branch simply ignores the rest of its slot
         logits = torch.empty((w.N, T, m.vocab), dtype=torch.float32, device=self.device)
         acc = dict(q=None if self.greedy else f32(inp["q"], self.device), draft_tok=i32(inp["drafts"], self.device),
                    u_acc=None if self.greedy else f32(inp["u_acc"], self.device),
@@ -213,6 +216,6 @@ class Case:
             assert np.array_equal(out_g[i, :a], out_w[i, :a])
             assert (out_g[i, n_w[i]:] == -1).all()
         # Algorithm 1 bookkeeping on the device
-        want_len = oracle.commit_lengths(np.full(w.N, w.R), self.gpu_accept[0], T)
+        want_len = oracle.commit_lengths(self.plens.copy(), self.gpu_accept[0], T)
         assert np.array_equal(self.gpu_plen, want_len)
         return worst, max_err

@@ -23,3 +23,8 @@ def test_c5_13b_sampled_branches_random_q():
     over 25.7 GB of weights; that recipe is exercised at two layers in test_gpu_verify.py."""
     w = wl.get_workload("c5").scaled(q_kind="random", q_temp=1.0)
     Case(w, branches=[0, 5]).run_oracle().run_gpu().compare()
+
+
+def test_c6_7b_state_evaluator_shape_sampled_branches():
+    """No shared prefix, eight private contexts of 384..1024 tokens: the shortest, the longest and one between."""
+    Case(wl.get_workload("c6"), branches=[0, 3, 7]).run_oracle().run_gpu().compare()

@@ -35,6 +35,21 @@ def test_small_bf16_synthetic_kv(N, gamma, S, R):
     Case(w).run_oracle().run_gpu().compare()
 
 
+@pytest.mark.parametrize("N,gamma,S,R,R_min", [(5, 3, 0, 300, 3),     # <= 16 rows, no shared prefix at all
+                                               (8, 4, 0, 300, 0),     # 32 rows; branch 0 starts from nothing
+                                               (3, 7, 90, 200, 1),    # ragged lengths next to a shared prefix
+                                               (2, 2, 0, 0, -1)])     # no context whatsoever: in-flight rows only
+def test_ragged_private_contexts_without_shared_prefix(N, gamma, S, R, R_min):
+    """State-evaluator shape (Section 3.2: different states, i.e. different prompts): branches with private
+    contexts of different lengths and an empty shared segment; the degenerate rows that see only themselves."""
+    w = wl.get_workload("c6").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
+                                     N=N, gamma=gamma, S=S, R=R, R_min=R_min, seed=177 + N)
+    c = Case(w).run_oracle().run_gpu()
+    c.compare()
+    if R_min >= 0:
+        assert c.plens[0] == R_min and c.plens[-1] == R
+
+
 def test_small_bf16_head128_long_private_context():
     """head_dim 128, 12 rows against 1000 shared and 260 private keys (three private key ranges)."""
     w = wl.get_workload("c3").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,

@@ -41,6 +41,7 @@ class Workload:
     q_noise_std: float
     kv_protocol: str        # "true_prefix" or "synthetic"
     seed: int               # weights seed; seed+1 prefix/KV, +2 q logits, +3 draft draws, +4 uniforms
+    R_min: int = -1         # >= 0: ragged private contexts, branch lengths seeded in [R_min, R]; < 0: all R
 
     def scaled(self, **kw):
         """Same workload with some fields replaced (e.g. fewer layers for a quick parity case)."""
@@ -66,6 +67,10 @@ WORKLOADS = {
                    q_noise_std=0.0, kv_protocol="synthetic", seed=4001),
     "c5": Workload("c5", _13B, N=8, gamma=5, S=4096, R=0, temperature=0.7, q_kind="perturbed", q_temp=0.7,
                    q_noise_std=0.5, kv_protocol="synthetic", seed=5001),
+    # State-evaluator shape (Section 3.2: the evaluator scores different states, i.e. different prompts): no
+    # shared prefix at all, every branch brings its own context of a different length.
+    "c6": Workload("c6", _7B, N=8, gamma=4, S=0, R=1024, temperature=0.7, q_kind="random", q_temp=1.0,
+                   q_noise_std=0.0, kv_protocol="synthetic", seed=6001, R_min=384),
 }
 
 

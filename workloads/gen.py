@@ -132,6 +132,18 @@ def pending_tokens(wl):
     return g.integers(0, wl.model.vocab, size=wl.N, dtype=np.int64).astype(np.int32)
 
 
+def private_lens(wl):
+    """[N] valid tokens of each branch's private context: all R, or seeded in [R_min, R] for ragged workloads
+    (then branch 0 gets R_min and branch N-1 gets R, so both ends occur)."""
+    if wl.R_min < 0 or wl.R_min >= wl.R:
+        return np.full(wl.N, wl.R, np.int32)
+    g = np.random.Generator(np.random.Philox(key=[np.uint64(wl.seed + 1), np.uint64(3)]))
+    lens = g.integers(wl.R_min, wl.R + 1, size=wl.N, dtype=np.int64).astype(np.int32)
+    lens[0] = wl.R_min
+    lens[-1] = wl.R
+    return lens
+
+
 def synthetic_kv(wl, layer):
     """Synthetic-KV protocol: post-RoPE K and V ~ N(0,1) for the shared prefix [H][S][dh] and the
     private contexts [N][H][R][dh] of one layer, on the storage grid of the model dtype."""
@@ -139,8 +151,10 @@ def synthetic_kv(wl, layer):
     bf16 = m.dtype == "bf16"
     H, dh = m.n_heads, m.head_dim
     base = 1000 + 4 * layer
-    ks = normal_tensor(wl.seed + 1, base + 0, (H, wl.S, dh), 1.0, 0.0, bf16)
-    vs = normal_tensor(wl.seed + 1, base + 1, (H, wl.S, dh), 1.0, 0.0, bf16)
+    ks = normal_tensor(wl.seed + 1, base + 0, (H, wl.S, dh), 1.0, 0.0, bf16) if wl.S else \
+        np.zeros((H, 0, dh), np.float32)
+    vs = normal_tensor(wl.seed + 1, base + 1, (H, wl.S, dh), 1.0, 0.0, bf16) if wl.S else \
+        np.zeros((H, 0, dh), np.float32)
     kp = normal_tensor(wl.seed + 1, base + 2, (wl.N, H, wl.R, dh), 1.0, 0.0, bf16) if wl.R else \
         np.zeros((wl.N, H, 0, dh), np.float32)
     vp = normal_tensor(wl.seed + 1, base + 3, (wl.N, H, wl.R, dh), 1.0, 0.0, bf16) if wl.R else \
