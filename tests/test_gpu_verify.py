@@ -50,6 +50,15 @@ def test_ragged_private_contexts_without_shared_prefix(N, gamma, S, R, R_min):
         assert c.plens[0] == R_min and c.plens[-1] == R
 
 
+@pytest.mark.parametrize("N,gamma", [(4, 4), (3, 5)])
+def test_small_bf16_bonus_row(N, gamma):
+    """gamma + 1 target rows per branch (the extra token after a fully accepted round), bf16 kernels, ragged
+    private contexts: 20 and 18 rows, i.e. a row-group boundary inside a branch."""
+    w = wl.get_workload("c6").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
+                                     N=N, gamma=gamma, S=50, R=30, R_min=2, seed=277 + N)
+    Case(w, bonus=True).run_oracle().run_gpu().compare()
+
+
 def test_small_bf16_head128_long_private_context():
     """head_dim 128, 12 rows against 1000 shared and 260 private keys (three private key ranges)."""
     w = wl.get_workload("c3").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,
