@@ -24,6 +24,8 @@
 //     both; emits the packed activation of the down projection).  The RMSNorm factor 1/rms of the input rows
 //     is applied AFTER the contraction: each consuming workgroup sums the producer's per-tile sums of squares
 //     in a fixed order at its start, while its first weight loads are already in flight.
+#include <map>
+#include <mutex>
 #include <type_traits>
 #include "seed_internal.h"
 #include "device_utils.h"
@@ -76,6 +78,187 @@ __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int
     *reinterpret_cast<uint2 *>(dst + kActLoOffset) = wl;
 }
 
+// Everything after the k loop, shared by both kernel forms: 1/rms of the input rows (unless the prologue had
+// it already), the cross-wavefront reduction of a workgroup's WK partial tiles, the split-K exchange between
+// workgroups, and the epilogue.  `smem` is the k loop's staging memory, reused for the reduction.
+template <int TM, int TN, int WN, int WK, int EPI, bool kPre>
+__device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN][TM], char *smem, int *s_last_p,
+                                             float *s_rinv, const f32x4 (&x_pre)[TN][TM], const uint2 (&gain_pre)[TN],
+                                             bool ssq_early, int nt0, bool active) {
+    using S = Shape<TM, TN, WN, WK>;
+    constexpr int kWaves = S::kWaves;
+    constexpr int RT = S::kRedTiles < TN * TM ? S::kRedTiles : TN * TM;   // tiles per reduction round
+    f32x4(*red)[WN][RT][64] = reinterpret_cast<f32x4(*)[WN][RT][64]>(smem);                 // [WK][WN][RT][64]
+    int &s_last = *s_last_p;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wn = w % WN, wk = w / WN;
+    const int g = lane >> 4, rlow = lane & 15;
+    const int nt_last = a.NT - 1;
+    if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
+        // 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order
+        // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
+        // four rows per wavefront at a time, all their loads in flight together (a row after a row would pay a
+        // memory latency each: twelve of them at 96 rows)
+        constexpr int kRowsAtOnce = 4, kPer = 8;
+        if (a.NT_in <= 64 * kPer) {
+            for (int row0 = w; row0 < a.M; row0 += kRowsAtOnce * kWaves) {
+                float v[kRowsAtOnce][kPer];
+#pragma unroll
+                for (int r = 0; r < kRowsAtOnce; ++r)
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) {
+                        const int row = min(row0 + r * kWaves, a.M - 1), t = lane + 64 * i;
+                        const float x = a.ssq_in[(size_t)row * a.NT_in + (t < a.NT_in ? t : 0)];
+                        v[r][i] = t < a.NT_in ? x : 0.f;
+                    }
+#pragma unroll
+                for (int r = 0; r < kRowsAtOnce; ++r) {
+                    float ssum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) ssum += v[r][i];
+                    ssum = wave_reduce_sum(ssum);
+                    const int row = row0 + r * kWaves;
+                    if (lane == 0 && row < a.M) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
+                }
+            }
+        } else {
+            for (int row = w; row < a.M; row += kWaves) {
+                float ssum = 0.f;
+                for (int t = lane; t < a.NT_in; t += 64) ssum += a.ssq_in[(size_t)row * a.NT_in + t];
+                ssum = wave_reduce_sum(ssum);
+                if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
+            }
+        }
+    }
+    __syncthreads();                                      // s_rinv visible; xs no longer read
+
+    if (WK > 1) {
+        // sum the WK partial tiles of each n-tile group through LDS (fixed order), RT tiles per round;
+        // wavefronts with wk == 0 end up holding the finished tiles
+#pragma unroll
+        for (int t0 = 0; t0 < TN * TM; t0 += RT) {
+            __syncthreads();                              // xs / the previous round is no longer read
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                if (t0 + t < TN * TM) red[wk][wn][t][lane] = acc[(t0 + t) / TM][(t0 + t) % TM];
+            __syncthreads();
+            if (wk == 0) {
+#pragma unroll
+                for (int t = 0; t < RT; ++t)
+                    if (t0 + t < TN * TM) {
+                        f32x4 s = red[0][wn][t][lane];
+#pragma unroll
+                        for (int i = 1; i < WK; ++i) s += red[i][wn][t][lane];
+                        acc[(t0 + t) / TM][(t0 + t) % TM] = s;
+                    }
+            }
+        }
+    }
+    const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
+
+    // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
+    const int ld_part = a.NT * 16;
+    if (a.SK > 1) {
+        // split-K across workgroups: publish the partial, then the last workgroup of this column group sums
+        // all partials in a fixed order
+        if (owner) {
+            float *pb = a.part + (size_t)blockIdx.y * a.M * ld_part;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = tm * 16 + rlow;
+                if (row >= a.M) continue;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    if (nt0 + tn <= nt_last)
+                        store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
+            }
+        }
+        if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
+        if (owner) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = tm * 16 + rlow;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (row < a.M && nt0 + tn <= nt_last) {
+                        const float *pp = a.part + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g;
+                        const size_t ps = (size_t)a.M * ld_part;
+                        int sk = 0;
+                        for (; sk + 4 <= a.SK; sk += 4) {        // four loads in flight; summed in fixed order
+                            const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
+                            const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
+                            s += p0;
+                            s += p1;
+                            s += p2;
+                            s += p3;
+                        }
+                        for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
+                    }
+                    acc[tn][tm] = s;
+                }
+            }
+        }
+    }
+
+    if (!owner) return;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int row = tm * 16 + rlow;
+        const bool valid = row < a.M;
+        if (EPI == EPI_STORE) {
+            const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
+            if (valid) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    if (nt0 + tn <= nt_last)
+                        *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + (nt0 + tn) * 16 + 4 * g) = acc[tn][tm] * sc;
+            }
+        } else if (EPI == EPI_RESID) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int col = (nt0 + tn) * 16 + 4 * g;
+                float ss = 0.f;
+                const bool tile_ok = nt0 + tn <= nt_last;
+                if (valid && tile_ok) {
+                    float *xp2 = a.x + (size_t)row * ld_part + col;
+                    f32x4 xv = (kPre ? x_pre[tn][tm] : *reinterpret_cast<f32x4 *>(xp2)) + acc[tn][tm];
+                    *reinterpret_cast<f32x4 *>(xp2) = xv;
+                    const uint2 gw = kPre ? gain_pre[tn]
+                                          : *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                    const float gv[4] = {bf2f((uint16_t)(gw.x & 0xffff)), bf2f((uint16_t)(gw.x >> 16)),
+                                         bf2f((uint16_t)(gw.y & 0xffff)), bf2f((uint16_t)(gw.y >> 16))};
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        ss += xv[i] * xv[i];
+                        v[i] = xv[i] * gv[i];
+                    }
+                    store_act4(a.act_out, row, col, a.KT_out, v);
+                }
+                ss += __shfl_xor(ss, 16);
+                ss += __shfl_xor(ss, 32);
+                if (valid && tile_ok && g == 0) a.ssq[(size_t)row * a.NT + nt0 + tn] = ss;
+            }
+        } else {   // EPI_SWIGLU: tiles (nt0 + 2p, nt0 + 2p + 1) = (gate, up) of feature block nt0 / 2 + p
+            if (valid) {
+                const float sc = s_rinv[row];
+#pragma unroll
+                for (int p = 0; p < TN / 2; ++p) {
+                    if (nt0 + 2 * p + 1 > nt_last) continue;          // ragged last group: no such feature block
+                    float h[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float gt = acc[2 * p][tm][i] * sc, up = acc[(2 * p + 1) % TN][tm][i] * sc;
+                        h[i] = gt / (1.0f + expf(-gt)) * up;
+                    }
+                    store_act4(a.act_out, row, ((nt0 >> 1) + p) * 16 + 4 * g, a.KT_out, h);
+                }
+            }
+        }
+    }
+}
+
 template <int TM, int TN, int WN, int WK, int EPI>
 __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     using S = Shape<TM, TN, WN, WK>;
@@ -90,7 +273,6 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     __shared__ int s_last;
     __shared__ float s_rinv[128];
     bf16x8(*xs)[TM][2][64] = reinterpret_cast<bf16x8(*)[TM][2][64]>(smem);                 // [XKT][TM][2][64]
-    f32x4(*red)[WN][RT][64] = reinterpret_cast<f32x4(*)[WN][RT][64]>(smem);                 // [WK][WN][RT][64]
     // All kernel arguments are fetched in ONE batch of scalar loads at the top: left alone, the compiler loads
     // each field just before its first use, and every such load is a round trip to memory (the argument
     // block is not in any cache when a launch starts) in front of the first weight request.
@@ -240,142 +422,242 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             for (int oc = 0; oc < OU; ++oc) chunk(k0 + (it * OU + oc) * XKT, oc, std::false_type{});
         }
     }
-    if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
-        // 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order
-        // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
-        for (int row = w; row < a.M; row += kWaves) {
-            float ssum = 0.f;
-            for (int t = lane; t < a.NT_in; t += 64) ssum += a.ssq_in[(size_t)row * a.NT_in + t];
-            ssum = wave_reduce_sum(ssum);
-            if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
-        }
-    }
-    __syncthreads();                                      // s_rinv visible; xs no longer read
+    finish_tiles<TM, TN, WN, WK, EPI, kPre>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, ssq_early, nt0, active);
+}
 
-    if (WK > 1) {
-        // sum the WK partial tiles of each n-tile group through LDS (fixed order), RT tiles per round;
-        // wavefronts with wk == 0 end up holding the finished tiles
-#pragma unroll
-        for (int t0 = 0; t0 < TN * TM; t0 += RT) {
-            __syncthreads();                              // xs / the previous round is no longer read
-#pragma unroll
-            for (int t = 0; t < RT; ++t)
-                if (t0 + t < TN * TM) red[wk][wn][t][lane] = acc[(t0 + t) / TM][(t0 + t) % TM];
-            __syncthreads();
-            if (wk == 0) {
-#pragma unroll
-                for (int t = 0; t < RT; ++t)
-                    if (t0 + t < TN * TM) {
-                        f32x4 s = red[0][wn][t][lane];
-#pragma unroll
-                        for (int i = 1; i < WK; ++i) s += red[i][wn][t][lane];
-                        acc[(t0 + t) / TM][(t0 + t) % TM] = s;
-                    }
-            }
-        }
-    }
-    const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
+// ---------------------------------------------------------------------------------------------------------
+// Form for three to eight row tiles (33..128 rows).  With that many rows a k-tile of activations is 6-16 KiB
+// and every wavefront reads all of it for each of its n-tiles: what limits the kernel is no longer HBM alone
+// but how many activation fragments a wavefront can have on their way from LDS while its MFMAs run, and how
+// many registers are left for weights in flight.  Differences from the form above:
+//   * the activation stages are filled by global -> LDS loads that bypass the registers (each lane's 16 bytes
+//     land at the stage base + 16 * lane, which is the fragment order the MFMAs read); NS stages of one weight
+//     group each, filled NS - 1 groups ahead, ONE workgroup barrier per group;
+//   * TN = 4 n-tiles per wavefront where the output is wide enough: each fragment read from LDS feeds 8 MFMAs;
+//   * the LDS reads are issued as one batch per k-tile and waited for fragment by fragment (inline assembly:
+//     the compiler, which cannot see that a read does not touch the stage being filled, would otherwise wait
+//     for the youngest global -> LDS load, and with it for every weight load issued before, ahead of each read).
+// Counting rule the waits rely on: per group every wavefront issues exactly P stage loads, then U * TN weight
+// loads, all unconditional with clamped addresses; loads complete in issue order.
+struct WideParams {
+    int U, GK, stage_bytes, NS, F, P, D, wait_stage, wait_weights;
+    bool valid;
+};
+constexpr WideParams wide_params(int TM, int TN, int WN, int WK) {
+    WideParams p{};
+    const int waves = WN * WK, budget = 144 * 1024;
+    // k-tiles per wavefront and group: two where a k-tile is only a few MFMAs, if three stages still fit
+    p.U = (TM * TN < 24 && 3 * (WK * 2 * TM * 2048) <= budget) ? 2 : 1;
+    p.GK = WK * p.U;                                      // k-tiles per group = per LDS stage
+    p.stage_bytes = p.GK * TM * 2048;
+    const int fit = budget / p.stage_bytes;
+    p.NS = fit > 4 ? 4 : fit;                             // stages
+    p.F = p.GK * TM * 2;                                  // 1 KiB fragments per stage
+    p.P = p.F / waves;                                    // stage loads per wavefront and group
+    // weight groups in flight per wavefront: about 16 KiB, and no more than the stages are filled ahead (a
+    // stage load completes only after the weight loads issued before it, so deeper rings gain nothing)
+    const int want = 16 / (p.U * TN) < 2 ? 2 : 16 / (p.U * TN);
+    p.D = want > p.NS - 1 ? p.NS - 1 : want;
+    // loads a wavefront may still have in flight at the end of group g with the stage of group g + 1 complete
+    p.wait_stage = (p.NS - 1) * p.U * TN + (p.NS - 2) * p.P;
+    // ... and when group g starts its MFMAs, with the weights requested D groups ago complete: the stage loads
+    // and weight loads of the D - 1 groups between, and this group's stage loads
+    p.wait_weights = (p.D - 1) * (p.P + p.U * TN) + p.P;
+    p.valid = p.NS >= 3 && p.F % waves == 0 && p.wait_stage < 64 && p.wait_weights < 64;   // (6-bit vmcnt)
+    return p;
+}
+template <int TM, int TN, int WN, int WK>
+struct WideShape {
+    static constexpr WideParams p = wide_params(TM, TN, WN, WK);
+    static constexpr int kWaves = WN * WK;
+    static constexpr int U = p.U, GK = p.GK, kStageBytes = p.stage_bytes, NS = p.NS, F = p.F, P = p.P, D = p.D;
+    static constexpr int kWaitStage = p.wait_stage, kWaitWeights = p.wait_weights;
+    static constexpr bool kValid = p.valid;
+};
 
-    // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
-    const int ld_part = a.NT * 16;
-    if (a.SK > 1) {
-        // split-K across workgroups: publish the partial, then the last workgroup of this column group sums
-        // all partials in a fixed order
-        if (owner) {
-            float *pb = a.part + (size_t)blockIdx.y * a.M * ld_part;
+// The loads of the k loop are issued and waited for by hand (inline assembly): with a global -> LDS load
+// among the pending ones the compiler's own counting falls back to "wait for everything" ahead of every use.
+// A register filled by such a load must not be touched before the matching wait; the waits take the
+// registers as in/out operands, so that nothing that uses them can be scheduled ahead of the wait.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N, int TN>
+__device__ __forceinline__ void wait_weights(bf16x8 (&wf)[TN]) {
+    static_assert(N >= 0 && N < 64 && (TN == 2 || TN == 4), "vmcnt is a 6-bit field");
+    if constexpr (TN == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(wf[0]), "+v"(wf[1]) : "n"(N));
+    else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]) : "n"(N));
+}
+// (wavefront-uniform 64-bit base in scalar registers + a 32-bit byte offset per lane: one address register
+// per load instead of two)
+__device__ __forceinline__ void load_weight_nt(bf16x8 &dst, const void *base, unsigned offset) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(offset), "s"(base));
+}
+
+// All 2 * TM fragments of one k-tile (hi and lo of every row tile; 1 KiB apart) in one batch.
+template <int TM>
+__device__ __forceinline__ void lds_read_ktile(bf16x8 (&f)[2 * TM], unsigned addr) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int row = tm * 16 + rlow;
-                if (row >= a.M) continue;
+    for (int i = 0; i < 2 * TM; ++i)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[i]) : "v"(addr), "n"(i * 1024));
+}
+// Wait until at most N of the batch's reads are outstanding; the fragments named become usable.
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8 &a, bf16x8 &b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+// The MFMAs of one k-tile, row tile by row tile: fragments 2 tm (hi) and 2 tm + 1 (lo) are waited for while the
+// 2 TM - 2 tm - 2 reads issued after them may still be on their way.
+template <int TM, int TN, int tm = 0>
+struct KtileMfma {
+    static __device__ __forceinline__ void run(bf16x8 (&f)[2 * TM], const bf16x8 (&wf)[TN], f32x4 (&acc)[TN][TM]) {
+        lds_wait<2 * TM - 2 * tm - 2>(f[2 * tm], f[2 * tm + 1]);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    if (nt0 + tn <= nt_last)
-                        store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
-            }
+        for (int tn = 0; tn < TN; ++tn) {
+            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[tn], f[2 * tm + 1], acc[tn][tm], 0, 0, 0);
+            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[tn], f[2 * tm], acc[tn][tm], 0, 0, 0);
         }
-        if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
-        if (owner) {
+        __builtin_amdgcn_sched_barrier(0);                // keep wait -> MFMAs -> next wait in this order
+        if constexpr (tm + 1 < TM) KtileMfma<TM, TN, tm + 1>::run(f, wf, acc);
+    }
+};
+
+template <int TM, int TN, int WN, int WK, int EPI>
+__global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
+    using S = WideShape<TM, TN, WN, WK>;
+    using S0 = Shape<TM, TN, WN, WK>;
+    constexpr int U = S::U, GK = S::GK, NS = S::NS, D = S::D, P = S::P, kWaves = S::kWaves;
+    constexpr int kStage = S::kStageBytes;
+    constexpr int RT = S0::kRedTiles < TN * TM ? S0::kRedTiles : TN * TM;
+    constexpr int RED_BYTES = (WK > 1) ? WK * WN * RT * 1024 : 16;
+    constexpr int XS_BYTES = NS * kStage;
+    static_assert(2 * TM * 1024 <= 65536, "ds_read offsets are 16-bit");
+    __shared__ __attribute__((aligned(1024))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
+    __shared__ int s_last;
+    __shared__ float s_rinv[128];
+    pin_args(a);
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (scalar: addresses below stay in SGPRs)
+    const int wn = w % WN, wk = w / WN;
+    const int nt0 = (blockIdx.x * WN + wn) * TN;
+    const bool active = nt0 < a.NT;
+    const int KT = a.KT;
+    const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
+    const int n_groups = (k1 - k0 + GK - 1) / GK;
+
+    f32x4 acc[TN][TM];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int row = tm * 16 + rlow;
+    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    if (row < a.M && nt0 + tn <= nt_last) {
-                        const float *pp = a.part + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g;
-                        const size_t ps = (size_t)a.M * ld_part;
-                        int sk = 0;
-                        for (; sk + 4 <= a.SK; sk += 4) {        // four loads in flight; summed in fixed order
-                            const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
-                            const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
-                            s += p0;
-                            s += p1;
-                            s += p2;
-                            s += p3;
+        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int nt_last = a.NT - 1;
+    unsigned woff[TN];                                   // byte offset of this lane's piece of k-tile 0 of each n-tile
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) woff[tn] = ((unsigned)min(nt0 + tn, nt_last) * (unsigned)KT * 64u + lane) * 16u;
+    const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(a.Xp) + lane;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
+
+    // stage load of group g: fragment f = w + i * kWaves of the stage, f = (kk * TM + tm) * 2 + hl; k-tiles past
+    // the end of the matrix are clamped (their MFMAs are skipped)
+    auto stage_load = [&](int g) {
+        const unsigned base = (unsigned)((g % NS) * kStage);
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            const int f = w + i * kWaves;
+            const int kk = f / (2 * TM), r = f - kk * (2 * TM);
+            const int kt = min(k0 + g * GK + kk, KT - 1);
+            const bf16x8 *src = xp + (((size_t)(r >> 1) * KT + kt) * 2 + (r & 1)) * 64;
+            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(smem + base + f * 1024), 16,
+                                             0, 0);
+        }
+    };
+    bf16x8 ring[D][U][TN];
+    auto load_a = [&](bf16x8 (&dst)[U][TN], int g) {     // this wavefront's k-tiles of group g (clamped)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const char *base = reinterpret_cast<const char *>(a.Wp) + (size_t)min(k0 + g * GK + wk * U + u, k1 - 1) * 1024;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) load_weight_nt(dst[u][tn], base, woff[tn]);
+        }
+    };
+    // prologue: the first NS - 1 stages and D weight groups, everything waited for once
+#pragma unroll
+    for (int g = 0; g < NS - 1; ++g) stage_load(g);
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd) load_a(ring[dd], dd);
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd)
+#pragma unroll
+        for (int u = 0; u < U; ++u) wait_weights<0, TN>(ring[dd][u]);
+    lds_barrier();
+
+    // One group.  DD = its ring slot.  TAIL = it belongs to the last round, which requests no further weights
+    // (a register that a load is still going to write must stay reserved until a wait covers that load: the
+    // result of a load nobody uses would be handed to other values at once) and where the k range may end
+    // inside the group; its waits count the loads that the groups before it really issued.
+    auto group = [&](int g, auto dd_tag, auto tail_tag) {
+        constexpr int DD = decltype(dd_tag)::value;
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        // loads issued after the weights of this group, which were requested at the end of group g - D
+        constexpr int kWaitW = TAIL ? (D - 1 - DD) * (P + U * TN) + (DD + 1) * P : S::kWaitWeights;
+        // loads issued after the stage loads of group g + 1 (start of group g + 2 - NS): the weight loads of
+        // those of the groups g + 2 - NS .. g that are not in the last round, the stage loads of the later ones
+        constexpr int kTailWeightGroups = NS - 2 - DD > 0 ? NS - 2 - DD : 0;
+        constexpr int kWaitS = TAIL ? kTailWeightGroups * U * TN + (NS - 2) * P : S::kWaitStage;
+        stage_load(g + NS - 1);                           // into the stage group g - 1 was read from
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned sbase = lds0 + (unsigned)((g % NS) * kStage) + lane * 16;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kk = wk * U + u;
+            wait_weights<kWaitW, TN>(ring[DD][u]);        // (also in a skipped k-tile: the registers stay reserved)
+            if (TAIL && k0 + g * GK + kk >= k1) continue; // (uniform)
+            bf16x8 f[2 * TM];
+            lds_read_ktile<TM>(f, sbase + (unsigned)(kk * TM * 2048));
+            KtileMfma<TM, TN>::run(f, ring[DD][u], acc);
+        }
+        if constexpr (!TAIL) load_a(ring[DD], g + D);     // refill this slot D groups ahead
+        wait_vmcnt<kWaitS>();                             // the stage of group g + 1 is complete (this wavefront's part)
+        lds_barrier();                                    // ... everybody's part; stage g % NS is free again
+    };
+    // groups in rounds of D (ring slots are compile-time indices); the last round is peeled
+    const int n_rounds = (n_groups + D - 1) / D;
+    auto round = [&](int r, auto tail_tag) {
+        const int g0 = r * D;
+        constexpr bool TAIL = decltype(tail_tag)::value;  // only the last round can be incomplete
+        group(g0, std::integral_constant<int, 0>{}, tail_tag);
+        if constexpr (D > 1) {
+            if (!TAIL || g0 + 1 < n_groups) {
+                group(g0 + 1, std::integral_constant<int, 1>{}, tail_tag);
+                if constexpr (D > 2) {
+                    if (!TAIL || g0 + 2 < n_groups) {
+                        group(g0 + 2, std::integral_constant<int, 2>{}, tail_tag);
+                        if constexpr (D > 3) {
+                            if (!TAIL || g0 + 3 < n_groups) group(g0 + 3, std::integral_constant<int, 3>{}, tail_tag);
                         }
-                        for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
                     }
-                    acc[tn][tm] = s;
                 }
             }
         }
-    }
-
-    if (!owner) return;
+        static_assert(D <= 4, "rounds are written out for up to four ring slots");
+    };
+    for (int r = 0; r < n_rounds - 1; ++r) round(r, std::false_type{});
+    if (n_rounds > 0) round(n_rounds - 1, std::true_type{});
+    // Everything still in flight lands before the registers and the staging memory get other uses: weights
+    // requested for groups past the end of the k range (the ring is named, so it stays reserved up to here)
+    // and stage loads past the last group.
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int row = tm * 16 + rlow;
-        const bool valid = row < a.M;
-        if (EPI == EPI_STORE) {
-            const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
-            if (valid) {
+    for (int dd = 0; dd < D; ++dd)
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    if (nt0 + tn <= nt_last)
-                        *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + (nt0 + tn) * 16 + 4 * g) = acc[tn][tm] * sc;
-            }
-        } else if (EPI == EPI_RESID) {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int col = (nt0 + tn) * 16 + 4 * g;
-                float ss = 0.f;
-                const bool tile_ok = nt0 + tn <= nt_last;
-                if (valid && tile_ok) {
-                    float *xp2 = a.x + (size_t)row * ld_part + col;
-                    f32x4 xv = (kPre ? x_pre[tn][tm] : *reinterpret_cast<f32x4 *>(xp2)) + acc[tn][tm];
-                    *reinterpret_cast<f32x4 *>(xp2) = xv;
-                    const uint2 gw = kPre ? gain_pre[tn]
-                                          : *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
-                    const float gv[4] = {bf2f((uint16_t)(gw.x & 0xffff)), bf2f((uint16_t)(gw.x >> 16)),
-                                         bf2f((uint16_t)(gw.y & 0xffff)), bf2f((uint16_t)(gw.y >> 16))};
-                    float v[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        ss += xv[i] * xv[i];
-                        v[i] = xv[i] * gv[i];
-                    }
-                    store_act4(a.act_out, row, col, a.KT_out, v);
-                }
-                ss += __shfl_xor(ss, 16);
-                ss += __shfl_xor(ss, 32);
-                if (valid && tile_ok && g == 0) a.ssq[(size_t)row * a.NT + nt0 + tn] = ss;
-            }
-        } else {   // EPI_SWIGLU: tiles (nt0 + 2p, nt0 + 2p + 1) = (gate, up) of feature block nt0 / 2 + p
-            if (valid) {
-                const float sc = s_rinv[row];
-#pragma unroll
-                for (int p = 0; p < TN / 2; ++p) {
-                    float h[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float gt = acc[2 * p][tm][i] * sc, up = acc[(2 * p + 1) % TN][tm][i] * sc;
-                        h[i] = gt / (1.0f + expf(-gt)) * up;
-                    }
-                    store_act4(a.act_out, row, ((nt0 >> 1) + p) * 16 + 4 * g, a.KT_out, h);
-                }
-            }
-        }
-    }
+        for (int u = 0; u < U; ++u) wait_weights<0, TN>(ring[dd][u]);
+    wait_vmcnt<0>();
+    f32x4 x_pre[TN][TM];
+    uint2 gain_pre[TN];
+    finish_tiles<TM, TN, WN, WK, EPI, false>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, false, nt0, active);
 }
 
 // Repack row-major W[n_rows][K] (bf16) into fragment tiles.  Destination tile index of source n-tile
@@ -425,6 +707,75 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
     }
 }
 
+// The wide form counts its own loads; a kernel that the compiler gave spill code (scratch loads and stores
+// are loads in that count too) must not run.  Checked once per kernel.
+int wide_kernel_usable(const void *kernel) {
+    static std::mutex mu;
+    static std::map<const void *, int> seen;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = seen.find(kernel);
+    if (it == seen.end()) {
+        hipFuncAttributes fa{};
+        const int rc = hip_fail(hipFuncGetAttributes(&fa, kernel), "hipFuncGetAttributes");
+        if (rc) return rc;
+        it = seen.emplace(kernel, (int)fa.localSizeBytes).first;
+    }
+    if (it->second != 0) {
+        set_error("gemm: this wide kernel was compiled with %d bytes of scratch per lane and is not used", it->second);
+        return SEED_E_UNSUPPORTED_DTYPE;
+    }
+    return SEED_OK;
+}
+
+template <int TM, int TN, int WN, int WK>
+int launch_wide_shape(const GemmArgs &a, int epi, hipStream_t st) {
+    using S = WideShape<TM, TN, WN, WK>;
+    if constexpr (!S::kValid) {
+        set_error("gemm: the wide form has no %dx%d workgroup with %d n-tiles for %d row tiles", WN, WK, TN, TM);
+        return SEED_E_CAPACITY;
+    } else {
+        GemmArgs b = a;
+        b.kt_per_split = (a.KT + a.SK - 1) / a.SK;
+        b.SK = (a.KT + b.kt_per_split - 1) / b.kt_per_split;
+        if (b.SK > 1 && (size_t)b.SK * a.M * a.NT * 16 > a.part_floats) {
+            set_error("gemm: %d-way split of %d x %d outputs exceeds the partial buffer (%zu floats)", b.SK, a.M,
+                      a.NT * 16, a.part_floats);
+            return SEED_E_CAPACITY;
+        }
+        if ((size_t)a.NT * a.KT * 1024 >= ((size_t)1 << 32)) {
+            set_error("gemm: the wide form addresses weights with 32-bit offsets (matrix of %d x %d tiles)", a.NT, a.KT);
+            return SEED_E_CAPACITY;
+        }
+        dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
+        int rc;
+        if (epi == EPI_SWIGLU) {
+            if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>))) return rc;
+            hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
+        } else if (epi == EPI_RESID) {
+            if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_RESID>))) return rc;
+            hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_RESID>), grid, block, 0, st, b);
+        } else {
+            if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_STORE>))) return rc;
+            hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_STORE>), grid, block, 0, st, b);
+        }
+        return hip_fail(hipGetLastError(), "gemm launch");
+    }
+}
+
+// Three to eight row tiles in the wide form: two or four n-tiles per wavefront.
+template <int TM>
+int launch_wide(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t st) {
+#define SEEDV_SHAPE(WNv, WKv)                                                             \
+    if (wn == WNv && wk == WKv)                                                           \
+        return tn == 4 ? launch_wide_shape<TM, 4, WNv, WKv>(a, epi, st) : launch_wide_shape<TM, 2, WNv, WKv>(a, epi, st);
+    if (tn == 2 || tn == 4) {
+        SEEDV_SHAPE(4, 2) SEEDV_SHAPE(2, 4) SEEDV_SHAPE(1, 8)
+    }
+#undef SEEDV_SHAPE
+    set_error("gemm: unsupported wide workgroup shape %dx%d with %d n-tiles", wn, wk, tn);
+    return SEED_E_INVALID_ARG;
+}
+
 // One or two row tiles (<= 32 rows): one or two n-tiles per wavefront, all workgroup shapes.
 template <int TM>
 int launch_small(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t st) {
@@ -457,10 +808,23 @@ int launch_large(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t
 
 // Launch with an explicit workgroup shape (wn x wk wavefronts, tn n-tiles per wavefront) and a.SK
 // workgroups along K.
-int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, int tn, hipStream_t st) {
+int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, int tn, int wide, hipStream_t st) {
     if (epi == EPI_SWIGLU && (tn < 2 || a.NT % 2 != 0)) {
         set_error("gemm: the SwiGLU epilogue needs paired tiles (tn=%d, NT=%d)", tn, a.NT);
         return SEED_E_INVALID_ARG;
+    }
+    if (wide) {
+        switch (m_tiles) {
+            case 3: return launch_wide<3>(a, epi, wn, wk, tn, st);
+            case 4: return launch_wide<4>(a, epi, wn, wk, tn, st);
+            case 5: return launch_wide<5>(a, epi, wn, wk, tn, st);
+            case 6: return launch_wide<6>(a, epi, wn, wk, tn, st);
+            case 7: return launch_wide<7>(a, epi, wn, wk, tn, st);
+            case 8: return launch_wide<8>(a, epi, wn, wk, tn, st);
+            default:
+                set_error("gemm: the wide form runs three to eight row tiles, not %d", m_tiles);
+                return SEED_E_INVALID_ARG;
+        }
     }
     switch (m_tiles) {
         case 1: return launch_small<1>(a, epi, wn, wk, tn, st);
@@ -481,8 +845,9 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
 // rows: wide outputs share activation fragments across wavefronts (WN); narrow outputs split K inside the
 // workgroup (WK), over all eight wavefronts when that gives one workgroup per CU without a split across
 // workgroups (no partials to exchange), else over four with two workgroups along K.
-void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk) {
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide) {
     *sk = 1;
+    *wide = 0;
     if (m_tiles <= 2) {
         *tn = (epi == EPI_SWIGLU || (NT >= 1300 && NT % 2 == 0)) ? 2 : 1;
         const int units = NT / *tn;                        // n-tile groups a wavefront owns one of
@@ -494,15 +859,20 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
         if (NT >= 1300) { *wn = 4; *wk = 2; }
         else if (NT >= 600) { *wn = 2; *wk = 4; }
         else { *wn = 2; *wk = 4; *sk = m_tiles <= 3 ? 2 : 4; }
+        // from five row tiles on the wide outputs run in the form that stages activations with global -> LDS loads
+        if (m_tiles >= 5 && NT >= 600) {
+            if (!wide_params(m_tiles, *tn, *wn, *wk).valid) { *wn = 4; *wk = 2; }   // (seven, eight row tiles)
+            *wide = wide_params(m_tiles, *tn, *wn, *wk).valid;
+        }
     }
     if (KT < 64) *sk = 1;
 }
 
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
-    int wn, wk, tn, sk;
-    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk);
+    int wn, wk, tn, sk, wide;
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide);
     if (a.SK < 1) a.SK = sk;
-    return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, st);
+    return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
 }
 
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,

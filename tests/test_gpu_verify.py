@@ -59,6 +59,16 @@ def test_small_bf16_bonus_row(N, gamma):
     Case(w, bonus=True).run_oracle().run_gpu().compare()
 
 
+@pytest.mark.parametrize("N,gamma", [(16, 5), (16, 6), (16, 8), (13, 7)])
+def test_wide_projection_form_ragged_k(N, gamma):
+    """65..128 rows with outputs wide enough for the projection form that stages activations by global -> LDS
+    loads (gate/up with 600 n-tiles, LM head with 1300), and a k extent (18 k-tiles) that ends inside a weight
+    group and inside a round of groups: five, six and eight row tiles."""
+    w = wl.get_workload("c4").scaled(n_layers=2, d_model=576, n_heads=9, head_dim=64, d_ff=4800, vocab=20800,
+                                     N=N, gamma=gamma, S=100, R=20, seed=377 + gamma)
+    Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
+
+
 def test_small_bf16_head128_long_private_context():
     """head_dim 128, 12 rows against 1000 shared and 260 private keys (three private key ranges)."""
     w = wl.get_workload("c3").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,
