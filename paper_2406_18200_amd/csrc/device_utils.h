@@ -1,5 +1,6 @@
 // Small device-side helpers for gfx950 kernels (wave64).
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -47,6 +48,27 @@ __device__ __forceinline__ float wave_reduce_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
+}
+
+// The same sum without the LDS crossbar for the first four steps: lanes are combined inside their row of 16 by
+// DPP moves (xor 1, xor 2, mirror of 8, mirror of 16: plain vector-ALU operands), and the four row sums are
+// read as scalars.  A __shfl_xor step is a ds_bpermute with its own round trip; six of them per value, for a
+// dozen values one after the other, is microseconds.  (Different association than wave_reduce_sum.)
+__device__ __forceinline__ float wave_reduce_sum_dpp(float v) {
+    auto step = [](float x, auto ctrl) {
+        const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, true);
+        return x + __builtin_bit_cast(float, moved);
+    };
+    v = step(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+    v = step(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+    v = step(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+    v = step(v, std::integral_constant<int, 0x140>{});   // row_mirror
+    const int bits = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(bits, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(bits, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(bits, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(bits, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 // Data handed from one workgroup to another INSIDE a launch (split-K partials, per-tile sums of squares)

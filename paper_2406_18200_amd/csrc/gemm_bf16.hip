@@ -78,6 +78,45 @@ __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int
     *reinterpret_cast<uint2 *>(dst + kActLoOffset) = wl;
 }
 
+// 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order: wavefront w
+// takes rows w, w + kWaves, ...; a row of up to 512 sums is two 16-byte loads per lane, and the loads of eight
+// rows are in flight together (row after row would pay a memory latency each: twelve of them at 96 rows).
+template <int kWaves>
+__device__ __forceinline__ void rows_rinv(const GemmArgs &a, float *s_rinv, int w, int lane) {
+    constexpr int kRowsAtOnce = 8;
+    const int nt_in = a.NT_in;
+    if (nt_in <= 512 && (nt_in & 3) == 0) {
+        for (int row0 = w; row0 < a.M; row0 += kRowsAtOnce * kWaves) {
+            f32x4 v[kRowsAtOnce][2];
+#pragma unroll
+            for (int r = 0; r < kRowsAtOnce; ++r)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int row = min(row0 + r * kWaves, a.M - 1), t = 4 * lane + 256 * i;
+                    // (the load itself is unconditional, its value masked: a select on the value lets the compiler
+                    // put the load under a branch, and a branch around a load drains the load queue at the join)
+                    const u32x4 x = *reinterpret_cast<const u32x4 *>(a.ssq_in + (size_t)row * nt_in + (t < nt_in ? t : 0));
+                    const uint32_t keep = t < nt_in ? 0xffffffffu : 0u;
+                    v[r][i] = __builtin_bit_cast(f32x4, x & keep);
+                }
+#pragma unroll
+            for (int r = 0; r < kRowsAtOnce; ++r) {
+                const f32x4 q = v[r][0] + v[r][1];
+                const float ssum = wave_reduce_sum_dpp((q[0] + q[1]) + (q[2] + q[3]));
+                // (no branch: every lane writes the one value; a row past the end repeats the last row's)
+                s_rinv[min(row0 + r * kWaves, a.M - 1)] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
+            }
+        }
+    } else {
+        for (int row = w; row < a.M; row += kWaves) {
+            float ssum = 0.f;
+            for (int t = lane; t < nt_in; t += 64) ssum += a.ssq_in[(size_t)row * nt_in + t];
+            ssum = wave_reduce_sum(ssum);
+            if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
+        }
+    }
+}
+
 // Everything after the k loop, shared by both kernel forms: 1/rms of the input rows (unless the prologue had
 // it already), the cross-wavefront reduction of a workgroup's WK partial tiles, the split-K exchange between
 // workgroups, and the epilogue.  `smem` is the k loop's staging memory, reused for the reduction.
@@ -95,40 +134,8 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
     const int g = lane >> 4, rlow = lane & 15;
     const int nt_last = a.NT - 1;
     if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
-        // 1/rms of the input rows from the producer's per-tile sums of squares, summed in a fixed order
         // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
-        // four rows per wavefront at a time, all their loads in flight together (a row after a row would pay a
-        // memory latency each: twelve of them at 96 rows)
-        constexpr int kRowsAtOnce = 4, kPer = 8;
-        if (a.NT_in <= 64 * kPer) {
-            for (int row0 = w; row0 < a.M; row0 += kRowsAtOnce * kWaves) {
-                float v[kRowsAtOnce][kPer];
-#pragma unroll
-                for (int r = 0; r < kRowsAtOnce; ++r)
-#pragma unroll
-                    for (int i = 0; i < kPer; ++i) {
-                        const int row = min(row0 + r * kWaves, a.M - 1), t = lane + 64 * i;
-                        const float x = a.ssq_in[(size_t)row * a.NT_in + (t < a.NT_in ? t : 0)];
-                        v[r][i] = t < a.NT_in ? x : 0.f;
-                    }
-#pragma unroll
-                for (int r = 0; r < kRowsAtOnce; ++r) {
-                    float ssum = 0.f;
-#pragma unroll
-                    for (int i = 0; i < kPer; ++i) ssum += v[r][i];
-                    ssum = wave_reduce_sum(ssum);
-                    const int row = row0 + r * kWaves;
-                    if (lane == 0 && row < a.M) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
-                }
-            }
-        } else {
-            for (int row = w; row < a.M; row += kWaves) {
-                float ssum = 0.f;
-                for (int t = lane; t < a.NT_in; t += 64) ssum += a.ssq_in[(size_t)row * a.NT_in + t];
-                ssum = wave_reduce_sum(ssum);
-                if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(a.NT_in * 16) + a.eps);
-            }
-        }
+        rows_rinv<kWaves>(a, s_rinv, w, lane);
     }
     __syncthreads();                                      // s_rinv visible; xs no longer read
 
@@ -589,10 +596,14 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     for (int g = 0; g < NS - 1; ++g) stage_load(g);
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) load_a(ring[dd], dd);
+    // the input rows' 1/rms while the first weights are on their way (its loads come back after them, so the
+    // wait inside is the prologue's wait)
+    if (EPI != EPI_RESID && a.ssq_in != nullptr) rows_rinv<kWaves>(a, s_rinv, w, lane);
 #pragma unroll
     for (int dd = 0; dd < D; ++dd)
 #pragma unroll
         for (int u = 0; u < U; ++u) wait_weights<0, TN>(ring[dd][u]);
+    wait_vmcnt<0>();
     lds_barrier();
 
     // One group.  DD = its ring slot.  TAIL = it belongs to the last round, which requests no further weights
@@ -657,7 +668,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     wait_vmcnt<0>();
     f32x4 x_pre[TN][TM];
     uint2 gain_pre[TN];
-    finish_tiles<TM, TN, WN, WK, EPI, false>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, false, nt0, active);
+    finish_tiles<TM, TN, WN, WK, EPI, false>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, /*ssq_early=*/true, nt0, active);
 }
 
 // Repack row-major W[n_rows][K] (bf16) into fragment tiles.  Destination tile index of source n-tile

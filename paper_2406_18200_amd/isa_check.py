@@ -55,6 +55,13 @@ def walk(blocks, order, kernel):
     steps = 0
     while work:
         name, pc, vm, lg = work.popleft()
+        # entries without a destination at the OLD end of a queue retire first and retire nothing else with
+        # them: dropping them changes no later verdict, and lets paths that differ only there (a store under a
+        # branch) fall together
+        while vm and vm[0] is None:
+            vm = vm[1:]
+        while lg and lg[0] == (-1, -1):
+            lg = lg[1:]
         key = (name, pc, vm, lg)
         if key in seen:
             continue
@@ -64,8 +71,8 @@ def walk(blocks, order, kernel):
         i = pc
         while True:
             steps += 1
-            if steps > 3_000_000:
-                print("  step bound reached"); return errors
+            if steps > 600_000:
+                errors.add("step bound reached: kernel not fully explored"); return errors
             if i >= len(ins):
                 idx = order.index(name)
                 if idx + 1 < len(order):
@@ -109,7 +116,7 @@ def walk(blocks, order, kernel):
             elif op.startswith('ds_write') or op.startswith('ds_store') or op.startswith('s_load') or op.startswith('s_buffer_load'):
                 lg.append((-1, -1))
             # keep the state bounded (older entries beyond what any wait distinguishes are complete in practice? no: keep)
-            if len(vm) > 80: vm = vm[-80:]
+            if len(vm) > 64: vm = vm[-64:]           # (the hardware counter holds 63: older ones have completed)
             i += 1
     return errors
 
