@@ -869,7 +869,13 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
         *tn = 2;
         if (NT >= 1300) { *wn = 4; *wk = 2; }
         else if (NT >= 600) { *wn = 2; *wk = 4; }
-        else { *wn = 2; *wk = 4; *sk = m_tiles <= 3 ? 2 : 4; }
+        else {
+            // narrow outputs: as many workgroups along k as bring the launch closest to one per CU
+            *wn = 2; *wk = 4;
+            const int groups = (NT + 3) / 4;
+            const int fill = (256 + groups / 2) / groups;
+            *sk = fill < 1 ? 1 : (fill > 4 ? 4 : fill);
+        }
         // from five row tiles on the wide outputs run in the form that stages activations with global -> LDS loads
         if (m_tiles >= 5 && NT >= 600) {
             if (!wide_params(m_tiles, *tn, *wn, *wk).valid) { *wn = 4; *wk = 2; }   // (seven, eight row tiles)
