@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per projection launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy
 # kernel of known size); see profiles/.  None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6,     # profiles/gemm_kernel_c3.md: 2 x 51,667 KiB fetched + 521 KiB written
-                          "c4": 135.7e6,     # profiles/verify_step_c4_c5.md: 2 x 61,251 KiB + 9,981 KiB
-                          "c5": 176.7e6}     # profiles/verify_step_c4_c5.md: 2 x 84,495 KiB + 3,602 KiB
+                          "c4": 135.7e6,     # profiles/verify_step_c4_c5.md: 2 x 61,258 KiB + 9,981 KiB
+                          "c5": 177.7e6}     # profiles/verify_step_c4_c5.md: 2 x 84,570 KiB + 4,399 KiB
 
 
 def wl_private_lens(w):
@@ -301,7 +301,7 @@ def main():
                  "useful_tflops": flops / (ms_per_step * 1e-3) / 1e12,
                  "mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                  "accepted_tokens": accepted, "wall_ms_per_step": wall_ms / args.steps},
-        "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming projection)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel / gemm_wide_kernel (weight-streaming projection)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                      "launches_per_step": launches / args.steps,
