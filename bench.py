@@ -122,7 +122,6 @@ def scheduled(args):
     n, G, L = wt.N, wt.gamma, args.scheduled
     prefix = wl.prefix_tokens(wt)
     first = gen.pending_tokens(wt)
-    u = wl.uniform24(wt.seed + 9, (3, n, L + G))
     s_t, s_d = torch.cuda.Stream(), torch.cuda.Stream()
     with torch.cuda.stream(s_t):
         up = UploadingWeights(wt.model, wt.seed, dev)
@@ -137,7 +136,7 @@ def scheduled(args):
                             max_shared=wd.S, max_private=L + 2 * G, device=dev)
         dctx.prefill_shared(i32(prefix, dev))
     torch.cuda.synchronize()
-    ud, ua, ur = (f32(x, dev) for x in u)
+    ud, ua, ur = sv.uniform_philox(wt.seed + 9, (3, n, L + G), device=dev)     # generated on the device: never crosses the host link
     units = sorted({n, max(1, (n + 1) // 2), 1}, reverse=True)
     results, ref = {}, None
     for unit in units:

@@ -206,6 +206,15 @@ int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, in
                       int32_t n_rows, int32_t vocab, void *hip_stream);
 
 /*
+ * The uniforms u of the accept test, of the residual draw and of the draft sampler (Section 3.1) generated on
+ * the device, so that they never cross the host link: out[i] (device, n floats) = (w >> 8) * 2^-24 in [0, 1),
+ * where w is word i % 4 of the Philox4x32-10 block (Salmon et al., SC'11) with counter (i / 4, 0, stream, 0) and
+ * key (seed, 0x5EED).  A pure function of (seed, stream, i): values are consumed by index, never "next from a
+ * stream", and equal the host generator of the test harness bit for bit.  n <= 2^34.
+ */
+int seed_uniform_philox(uint32_t seed, uint32_t stream, float *out, int64_t n, void *hip_stream);
+
+/*
  * Import externally produced KV for one layer (synthetic-KV protocol): k_shared / v_shared
  * [H][shared_len][dh] (keys already rotated), k_private / v_private [n_branches][H][private_len][dh],
  * all in the context's dtype, device pointers; private pointers may be NULL when private_len == 0.

@@ -6,4 +6,4 @@ of the path runs in the library's HIP kernels.  There is no CPU fallback: import
 any call raises if libseed_verify.so is missing.
 """
 from .binding import (SeedError, VerifyContext, accept_resample, sample_probs, load_library,  # noqa: F401
-                      library_path, ModelShape, sched_run)
+                      library_path, ModelShape, sched_run, uniform_philox)

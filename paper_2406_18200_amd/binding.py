@@ -69,7 +69,7 @@ class SchedArgsC(C.Structure):
 
 
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
-           "seed_accept_resample", "seed_sample_probs", "seed_kv_load", "seed_verify_status",
+           "seed_accept_resample", "seed_sample_probs", "seed_uniform_philox", "seed_kv_load", "seed_verify_status",
            "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_destroy", "seed_last_error",
            "seed_sched_workspace_bytes", "seed_sched_run")
 
@@ -96,6 +96,7 @@ def load_library():
     lib.seed_draft_step.argtypes = [C.c_void_p, C.POINTER(DraftArgsC)]
     lib.seed_accept_resample.argtypes = [C.POINTER(AcceptArgsC), C.c_void_p]
     lib.seed_sample_probs.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.seed_uniform_philox.argtypes = [C.c_uint32, C.c_uint32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.seed_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.c_int32, C.c_int32]
     lib.seed_verify_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
@@ -187,6 +188,15 @@ def sample_probs(probs, u):
     assert probs.stride(1) == 1
     out = torch.empty(n, dtype=torch.int32, device=probs.device)
     _check(lib.seed_sample_probs(_ptr(probs), probs.stride(0), _ptr(u), _ptr(out), n, V, _stream_handle()))
+    return out
+
+
+def uniform_philox(seed, shape, stream=0, device="cuda:0"):
+    """seed_uniform_philox: float32 uniforms on the 2^-24 grid, element i a pure function of (seed, stream, i)."""
+    import torch
+    lib = load_library()
+    out = torch.empty(shape, dtype=torch.float32, device=device)
+    _check(lib.seed_uniform_philox(int(seed) & 0xFFFFFFFF, int(stream) & 0xFFFFFFFF, _ptr(out), out.numel(), _stream_handle()))
     return out
 
 

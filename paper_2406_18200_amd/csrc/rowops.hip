@@ -267,6 +267,30 @@ __global__ void add_len_kernel(int32_t *len, int n, int delta, const int32_t *sl
     if (i < n) len[slot != nullptr ? min(max(slot[i], 0), n_slots - 1) : i] += delta;
 }
 
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11), from the
+// published definition: ten rounds of (c0, c1, c2, c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1,
+// lo(M0 c0)), the key bumped by the Weyl constants after each round.  Block b = counter (b, 0, stream, 0),
+// key (seed, 0x5EED); element i of the output is word i % 4 of block i / 4 as u = (word >> 8) * 2^-24: the
+// uniforms of the accept test and of the samplers (Section 3.1), consumed by index.  Integer work: bit-exact.
+__global__ void philox_uniform_kernel(uint32_t seed, uint32_t stream, float *__restrict__ out, int64_t n) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (4 * b >= n) return;
+    uint32_t c0 = (uint32_t)b, c1 = 0u, c2 = stream, c3 = 0u, k0 = seed, k1 = 0x5EEDu;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    const uint32_t w[4] = {c0, c1, c2, c3};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (4 * b + i < n) out[4 * b + i] = (float)(w[i] >> 8) * 5.9604644775390625e-08f;   // 2^-24: exact
+}
+
 }  // namespace
 
 int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,
@@ -337,6 +361,13 @@ int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, i
     if (n == 0) return SEED_OK;
     hipLaunchKernelGGL(add_len_kernel, dim3((n + 63) / 64), dim3(64), 0, st, len, n, delta, branch_slot, n_slots);
     return hip_fail(hipGetLastError(), "add_len launch");
+}
+
+int launch_philox_uniform(uint32_t seed, uint32_t stream, float *out, int64_t n, hipStream_t st) {
+    if (n == 0) return SEED_OK;
+    const int64_t blocks = ((n + 3) / 4 + 255) / 256;
+    hipLaunchKernelGGL(philox_uniform_kernel, dim3((unsigned)blocks), dim3(256), 0, st, seed, stream, out, n);
+    return hip_fail(hipGetLastError(), "philox launch");
 }
 
 }  // namespace seedv

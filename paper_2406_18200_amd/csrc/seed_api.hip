@@ -565,6 +565,14 @@ int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, in
     return launch_sample_probs(probs, row_stride, u, tok_out, n_rows, vocab, (hipStream_t)hip_stream);
 }
 
+int seed_uniform_philox(uint32_t seed, uint32_t stream, float *out, int64_t n, void *hip_stream) {
+    if (n < 0) { set_error("uniform: need n >= 0"); return SEED_E_INVALID_ARG; }
+    if (n == 0) return SEED_OK;
+    if (!out) { set_error("uniform: NULL pointer"); return SEED_E_NULL_PTR; }
+    if ((n + 3) / 4 > ((int64_t)1 << 32)) { set_error("uniform: the block counter is 32 bits (n <= 2^34)"); return SEED_E_CAPACITY; }
+    return launch_philox_uniform(seed, stream, out, n, (hipStream_t)hip_stream);
+}
+
 int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
     if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
     if (a == nullptr) { set_error("step args is NULL"); return SEED_E_NULL_PTR; }

@@ -63,6 +63,7 @@ int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, vo
 int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void *gain, float *x, void *act,
                       float *ssq, int M, int d, hipStream_t st);
 int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t st);
+int launch_philox_uniform(uint32_t seed, uint32_t stream, float *out, int64_t n, hipStream_t st);
 int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
                    void *k_shared, void *v_shared, void *k_priv, void *v_priv,
                    const int32_t *private_len, int M, int Mq,
