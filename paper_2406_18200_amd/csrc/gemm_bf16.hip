@@ -783,6 +783,8 @@ int launch_wide(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t 
         SEEDV_SHAPE(4, 2) SEEDV_SHAPE(2, 4) SEEDV_SHAPE(1, 8)
     }
 #undef SEEDV_SHAPE
+    // twelve wavefronts, six n-tiles per workgroup: 1376 n-tiles (7B gate/up) become 230 workgroups instead of 172
+    if (tn == 2 && wn == 3 && wk == 4) return launch_wide_shape<TM, 2, 3, 4>(a, epi, st);
     set_error("gemm: unsupported wide workgroup shape %dx%d with %d n-tiles", wn, wk, tn);
     return SEED_E_INVALID_ARG;
 }
@@ -879,6 +881,11 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
         // from five row tiles on the wide outputs run in the form that stages activations with global -> LDS loads
         if (m_tiles >= 5 && NT >= 600) {
             if (!wide_params(m_tiles, *tn, *wn, *wk).valid) { *wn = 4; *wk = 2; }   // (seven, eight row tiles)
+            // six n-tiles per workgroup (twelve wavefronts) where that still is one round of workgroups and
+            // eight would leave a quarter of the CUs idle: 7B gate/up, 1376 n-tiles, 230 workgroups instead of 172
+            if (*wn == 4 && (NT + 5) / 6 <= 256 && (NT + 7) / 8 < 200 && wide_params(m_tiles, 2, 3, 4).valid) {
+                *wn = 3; *wk = 4;
+            }
             *wide = wide_params(m_tiles, *tn, *wn, *wk).valid;
         }
     }
