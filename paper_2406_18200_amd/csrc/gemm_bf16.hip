@@ -493,8 +493,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 template <int N, int TN>
 __device__ __forceinline__ void wait_weights(bf16x8 (&wf)[TN]) {
-    static_assert(N >= 0 && N < 64 && (TN == 2 || TN == 4), "vmcnt is a 6-bit field");
-    if constexpr (TN == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(wf[0]), "+v"(wf[1]) : "n"(N));
+    static_assert(N >= 0 && N < 64 && (TN == 1 || TN == 2 || TN == 4), "vmcnt is a 6-bit field");
+    if constexpr (TN == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(wf[0]) : "n"(N));
+    else if constexpr (TN == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(wf[0]), "+v"(wf[1]) : "n"(N));
     else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(wf[0]), "+v"(wf[1]), "+v"(wf[2]), "+v"(wf[3]) : "n"(N));
 }
 // (wavefront-uniform 64-bit base in scalar registers + a 32-bit byte offset per lane: one address register
@@ -760,8 +761,13 @@ int launch_wide_shape(const GemmArgs &a, int epi, hipStream_t st) {
         dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
         int rc;
         if (epi == EPI_SWIGLU) {
-            if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>))) return rc;
-            hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
+            if constexpr (TN >= 2) {
+                if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>))) return rc;
+                hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
+            } else {
+                set_error("gemm: the SwiGLU epilogue needs paired tiles");
+                return SEED_E_INVALID_ARG;
+            }
         } else if (epi == EPI_RESID) {
             if ((rc = wide_kernel_usable((const void *)gemm_wide_kernel<TM, TN, WN, WK, EPI_RESID>))) return rc;
             hipLaunchKernelGGL((gemm_wide_kernel<TM, TN, WN, WK, EPI_RESID>), grid, block, 0, st, b);
@@ -785,6 +791,8 @@ int launch_wide(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t 
 #undef SEEDV_SHAPE
     // twelve wavefronts, six n-tiles per workgroup: 1376 n-tiles (7B gate/up) become 230 workgroups instead of 172
     if (tn == 2 && wn == 3 && wk == 4) return launch_wide_shape<TM, 2, 3, 4>(a, epi, st);
+    // ... and three n-tiles per workgroup, one per wavefront: 768 n-tiles (7B QKV) become 256 workgroups
+    if (tn == 1 && wn == 3 && wk == 4 && epi != EPI_SWIGLU) return launch_wide_shape<TM, 1, 3, 4>(a, epi, st);
     set_error("gemm: unsupported wide workgroup shape %dx%d with %d n-tiles", wn, wk, tn);
     return SEED_E_INVALID_ARG;
 }
@@ -885,6 +893,12 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
             // eight would leave a quarter of the CUs idle: 7B gate/up, 1376 n-tiles, 230 workgroups instead of 172
             if (*wn == 4 && (NT + 5) / 6 <= 256 && (NT + 7) / 8 < 200 && wide_params(m_tiles, 2, 3, 4).valid) {
                 *wn = 3; *wk = 4;
+            }
+            // ... and three (one per wavefront) for the mid-width outputs: 7B QKV, 768 n-tiles, 256 workgroups
+            // instead of 192
+            if (*wn == 2 && epi != EPI_SWIGLU && (NT + 2) / 3 <= 256 && (NT + 3) / 4 < 200 &&
+                wide_params(m_tiles, 1, 3, 4).valid) {
+                *wn = 3; *wk = 4; *tn = 1;
             }
             *wide = wide_params(m_tiles, *tn, *wn, *wk).valid;
         }
