@@ -181,6 +181,62 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
             }
         }
         if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
+        if constexpr (EPI != EPI_SWIGLU) {
+            // Every wavefront of the last workgroup finishes a share of the workgroup's tiles: the partials lie
+            // in global memory, so the wavefront that computed a tile need not be the one that sums it.  (With
+            // only the wk == 0 wavefronts at it, two of eight, this tail of a 4-way split at 96 rows took 13 us
+            // next to an 11 us k loop.)  Same order of summation as below: partial 0, 1, 2, ...
+            constexpr int kTilesN = WN * TN;
+            const size_t ps = (size_t)a.M * ld_part;
+            const int wu = __builtin_amdgcn_readfirstlane(w);
+            if (wu >= kWaves) return;
+            for (int t = wu; t < kTilesN * TM; t += kWaves) {
+                const int tg = t / TM, tm = t - tg * TM;
+                const int nt = blockIdx.x * kTilesN + tg;
+                if (nt > nt_last) continue;                  // (uniform) ragged last column group
+                const int row = tm * 16 + rlow, col = nt * 16 + 4 * g;
+                const bool valid = row < a.M;
+                f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (valid) {
+                    const float *pp = a.part + (size_t)row * ld_part + col;
+                    int sk = 0;
+                    for (; sk + 4 <= a.SK; sk += 4) {
+                        const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
+                        const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
+                        s += p0;
+                        s += p1;
+                        s += p2;
+                        s += p3;
+                    }
+                    for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
+                }
+                if (EPI == EPI_STORE) {
+                    const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
+                    if (valid) *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + col) = s * sc;
+                } else {
+                    float ss = 0.f;
+                    if (valid) {
+                        float *xp2 = a.x + (size_t)row * ld_part + col;
+                        const f32x4 xv = *reinterpret_cast<f32x4 *>(xp2) + s;
+                        *reinterpret_cast<f32x4 *>(xp2) = xv;
+                        const uint2 gw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                        const float gv[4] = {bf2f((uint16_t)(gw.x & 0xffff)), bf2f((uint16_t)(gw.x >> 16)),
+                                             bf2f((uint16_t)(gw.y & 0xffff)), bf2f((uint16_t)(gw.y >> 16))};
+                        float v[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            ss += xv[i] * xv[i];
+                            v[i] = xv[i] * gv[i];
+                        }
+                        store_act4(a.act_out, row, col, a.KT_out, v);
+                    }
+                    ss += __shfl_xor(ss, 16);
+                    ss += __shfl_xor(ss, 32);
+                    if (valid && g == 0) a.ssq[(size_t)row * a.NT + nt] = ss;
+                }
+            }
+            return;
+        }
         if (owner) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
