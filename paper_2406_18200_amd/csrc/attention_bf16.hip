@@ -583,7 +583,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
 #pragma unroll
         for (int u = 0; u < kB; ++u) {
             if (j0 + u > j) continue;
-            const float s = wave_reduce_sum(sc[u]) * P.scale_log2e;
+            const float s = wave_reduce_sum_dpp(sc[u]) * P.scale_log2e;   // (DPP: the keys of a row are a dependent chain)
             const float m_new = fmaxf(m, s);
             const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
             l = l * alpha + p;

@@ -436,7 +436,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             float ssum = 0.f;
 #pragma unroll
             for (int i = 0; i < kSsqPer; ++i) ssum += ssq_pre[r][i];       // same order as the late path
-            ssum = wave_reduce_sum(ssum);
+            ssum = wave_reduce_sum_dpp(ssum);
             const int row = w + r * kWaves;
             if (ssq_early && lane == 0 && row < a.M) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
         }
