@@ -17,13 +17,18 @@
 //   * v_mfma_f32_16x16x32_bf16 computes Y^T tiles: D[i = feature][j = token row].
 //   * Split-K across workgroups (narrow outputs need it to fill 256 CUs): partial sums go to an fp32 buffer,
 //     and the LAST workgroup to finish a column group (device-scope counter) re-reads all partials in a fixed
-//     order and runs the epilogue, so results are deterministic and no separate reduction kernel is needed.
+//     order (all its wavefronts, a share of the tiles each) and runs the epilogue, so results are deterministic
+//     and no separate reduction kernel is needed.
 //   * Epilogues: STORE (optional per-row scale = the RMSNorm factor of the input rows), RESID (residual add,
 //     next RMSNorm's gain folded into the packed hi/lo activation, per-tile sums of squares of the new
 //     residual rows), SWIGLU (gate and up tiles are interleaved in the packed weight so one wavefront holds
 //     both; emits the packed activation of the down projection).  The RMSNorm factor 1/rms of the input rows
 //     is applied AFTER the contraction: each consuming workgroup sums the producer's per-tile sums of squares
 //     in a fixed order at its start, while its first weight loads are already in flight.
+// Two kernel forms share the weight layout, the split-K exchange and the epilogues (finish_tiles):
+// gemm_kernel (1..4 row tiles, and the narrow outputs at any row count) and gemm_wide_kernel (5..8 row tiles
+// on outputs of 600 n-tiles and more; described where it is defined).  gemm_bf16_pick chooses form, workgroup
+// shape and split from measurements on the 7B / 13B projection shapes.
 #include <map>
 #include <mutex>
 #include <type_traits>
@@ -496,12 +501,17 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
 //   * the activation stages are filled by global -> LDS loads that bypass the registers (each lane's 16 bytes
 //     land at the stage base + 16 * lane, which is the fragment order the MFMAs read); NS stages of one weight
 //     group each, filled NS - 1 groups ahead, ONE workgroup barrier per group;
-//   * TN = 4 n-tiles per wavefront where the output is wide enough: each fragment read from LDS feeds 8 MFMAs;
+//   * one, two or four n-tiles per wavefront and workgroups of eight or twelve wavefronts (3 x 4: three per
+//     SIMD, at most 168 registers), chosen so that a launch is one round of workgroups over most of the CUs;
+//   * weights are addressed as a wavefront-uniform base in scalar registers plus one 32-bit lane offset per
+//     n-tile: with 64-bit per-lane addresses the kernel spilled at six row tiles;
 //   * the LDS reads are issued as one batch per k-tile and waited for fragment by fragment (inline assembly:
 //     the compiler, which cannot see that a read does not touch the stage being filled, would otherwise wait
 //     for the youngest global -> LDS load, and with it for every weight load issued before, ahead of each read).
 // Counting rule the waits rely on: per group every wavefront issues exactly P stage loads, then U * TN weight
-// loads, all unconditional with clamped addresses; loads complete in issue order.
+// loads, all unconditional with clamped addresses (the last round of groups issues no weight loads and counts
+// accordingly); loads complete in issue order.  tests/test_isa_inflight.py replays the compiled ISA against
+// these counts.
 struct WideParams {
     int U, GK, stage_bytes, NS, F, P, D, wait_stage, wait_weights;
     bool valid;
