@@ -952,21 +952,24 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
             const int fill = (256 + groups / 2) / groups;
             *sk = fill < 1 ? 1 : (fill > 4 ? 4 : fill);
         }
-        // from five row tiles on the wide outputs run in the form that stages activations with global -> LDS loads
-        if (m_tiles >= 5 && NT >= 600) {
-            if (!wide_params(m_tiles, *tn, *wn, *wk).valid) { *wn = 4; *wk = 2; }   // (seven, eight row tiles)
-            // six n-tiles per workgroup (twelve wavefronts) where that still is one round of workgroups and
-            // eight would leave a quarter of the CUs idle: 7B gate/up, 1376 n-tiles, 230 workgroups instead of 172
+        // The wide outputs run in the form that stages activations with global -> LDS loads: from five row tiles
+        // on always; from three on where a twelve-wavefront shape fits the output (measured at 40 rows on the 7B
+        // shapes: gate/up 42 -> 38 us, QKV 32 -> 29.5 us; elsewhere the first form is as fast or faster there).
+        if (NT >= 600) {
+            const bool five = m_tiles >= 5;
+            if (five && !wide_params(m_tiles, *tn, *wn, *wk).valid) { *wn = 4; *wk = 2; }   // (seven, eight row tiles)
             if (*wn == 4 && (NT + 5) / 6 <= 256 && (NT + 7) / 8 < 200 && wide_params(m_tiles, 2, 3, 4).valid) {
-                *wn = 3; *wk = 4;
+                // six n-tiles per workgroup where that still is one round of workgroups and eight would leave a
+                // quarter of the CUs idle: 7B gate/up, 1376 n-tiles, 230 workgroups instead of 172
+                *wn = 3; *wk = 4; *wide = 1;
+            } else if (*wn == 2 && epi != EPI_SWIGLU && (NT + 2) / 3 <= 256 && (NT + 3) / 4 < 200 &&
+                       wide_params(m_tiles, 1, 3, 4).valid) {
+                // three (one per wavefront) for the mid-width outputs: 7B QKV, 768 n-tiles, 256 workgroups
+                // instead of 192
+                *wn = 3; *wk = 4; *tn = 1; *wide = 1;
+            } else if (five) {
+                *wide = wide_params(m_tiles, *tn, *wn, *wk).valid;
             }
-            // ... and three (one per wavefront) for the mid-width outputs: 7B QKV, 768 n-tiles, 256 workgroups
-            // instead of 192
-            if (*wn == 2 && epi != EPI_SWIGLU && (NT + 2) / 3 <= 256 && (NT + 3) / 4 < 200 &&
-                wide_params(m_tiles, 1, 3, 4).valid) {
-                *wn = 3; *wk = 4; *tn = 1;
-            }
-            *wide = wide_params(m_tiles, *tn, *wn, *wk).valid;
         }
     }
     if (KT < 64) *sk = 1;

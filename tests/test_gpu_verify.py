@@ -60,12 +60,14 @@ def test_small_bf16_bonus_row(N, gamma):
 
 
 @pytest.mark.parametrize("N,gamma,vocab", [(16, 5, 20800), (16, 6, 20800), (16, 8, 20800), (13, 7, 20800),
-                                           (16, 6, 10400), (16, 5, 10400)])
+                                           (16, 6, 10400), (16, 5, 10400),
+                                           (8, 5, 20800), (8, 5, 10400), (16, 4, 20800)])   # 40 and 64 rows
 def test_wide_projection_form_ragged_k(N, gamma, vocab):
     """65..128 rows with outputs wide enough for the projection form that stages activations by global -> LDS
     loads (gate/up with 600 n-tiles, LM head with 1300 or 650), and a k extent (18 k-tiles) that ends inside a
-    weight group and inside a round of groups: five, six and eight row tiles; at six row tiles the LM heads run
-    the twelve-wavefront shapes (two n-tiles per wavefront at 1300 n-tiles, one at 650)."""
+    weight group and inside a round of groups: five, six and eight row tiles; at three and six row tiles the LM
+    heads run the twelve-wavefront shapes (two n-tiles per wavefront at 1300 n-tiles, one at 650); at four row
+    tiles there is no such shape and the first form runs."""
     w = wl.get_workload("c4").scaled(n_layers=2, d_model=576, n_heads=9, head_dim=64, d_ff=4800, vocab=vocab,
                                      N=N, gamma=gamma, S=100, R=20, seed=377 + gamma)
     Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
