@@ -17,6 +17,11 @@ def test_c4_7b_wide_sampled_branches():
     Case(wl.get_workload("c4"), branches=[0, 7, 15]).run_oracle().run_gpu().compare()
 
 
+def test_c4_7b_wide_greedy_sampled_branches():
+    """The same configuration in greedy verification mode (the second mode the configuration names)."""
+    Case(wl.get_workload("c4"), greedy=True, branches=[3, 12]).run_oracle().run_gpu().compare()
+
+
 def test_c5_13b_sampled_branches_random_q():
     """13B shapes, N=8 x gamma=5 over a 4096-token shared prefix, full 40 layers.  The draft distributions
     here are the random-logit kind: building the perturbed-target kind needs gamma sequential oracle passes

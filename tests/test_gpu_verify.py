@@ -73,6 +73,16 @@ def test_wide_projection_form_ragged_k(N, gamma, vocab):
     Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
 
 
+@pytest.mark.parametrize("N,gamma", [(16, 6), (3, 4)])
+def test_small_bf16_greedy_verification(N, gamma):
+    """Greedy verification (accept while the draft equals the target's argmax) through the bf16 kernels; the
+    argmax is taken on each side from its own logits, so branches whose top two logits are within the logits
+    tolerance are compared on validity only (the harness marks them)."""
+    w = wl.get_workload("c4").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,
+                                     N=N, gamma=gamma, S=300, R=33, seed=477 + N)
+    Case(w, greedy=True).run_oracle().run_gpu().compare()
+
+
 def test_small_bf16_head128_long_private_context():
     """head_dim 128, 12 rows against 1000 shared and 260 private keys (three private key ranges)."""
     w = wl.get_workload("c3").scaled(n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ff=1024, vocab=4096,
