@@ -28,7 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # kernel of known size); see profiles/.  None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {"c3": 106.3e6,     # profiles/gemm_kernel_c3.md: 2 x 51,667 KiB fetched + 521 KiB written
                           "c4": 135.7e6,     # profiles/verify_step_c4_c5.md: 2 x 61,258 KiB + 9,981 KiB
-                          "c5": 177.7e6}     # profiles/verify_step_c4_c5.md: 2 x 84,570 KiB + 4,399 KiB
+                          "c5": 177.7e6,     # profiles/verify_step_c4_c5.md: 2 x 84,570 KiB + 4,399 KiB
+                          "c6": 112.0e6}     # profiles/verify_step_c6.md: 2 x 53,528 KiB + 2,347 KiB
 
 
 def wl_private_lens(w):
