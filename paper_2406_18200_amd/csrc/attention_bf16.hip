@@ -811,7 +811,10 @@ void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_key
         *keys_per_range_priv = 128;
     } else {
         const int rounds = (cap_priv_keys + 127) / 128;
-        int kp = 512 / (N * H > 0 ? N * H : 1);
+        // about one branch workgroup per CU: with 8 branches x 32 heads of up to 1024 private keys, one range
+        // each (256 workgroups) was measured faster than two (512) and much faster than four or eight (every
+        // range adds a partial to write, read back and merge)
+        int kp = 256 / (N * H > 0 ? N * H : 1);
         if (kp < 1) kp = 1;
         if (kp > rounds) kp = rounds;
         if (kp > 32) kp = 32;
