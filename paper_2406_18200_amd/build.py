@@ -26,6 +26,23 @@ def build(verbose=True):
     return LIB
 
 
+def build_sweep(verbose=True):
+    """The stand-alone projection-kernel sweep (csrc/gemm_sweep.hip): a development tool, not part of the library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "gemm_sweep")
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc] + flags + [os.path.join(CSRC, "gemm_sweep.hip"), "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stdout)
+    return out
+
+
 if __name__ == "__main__":
-    build()
+    if "--sweep" in sys.argv[1:]:
+        build_sweep()
+    else:
+        build()
     sys.exit(0)
