@@ -11,7 +11,7 @@ outstanding loads per counter (vmcnt, lgkmcnt), retires entries at each s_waitcn
 (loads complete in issue order), and reports any instruction that names a register of an outstanding load.
 It also validates the compiler's own waits for the loads it tracks itself.
 
-Usage: python -m paper_2406_18200_amd.isa_check file.s [substring of the mangled kernel names to check]
+Usage: python tests/isa_check.py file.s [substring of the mangled kernel names to check]
 """
 import re, sys
 from collections import deque

@@ -9,7 +9,7 @@ import tempfile
 import pytest
 
 from paper_2406_18200_amd import build as B
-from paper_2406_18200_amd import isa_check
+import isa_check
 
 
 def test_checker_finds_a_planted_violation_and_accepts_the_fix():
