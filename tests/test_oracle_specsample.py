@@ -210,3 +210,25 @@ def test_bonus_row_and_bookkeeping_loop():
         L = np.minimum(L + n, l)
         step += 1
     assert (L == l).all()
+
+
+def test_softmax_temperature_closed_forms():
+    """p = softmax(logits / T): logits (0, ln 2) give (1/3, 2/3) at T = 1, (1/5, 4/5) at T = 1/2 (the odds 2 are
+    raised to the power 1/T) and (1, sqrt 2) / (1 + sqrt 2) at T = 2; a constant added to every logit changes
+    nothing; rows are independent.  Dividing by T is what Section 3.1's sampling temperature means: T -> 0
+    approaches the greedy choice, so a lower T must sharpen the distribution."""
+    ln2 = np.log(2.0)
+    z = np.array([0.0, ln2])
+    for T, want in ((1.0, [1 / 3, 2 / 3]), (0.5, [1 / 5, 4 / 5]), (2.0, [1 / (1 + 2 ** 0.5), 2 ** 0.5 / (1 + 2 ** 0.5)])):
+        got = oracle.softmax_temperature(z, T)
+        assert got.dtype == np.float32
+        assert np.allclose(got, want, rtol=0, atol=1e-7), (T, got)
+        assert np.allclose(oracle.softmax_temperature(z + 123.456, T), want, rtol=0, atol=1e-7)
+    # three logits, T = 1/3: odds (1 : 2 : 3) become (1 : 8 : 27)
+    got = oracle.softmax_temperature(np.log([1.0, 2.0, 3.0]), 1.0 / 3.0)
+    assert np.allclose(got, np.array([1, 8, 27]) / 36.0, atol=1e-7)
+    # batched rows are treated independently, along the last axis
+    rows = np.array([[0.0, ln2], [ln2, 0.0], [5.0, 5.0]])
+    assert np.allclose(oracle.softmax_temperature(rows, 1.0), [[1 / 3, 2 / 3], [2 / 3, 1 / 3], [0.5, 0.5]], atol=1e-7)
+    # large logits do not overflow
+    assert np.allclose(oracle.softmax_temperature(np.array([1000.0, 1000.0 + ln2]), 1.0), [1 / 3, 2 / 3], atol=1e-7)
