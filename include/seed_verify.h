@@ -107,7 +107,8 @@ typedef struct {
     float temperature;     /* > 0 unless greedy (LOGITS kind only)               */
     const float *p_or_logits; /* [N][n_target_rows][V]                           */
     const float *q;           /* [N][gamma][V]                                   */
-    const int32_t *draft_tok; /* [N][gamma], each in [0, V)                      */
+    const int32_t *draft_tok; /* [N][gamma], each in [0, V); an id outside is never
+                                 used as an index and counts as rejected          */
     const float *u_acc;       /* [N][gamma]                                      */
     const float *u_res;       /* [N]                                             */
     int32_t *accept_len;      /* [N]            out                              */
@@ -223,8 +224,10 @@ int seed_kv_load(seed_ctx *ctx, int32_t layer, const void *k_shared, const void 
                  int32_t shared_len, const void *k_private, const void *v_private,
                  int32_t n_branches, int32_t private_len);
 
-/* Synchronises the context's stream and returns the device status word (0 = clean; bit 0 = a branch
- * overflowed its private capacity) in *host_status, then clears it. */
+/* Synchronises the context's stream and returns the device status word in *host_status, then clears it.
+ * 0 = clean; bit 0 = a branch overflowed its private capacity (its out-of-range rows were dropped); bit 1 = a
+ * branch_slot entry was out of range (clamped); bit 2 = a draft token id of the accept step was outside
+ * [0, vocab) (treated as rejected); bit 3 = a row token id was outside [0, vocab) (clamped). */
 int seed_verify_status(seed_ctx *ctx, int32_t *host_status);
 
 /*
@@ -237,6 +240,22 @@ int seed_verify_status(seed_ctx *ctx, int32_t *host_status);
  */
 int seed_verify_profile_enable(seed_ctx *ctx, int32_t enable);
 int seed_verify_profile_read(seed_ctx *ctx, int64_t *launches, double *total_ms, double *weight_bytes);
+
+/*
+ * What a pair of timing events adds around a launch: brackets n_pairs launches of an empty kernel on the
+ * context's stream the same way, synchronises and returns the average elapsed time per pair in milliseconds.
+ * (The bracketed time of a projection launch minus this figure is the kernel's own duration as a kernel trace
+ * reports it, up to the empty kernel's own run time of about a microsecond.)  The profile must have been read.
+ */
+int seed_verify_profile_overhead(seed_ctx *ctx, int32_t n_pairs, double *ms_per_pair);
+
+/*
+ * Measurement aid: one launch that reads `bytes` (multiple of 16) of device memory at `buf` (16-byte aligned)
+ * once, with the access pattern of the weight-streaming projections and nothing else.  Timed by the caller
+ * over a buffer much larger than the 256 MB last-level cache, its rate is the practical ceiling of an
+ * HBM-bound kernel on this chip.  sink: NULL or 16 writable bytes (never written in practice).
+ */
+int seed_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *hip_stream);
 
 void seed_verify_destroy(seed_ctx *ctx);
 

@@ -70,7 +70,8 @@ class SchedArgsC(C.Structure):
 
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
            "seed_accept_resample", "seed_sample_probs", "seed_uniform_philox", "seed_kv_load", "seed_verify_status",
-           "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_destroy", "seed_last_error",
+           "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_profile_overhead", "seed_hbm_read_probe",
+           "seed_verify_destroy", "seed_last_error",
            "seed_sched_workspace_bytes", "seed_sched_run")
 
 
@@ -103,6 +104,8 @@ def load_library():
     lib.seed_verify_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.seed_verify_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                              C.POINTER(C.c_double)]
+    lib.seed_verify_profile_overhead.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
+    lib.seed_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.seed_verify_destroy.argtypes = [C.c_void_p]
     lib.seed_verify_destroy.restype = None
     lib.seed_sched_workspace_bytes.restype = C.c_size_t
@@ -198,6 +201,12 @@ def uniform_philox(seed, shape, stream=0, device="cuda:0"):
     out = torch.empty(shape, dtype=torch.float32, device=device)
     _check(lib.seed_uniform_philox(int(seed) & 0xFFFFFFFF, int(stream) & 0xFFFFFFFF, _ptr(out), out.numel(), _stream_handle()))
     return out
+
+
+def hbm_read_probe(buf):
+    """seed_hbm_read_probe: one streaming read of the device tensor `buf` on the current stream."""
+    lib = load_library()
+    _check(lib.seed_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size() // 16 * 16, None, _stream_handle()))
 
 
 class VerifyContext:
@@ -304,6 +313,12 @@ class VerifyContext:
         n, ms, by = C.c_int64(0), C.c_double(0), C.c_double(0)
         _check(self.lib.seed_verify_profile_read(self.handle, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
+
+    def profile_overhead(self, n_pairs=200):
+        """seed_verify_profile_overhead: milliseconds a pair of timing events adds around a launch."""
+        ms = C.c_double(0)
+        _check(self.lib.seed_verify_profile_overhead(self.handle, int(n_pairs), C.byref(ms)))
+        return ms.value
 
     def status(self):
         s = C.c_int32(0)

@@ -301,7 +301,8 @@ struct RowInfo {
 // by a group of 16 / rows wavefronts: softmax statistics (or argmax in greedy mode), p(x) and the accept test.
 // Phase 2: the whole workgroup draws the replacement / bonus token for the one row that needs it.
 __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_args a, const SliceStats *stats,
-                                                                int n_slices, const int32_t *slot, int n_slots) {
+                                                                int n_slices, const int32_t *slot, int n_slots,
+                                                                int32_t *status) {
     __shared__ Shared sm;
     __shared__ RowInfo ri;
     const int b = blockIdx.x;
@@ -393,15 +394,20 @@ __global__ __launch_bounds__(kBlock) void accept_resample_kernel(seed_accept_arg
             ri.best[r] = mi;
             int ok = 0;
             if (j < G) {
-                const int x = a.draft_tok[b * G + j];
+                // a draft id outside [0, V) is never used as an index: it reads as token 0, counts as rejected
+                // and raises bit 2 of the status word
+                const int x_raw = a.draft_tok[b * G + j];
+                const bool x_ok = (unsigned)x_raw < (unsigned)V;
+                const int x = x_ok ? x_raw : 0;
+                if (!x_ok && status != nullptr) atomicOr(status, 4);
                 if (a.greedy) {
-                    ok = (x == mi);
+                    ok = x_ok && (x == mi);
                     if (a.p_tok != nullptr) a.p_tok[b * G + j] = 0.f;
                 } else {
                     const TargetRow row{src, is_logits, mv, ri.sum[r], 1.0f / a.temperature};
-                    const float pj = row.p(x);
+                    const float pj = x_ok ? row.p(x) : 0.f;
                     if (a.p_tok != nullptr) a.p_tok[b * G + j] = pj;
-                    ok = __fmul_rn(a.u_acc[b * G + j], a.q[((size_t)b * G + j) * V + x]) < pj;
+                    ok = x_ok && __fmul_rn(a.u_acc[b * G + j], a.q[((size_t)b * G + j) * V + x]) < pj;
                 }
             }
             ri.ok[r] = ok;
@@ -534,8 +540,9 @@ size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices
 
 // scratch (optional, accept_scratch_bytes(n_branches * n_target_rows) bytes): with it the softmax statistics
 // of the rows are computed by a launch that fills the chip; without it inside the one workgroup per branch.
+// status (optional): device status word; bit 2 is raised by a draft token id outside [0, vocab).
 int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
-                  hipStream_t st) {
+                  int32_t *status, hipStream_t st) {
     if (a.n_branches == 0) return SEED_OK;
     const bool need_stats = a.probs_kind == SEED_KIND_LOGITS || a.greedy;
     SliceStats *stats = nullptr;
@@ -549,7 +556,7 @@ int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branc
                            a.greedy ? 1.0f : 1.0f / a.temperature, stats);
     }
     hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, stats, n_slices,
-                       branch_slot, n_slots);
+                       branch_slot, n_slots, status);
     return hip_fail(hipGetLastError(), "accept_resample launch");
 }
 

@@ -51,7 +51,8 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void rownorm_kernel(float *__restrict__ x, const float *__restrict__ part,
                                                       int SK, int64_t split_stride,
                                                       const int32_t *__restrict__ tok, const void *emb, int vocab,
-                                                      const void *gain, float eps, void *act, int M, int d) {
+                                                      const void *gain, float eps, void *act, int M, int d,
+                                                      int32_t *status) {
     const int r = blockIdx.x;
     const int n8 = d >> 3;
     if (r >= M) {
@@ -60,7 +61,10 @@ __global__ __launch_bounds__(256) void rownorm_kernel(float *__restrict__ x, con
         return;
     }
     int t = 0;
-    if (tok != nullptr) t = min(max(tok[r], 0), vocab - 1);
+    if (tok != nullptr) {
+        t = min(max(tok[r], 0), vocab - 1);               // an id outside the vocabulary is clamped and flagged
+        if (t != tok[r] && threadIdx.x == 0 && status != nullptr) atomicOr(status, 8);
+    }
     float ss = 0.f;
     for (int c8 = threadIdx.x; c8 < n8; c8 += 256) {
         const int c = c8 * 8;
@@ -226,9 +230,10 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(const float *__restrict__ q
 __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t *__restrict__ tok, const uint16_t *__restrict__ emb,
                                                          int vocab, const uint16_t *__restrict__ gain,
                                                          float *__restrict__ x, void *act, float *__restrict__ ssq,
-                                                         int d) {
+                                                         int d, int32_t *status) {
     const int r = blockIdx.x;
-    const int t = min(max(tok[r], 0), vocab - 1);
+    const int t = min(max(tok[r], 0), vocab - 1);          // an id outside the vocabulary is clamped and flagged
+    if (t != tok[r] && threadIdx.x == 0 && status != nullptr) atomicOr(status, 8);
     const int n8 = d >> 3;                                  // even: d is a multiple of 32
     for (int c8 = threadIdx.x; c8 < n8; c8 += 256) {
         const int c = c8 * 8;
@@ -261,6 +266,26 @@ __global__ void kv_import_kernel(const void *src, void *dst, int heads, int len,
         else reinterpret_cast<float *>(dst)[o] = reinterpret_cast<const float *>(src)[e];
     }
 }
+
+// Measurement aids: a pure streaming read (every lane 16-byte non-temporal loads, eight in flight, the way the
+// projection kernels read their weights) whose rate is the practical ceiling of a weight-streaming kernel on
+// this chip, and an empty kernel for calibrating what a pair of timing events adds around a launch.
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4 *__restrict__ src, size_t n16,
+                                                             u32x4 *__restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(src + i + k * stride);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc ^= v[k];
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    if (sink != nullptr && (acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5EEDF00Du) sink[0] = acc;   // keeps the loads alive
+}
+__global__ void empty_kernel() {}
 
 __global__ void add_len_kernel(int32_t *len, int n, int delta, const int32_t *slot, int n_slots) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -295,13 +320,13 @@ __global__ void philox_uniform_kernel(uint32_t seed, uint32_t stream, float *__r
 
 int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,
                    const void *emb, int vocab, const void *gain, float eps, void *act, int M, int Mp, int d,
-                   hipStream_t st) {
+                   int32_t *status, hipStream_t st) {
     if (bf16)
         hipLaunchKernelGGL(rownorm_kernel<true>, dim3(Mp), dim3(256), 0, st, x, part, SK, split_stride, tok, emb,
-                           vocab, gain, eps, act, M, d);
+                           vocab, gain, eps, act, M, d, status);
     else
         hipLaunchKernelGGL(rownorm_kernel<false>, dim3(Mp), dim3(256), 0, st, x, part, SK, split_stride, tok, emb,
-                           vocab, gain, eps, act, M, d);
+                           vocab, gain, eps, act, M, d, status);
     return hip_fail(hipGetLastError(), "rownorm launch");
 }
 
@@ -337,9 +362,9 @@ int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t 
 }
 
 int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void *gain, float *x, void *act,
-                      float *ssq, int M, int d, hipStream_t st) {
+                      float *ssq, int M, int d, int32_t *status, hipStream_t st) {
     hipLaunchKernelGGL(embed_norm_kernel, dim3(M), dim3(256), 0, st, tok, (const uint16_t *)emb, vocab,
-                       (const uint16_t *)gain, x, act, ssq, d);
+                       (const uint16_t *)gain, x, act, ssq, d, status);
     return hip_fail(hipGetLastError(), "embed_norm launch");
 }
 
@@ -361,6 +386,16 @@ int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, i
     if (n == 0) return SEED_OK;
     hipLaunchKernelGGL(add_len_kernel, dim3((n + 63) / 64), dim3(64), 0, st, len, n, delta, branch_slot, n_slots);
     return hip_fail(hipGetLastError(), "add_len launch");
+}
+
+int launch_hbm_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t st) {
+    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(256 * 8), dim3(256), 0, st, (const u32x4 *)buf, bytes / 16, (u32x4 *)sink);
+    return hip_fail(hipGetLastError(), "read probe launch");
+}
+
+int launch_empty(hipStream_t st) {
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, st);
+    return hip_fail(hipGetLastError(), "empty launch");
 }
 
 int launch_philox_uniform(uint32_t seed, uint32_t stream, float *out, int64_t n, hipStream_t st) {

@@ -304,7 +304,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         return SEED_E_CAPACITY;
     }
 
-    rc = launch_embed_norm(row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), x, at(c, L.act_d), ssq, M, d, st);
+    rc = launch_embed_norm(row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), x, at(c, L.act_d), ssq, M, d, status, st);
     if (rc) return rc;
     for (int l = 0; l < g.n_layers; ++l) {
         GemmArgs a{};
@@ -389,7 +389,7 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
         return profiled(c, (double)Nout * K * 4.0, [&]() { return launch_gemm_f32(W, X, out, M, Nout, K, ld, st); });
     };
     rc = launch_rownorm(false, x, nullptr, 0, 0, row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), g.rms_eps, act_d, M,
-                        M, d, st);
+                        M, d, status, st);
     if (rc) return rc;
     for (int l = 0; l < g.n_layers; ++l) {
         rc = gemm(layer_w(c, l, L.w_qkv), 3 * HD, d, act_d, part, 3 * HD);
@@ -405,7 +405,7 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
         rc = gemm(layer_w(c, l, L.w_o), d, HD, act_hd, part, d);
         if (rc) return rc;
         rc = launch_rownorm(false, x, part, 1, 0, nullptr, nullptr, V, layer_w(c, l, L.g_ffn), g.rms_eps, act_d, M, M, d,
-                            st);
+                            nullptr, st);
         if (rc) return rc;
         rc = gemm(layer_w(c, l, L.w_gu), 2 * F, d, act_d, part, 2 * F);
         if (rc) return rc;
@@ -414,7 +414,7 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
         rc = gemm(layer_w(c, l, L.w_d), d, F, act_f, part, d);
         if (rc) return rc;
         const void *next_gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
-        rc = launch_rownorm(false, x, part, 1, 0, nullptr, nullptr, V, next_gain, g.rms_eps, act_d, M, M, d, st);
+        rc = launch_rownorm(false, x, part, 1, 0, nullptr, nullptr, V, next_gain, g.rms_eps, act_d, M, M, d, nullptr, st);
         if (rc) return rc;
     }
     if (logits != nullptr) return gemm(at(c, L.lm), V, d, act_d, logits, V);
@@ -548,10 +548,34 @@ int seed_verify_profile_read(seed_ctx *c, int64_t *launches, double *total_ms, d
     return SEED_OK;
 }
 
+int seed_verify_profile_overhead(seed_ctx *c, int32_t n_pairs, double *ms_per_pair) {
+    if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
+    if (n_pairs < 1 || n_pairs > 100000 || ms_per_pair == nullptr) { set_error("profile_overhead: need 1 <= n_pairs <= 100000 and an output pointer"); return SEED_E_INVALID_ARG; }
+    const bool was = c->profiling;
+    if (c->ev_used != 0) { set_error("profile_overhead: read the recorded launches first"); return SEED_E_INVALID_ARG; }
+    c->profiling = true;
+    int rc = SEED_OK;
+    for (int i = 0; i < n_pairs && rc == SEED_OK; ++i) rc = profiled(c, 0.0, [&]() { return launch_empty(c->stream); });
+    c->profiling = was;
+    if (rc) return rc;
+    int64_t n = 0;
+    double ms = 0.0;
+    rc = seed_verify_profile_read(c, &n, &ms, nullptr);
+    if (rc) return rc;
+    *ms_per_pair = ms / (double)n;
+    return SEED_OK;
+}
+
+int seed_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *hip_stream) {
+    if (buf == nullptr) { set_error("read probe: buffer is NULL"); return SEED_E_NULL_PTR; }
+    if (bytes < 16 || ((uintptr_t)buf & 15) != 0) { set_error("read probe: need a 16-byte aligned buffer of at least 16 bytes"); return SEED_E_INVALID_ARG; }
+    return launch_hbm_read_probe(buf, bytes, sink, (hipStream_t)hip_stream);
+}
+
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     int rc = check_accept_args(args);
     if (rc) return rc;
-    return launch_accept(*args, nullptr, nullptr, 0, (hipStream_t)hip_stream);
+    return launch_accept(*args, nullptr, nullptr, 0, nullptr, (hipStream_t)hip_stream);
 }
 
 int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out, int32_t n_rows,
@@ -624,7 +648,8 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
     int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, a->branch_slot, logits);
     if (rc) return rc;
     if (a->accept != nullptr)
-        return launch_accept(acc, at(c, c->L.acc_stats), a->branch_slot, g.max_branches, c->stream);
+        return launch_accept(acc, at(c, c->L.acc_stats), a->branch_slot, g.max_branches, (int32_t *)at(c, c->L.status),
+                             c->stream);
     if (a->flags & SEED_STEP_COMMIT_ALL)
         return launch_add_len(a->private_len, N, T, a->branch_slot, g.max_branches, c->stream);
     return SEED_OK;

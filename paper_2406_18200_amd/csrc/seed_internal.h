@@ -18,7 +18,7 @@ int hip_fail(hipError_t e, const char *what);
 // ---- accept.hip ------------------------------------------------------------------------------
 size_t accept_scratch_bytes(int max_rows);
 int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
-                  hipStream_t st);   // scratch, branch_slot may be NULL
+                  int32_t *status, hipStream_t st);   // scratch, branch_slot, status may be NULL
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
@@ -57,11 +57,11 @@ int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile
 // ---- rowops.hip ----------------------------------------------------------------------------------
 int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,
                    const void *emb, int vocab, const void *gain, float eps, void *act, int M, int Mp, int d,
-                   hipStream_t st);
+                   int32_t *status, hipStream_t st);   // status may be NULL
 int launch_swiglu(bool bf16, const float *part, int SK, int64_t split_stride, void *act, int M, int Mp, int F,
                   hipStream_t st);
 int launch_embed_norm(const int32_t *tok, const void *emb, int vocab, const void *gain, float *x, void *act,
-                      float *ssq, int M, int d, hipStream_t st);
+                      float *ssq, int M, int d, int32_t *status, hipStream_t st);
 int launch_rope_table(float *table, int n_pos, int dh, float theta, hipStream_t st);
 int launch_philox_uniform(uint32_t seed, uint32_t stream, float *out, int64_t n, hipStream_t st);
 int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q_out, size_t q_plane,
@@ -71,6 +71,8 @@ int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q
                    int max_private, int32_t *status, hipStream_t st);
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
                      hipStream_t st);
+int launch_hbm_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t st);
+int launch_empty(hipStream_t st);
 int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,

@@ -147,6 +147,42 @@ def test_private_capacity_overflow_is_flagged_not_fatal():
     c.ctx.close()
 
 
+def test_token_ids_outside_the_vocabulary_are_flagged_not_indexed():
+    """A draft token id outside [0, V) handed to the accept step is never used as an index: it counts as
+    rejected, its p(x) reads 0 and bit 2 of the status word is raised; a row token id outside the vocabulary is
+    clamped and raises bit 3.  Every kernel exits normally and the other branches are unaffected."""
+    import torch
+    import workloads.device as D
+    w = wl.get_workload("c3").scaled(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ff=704, vocab=2000,
+                                     N=4, gamma=3, S=70, R=5, seed=321)
+    c = Case(w).run_oracle().run_gpu(keep_ctx=True)
+    c.compare()
+    inp, G, V = c.inp, w.gamma, w.model.vocab
+    good = [x.copy() for x in c.gpu_accept]
+    for bad_id, branch in ((V + 7, 1), (-3, 2), (2 ** 31 - 1, 0)):
+        drafts = inp["drafts"].copy()
+        drafts[branch, G - 1] = bad_id                       # the last draft is not among the fed rows
+        c.dev_plen.fill_(w.R)
+        acc = dict(q=D.f32(inp["q"]), draft_tok=D.i32(drafts), u_acc=D.f32(inp["u_acc"]), u_res=D.f32(inp["u_res"]),
+                   temperature=w.temperature)
+        outs = [o.cpu().numpy() for o in c.ctx.step(D.i32(inp["row_tok"]), w.S, c.dev_plen, accept=acc)]
+        torch.cuda.synchronize()
+        assert c.ctx.status() == 4
+        a, out, n, ptok = outs
+        assert a[branch] == min(good[0][branch], G - 1) and ptok[branch, G - 1] == 0.0
+        assert n[branch] == a[branch] + 1 and 0 <= out[branch, a[branch]] < V
+        others = [b for b in range(w.N) if b != branch]
+        for g, o in zip(good, outs):
+            assert np.array_equal(g[others], o[others])
+    rows = inp["row_tok"].copy()
+    rows[3, 1] = V                                           # first id past the end
+    c.dev_plen.fill_(w.R)
+    c.ctx.step(D.i32(rows), w.S, c.dev_plen)
+    torch.cuda.synchronize()
+    assert c.ctx.status() == 8 and c.ctx.status() == 0
+    c.ctx.close()
+
+
 def test_empty_and_single_row_steps():
     import torch
     import workloads.device as D
