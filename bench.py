@@ -240,20 +240,19 @@ def measure_verify(w, args, dev, with_inputs=False):
     plen = plen0.clone()
     if q is None:
         # q_j = softmax((target logits_j + noise) / temp), drafts sampled autoregressively (timing run: the
-        # target logits come from the library itself, one single-row step per draft position)
+        # target logits come from the library itself, one step per draft position)
         q = np.zeros((N, G, m.vocab), np.float32)
         drafts = np.zeros((N, G), np.int32)
         u_d = wl.uniform24(w.seed + 3, (N, G))
-        cur = pending.copy()
-        lg = torch.empty((N, 1, m.vocab), dtype=torch.float32, device=dev)
+        rows = pending[:, None].astype(np.int32)
         for j in range(G):
-            ctx.step(i32(cur[:, None], dev), w.S, plen, flags=4, logits_out=lg)   # COMMIT_ALL: keep the row
-            ell = lg.cpu().numpy()[:, 0]
+            lg = torch.empty((N, j + 1, m.vocab), dtype=torch.float32, device=dev)
+            ctx.step(i32(rows, dev), w.S, plen, logits_out=lg)        # pending token + drafts so far, nothing committed
+            ell = lg[:, j].cpu().numpy()
             for b in range(N):
                 q[b, j] = wl.perturbed_draft_q(w, ell[b], b, j)
             drafts[:, j] = wl.draw_tokens(q[:, j], u_d[:, j])
-            cur = drafts[:, j].copy()
-        plen.copy_(plen0)
+            rows = np.concatenate([rows, drafts[:, j:j + 1]], axis=1).astype(np.int32)
     else:
         drafts = wl.draw_tokens(q, wl.uniform24(w.seed + 3, (N, G)))
     row_tok = np.concatenate([pending[:, None], drafts[:, :T - 1]], axis=1).astype(np.int32)

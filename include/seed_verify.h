@@ -242,10 +242,11 @@ int seed_verify_profile_enable(seed_ctx *ctx, int32_t enable);
 int seed_verify_profile_read(seed_ctx *ctx, int64_t *launches, double *total_ms, double *weight_bytes);
 
 /*
- * What a pair of timing events adds around a launch: brackets n_pairs launches of an empty kernel on the
- * context's stream the same way, synchronises and returns the average elapsed time per pair in milliseconds.
- * (The bracketed time of a projection launch minus this figure is the kernel's own duration as a kernel trace
- * reports it, up to the empty kernel's own run time of about a microsecond.)  The profile must have been read.
+ * What a pair of timing events adds around a launch: brackets n_pairs launches of a one-wavefront kernel that
+ * runs for about 20 microseconds by the device's constant-rate wall clock (and records how long it really ran)
+ * the same way, synchronises, and returns (time between the events - time the kernel ran) per pair, in
+ * milliseconds.  The bracketed time of a projection launch minus this figure is the kernel's own duration as a
+ * kernel trace reports it.  The profile must have been read.
  */
 int seed_verify_profile_overhead(seed_ctx *ctx, int32_t n_pairs, double *ms_per_pair);
 

@@ -21,3 +21,5 @@ from .transformer import decode_rows, verify_forward, rms_norm, rope_rotate  # n
 from .specsample import (softmax_temperature, accept_resample, fixed_point_draw,  # noqa: F401
                          sample_from_probs, commit_lengths)
 from .specdecode import speculative_rounds  # noqa: F401
+from .spectree import (tree_from_k_config, tree_forward, accept_resample_tree, commit_rows_tree,  # noqa: F401
+                       children_of, path_to)

@@ -272,20 +272,32 @@ __global__ void kv_import_kernel(const void *src, void *dst, int heads, int len,
 // this chip, and an empty kernel for calibrating what a pair of timing events adds around a launch.
 __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4 *__restrict__ src, size_t n16,
                                                              u32x4 *__restrict__ sink) {
+    constexpr int kInFlight = 16;
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
-    for (; i + 7 * stride < n16; i += 8 * stride) {
-        u32x4 v[8];
+    for (; i + (kInFlight - 1) * stride < n16; i += kInFlight * stride) {
+        u32x4 v[kInFlight];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(src + i + k * stride);
+        for (int k = 0; k < kInFlight; ++k) v[k] = __builtin_nontemporal_load(src + i + k * stride);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc ^= v[k];
+        for (int k = 0; k < kInFlight; ++k) acc ^= v[k];
     }
     for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
     if (sink != nullptr && (acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5EEDF00Du) sink[0] = acc;   // keeps the loads alive
 }
-__global__ void empty_kernel() {}
+
+// One wavefront that runs for a known time: it reads the constant-rate wall clock, waits until `ticks` have
+// passed (bounded: it gives up after max_polls readings) and adds what really passed to *elapsed_total.  The
+// time between a pair of timing events around it, minus that, is what the pair itself adds to a launch.
+__global__ void calib_spin_kernel(unsigned long long ticks, unsigned long long max_polls,
+                                  unsigned long long *elapsed_total) {
+    if (threadIdx.x != 0) return;
+    const unsigned long long t0 = wall_clock64();
+    unsigned long long t = t0;
+    for (unsigned long long i = 0; i < max_polls && t - t0 < ticks; ++i) t = wall_clock64();
+    atomicAdd(elapsed_total, t - t0);
+}
 
 __global__ void add_len_kernel(int32_t *len, int n, int delta, const int32_t *slot, int n_slots) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -389,13 +401,13 @@ int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, i
 }
 
 int launch_hbm_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t st) {
-    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(256 * 8), dim3(256), 0, st, (const u32x4 *)buf, bytes / 16, (u32x4 *)sink);
+    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(256 * 16), dim3(256), 0, st, (const u32x4 *)buf, bytes / 16, (u32x4 *)sink);
     return hip_fail(hipGetLastError(), "read probe launch");
 }
 
-int launch_empty(hipStream_t st) {
-    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, st);
-    return hip_fail(hipGetLastError(), "empty launch");
+int launch_calib_spin(unsigned long long ticks, unsigned long long *elapsed_total, hipStream_t st) {
+    hipLaunchKernelGGL(calib_spin_kernel, dim3(1), dim3(64), 0, st, ticks, 1ull << 22, elapsed_total);
+    return hip_fail(hipGetLastError(), "calibration launch");
 }
 
 int launch_philox_uniform(uint32_t seed, uint32_t stream, float *out, int64_t n, hipStream_t st) {

@@ -551,18 +551,32 @@ int seed_verify_profile_read(seed_ctx *c, int64_t *launches, double *total_ms, d
 int seed_verify_profile_overhead(seed_ctx *c, int32_t n_pairs, double *ms_per_pair) {
     if (c == nullptr) { set_error("context is NULL"); return SEED_E_NOT_INIT; }
     if (n_pairs < 1 || n_pairs > 100000 || ms_per_pair == nullptr) { set_error("profile_overhead: need 1 <= n_pairs <= 100000 and an output pointer"); return SEED_E_INVALID_ARG; }
-    const bool was = c->profiling;
     if (c->ev_used != 0) { set_error("profile_overhead: read the recorded launches first"); return SEED_E_INVALID_ARG; }
+    int dev = 0, khz = 0;
+    int rc = hip_fail(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    rc = hip_fail(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev), "wall clock rate");
+    if (rc) return rc;
+    if (khz <= 0) { set_error("profile_overhead: the device reports no wall clock rate"); return SEED_E_HIP; }
+    // the counter lives in the status block, past the status word
+    unsigned long long *total = reinterpret_cast<unsigned long long *>((char *)at(c, c->L.status) + 64);
+    rc = hip_fail(hipMemsetAsync(total, 0, 8, c->stream), "calibration clear");
+    if (rc) return rc;
+    const unsigned long long ticks = (unsigned long long)khz * 20 / 1000;        // 20 microseconds
+    const bool was = c->profiling;
     c->profiling = true;
-    int rc = SEED_OK;
-    for (int i = 0; i < n_pairs && rc == SEED_OK; ++i) rc = profiled(c, 0.0, [&]() { return launch_empty(c->stream); });
+    for (int i = 0; i < n_pairs && rc == SEED_OK; ++i)
+        rc = profiled(c, 0.0, [&]() { return launch_calib_spin(ticks, total, c->stream); });
     c->profiling = was;
     if (rc) return rc;
     int64_t n = 0;
     double ms = 0.0;
-    rc = seed_verify_profile_read(c, &n, &ms, nullptr);
+    rc = seed_verify_profile_read(c, &n, &ms, nullptr);      // synchronises the stream
     if (rc) return rc;
-    *ms_per_pair = ms / (double)n;
+    unsigned long long spent = 0;
+    rc = hip_fail(hipMemcpy(&spent, total, 8, hipMemcpyDeviceToHost), "calibration read");
+    if (rc) return rc;
+    *ms_per_pair = (ms - (double)spent / (double)khz) / (double)n;
     return SEED_OK;
 }
 

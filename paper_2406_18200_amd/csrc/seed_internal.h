@@ -72,7 +72,7 @@ int launch_rope_kv(bool bf16, const float *qkv, const float *rope_table, void *q
 int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int heads, int len, int dh, int cap,
                      hipStream_t st);
 int launch_hbm_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t st);
-int launch_empty(hipStream_t st);
+int launch_calib_spin(unsigned long long ticks, unsigned long long *elapsed_total, hipStream_t st);
 int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,

@@ -226,20 +226,19 @@ class Case:
 
     def _fill_q_with_library(self, ctx, plen):
         """q of the branches the oracle does not evaluate: perturbed copies of the LIBRARY's own target logits,
-        one single-row step per draft position (the oracle's branches are fed their oracle-made drafts)."""
+        one step per draft position (the oracle's branches are fed their oracle-made drafts)."""
         w, m, inp = self.w, self.w.model, self.inp
         todo, G = inp["fill_with_library"], w.gamma
-        keep = plen.clone()
-        cur = inp["pending"].copy()
-        lg = torch.empty((w.N, 1, m.vocab), dtype=torch.float32, device=self.device)
+        rows = inp["pending"][:, None].astype(np.int32)
         for j in range(G):
-            ctx.step(i32(cur[:, None], self.device), w.S, plen, flags=B.SEED_STEP_COMMIT_ALL, logits_out=lg)
-            ell = lg.cpu().numpy()[:, 0]
+            # position j's target logits: a step over the pending token and the drafts so far, nothing committed
+            lg = torch.empty((w.N, j + 1, m.vocab), dtype=torch.float32, device=self.device)
+            ctx.step(i32(rows, self.device), w.S, plen, logits_out=lg)
+            ell = lg[:, j].cpu().numpy()
             for b in todo:
                 inp["q"][b, j] = wl.perturbed_draft_q(w, ell[b], b, j)
                 inp["drafts"][b, j] = wl.draw_tokens(inp["q"][b, j][None], inp["u_draft"][b, j][None])[0]
-            cur = inp["drafts"][:, j].copy()
-        plen.copy_(keep)
+            rows = np.concatenate([rows, inp["drafts"][:, j:j + 1]], axis=1).astype(np.int32)
         T = inp["T"]
         inp["row_tok"] = np.concatenate([inp["pending"][:, None], inp["drafts"][:, :T - 1]], axis=1).astype(np.int32)
 
