@@ -200,6 +200,20 @@ int seed_draft_step(seed_ctx *ctx, const seed_draft_args *args);
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream);
 
 /*
+ * The same accept / resample for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It runs the two-launch form
+ * of the accept step (row statistics spread over the chip, then one workgroup per branch) that a verify step
+ * runs out of its context's workspace, with the statistics in an array that is part of the library's device
+ * image: this call allocates nothing and frees nothing.  At most 4096 target rows (n_branches *
+ * n_target_rows), else SEED_E_CAPACITY; the array is 1 MiB per GPU, held until the process ends.  Arguments,
+ * outputs and errors otherwise as seed_accept_resample; the probabilities of the LOGITS kind may differ from
+ * that entry point's in the last bits (the statistics are summed slice by slice).  Every call on a GPU uses
+ * that GPU's one array: calls that overlap on one GPU (two streams, two threads) race; calls on one stream
+ * are ordered.  Nothing in the array has to be cleared between calls.
+ */
+int seed_accept_resample_static(const seed_accept_args *args, void *hip_stream);
+
+/*
  * Stateless draw x ~ probs rows by the fixed-point inverse CDF (the draft-side sampler of Section 3.1).
  * probs: n_rows rows of V floats, row i at probs + i * row_stride; u: [n_rows]; tok_out: [n_rows].
  */

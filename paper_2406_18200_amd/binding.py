@@ -69,7 +69,7 @@ class SchedArgsC(C.Structure):
 
 
 EXPORTS = ("seed_verify_workspace_bytes", "seed_verify_init", "seed_verify_step", "seed_draft_step",
-           "seed_accept_resample", "seed_sample_probs", "seed_uniform_philox", "seed_kv_load", "seed_verify_status",
+           "seed_accept_resample", "seed_accept_resample_static", "seed_sample_probs", "seed_uniform_philox", "seed_kv_load", "seed_verify_status",
            "seed_verify_profile_enable", "seed_verify_profile_read", "seed_verify_profile_overhead", "seed_hbm_read_probe",
            "seed_verify_destroy", "seed_last_error",
            "seed_sched_workspace_bytes", "seed_sched_run")
@@ -96,6 +96,7 @@ def load_library():
     lib.seed_verify_step.argtypes = [C.c_void_p, C.POINTER(StepArgsC)]
     lib.seed_draft_step.argtypes = [C.c_void_p, C.POINTER(DraftArgsC)]
     lib.seed_accept_resample.argtypes = [C.POINTER(AcceptArgsC), C.c_void_p]
+    lib.seed_accept_resample_static.argtypes = [C.POINTER(AcceptArgsC), C.c_void_p]
     lib.seed_sample_probs.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.seed_uniform_philox.argtypes = [C.c_uint32, C.c_uint32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.seed_kv_load.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
@@ -167,19 +168,22 @@ def _accept_outputs(N, gamma, device, want_p_tok=True):
 
 
 def accept_resample(p_or_logits, q, draft_tok, u_acc, u_res, *, kind="probs", temperature=1.0, greedy=False,
-                    private_len=None):
+                    private_len=None, static_scratch=False, outs=None):
     """seed_accept_resample: p_or_logits float32 [N][Tp][V], q float32 [N][gamma][V], draft_tok int32
     [N][gamma], u_acc float32 [N][gamma], u_res float32 [N] (device tensors).  Returns device tensors
-    (accept_len, out_tok, n_out, p_tok)."""
+    (accept_len, out_tok, n_out, p_tok).  static_scratch: call seed_accept_resample_static instead (the entry
+    point that allocates nothing; pass `outs`, four preallocated output tensors, to allocate nothing here either)."""
     lib = load_library()
     N, Tp, V = p_or_logits.shape
     gamma = draft_tok.shape[1]
     for t in (p_or_logits, q, draft_tok, u_acc, u_res):
         assert t is None or t.is_contiguous()
-    outs = _accept_outputs(N, gamma, p_or_logits.device)
+    if outs is None:
+        outs = _accept_outputs(N, gamma, p_or_logits.device)
     a = _accept_struct(N, gamma, Tp, V, SEED_KIND_LOGITS if kind == "logits" else SEED_KIND_PROBS, greedy,
                        temperature, p_or_logits, q, draft_tok, u_acc, u_res, *outs, private_len)
-    _check(lib.seed_accept_resample(C.byref(a), _stream_handle()))
+    fn = lib.seed_accept_resample_static if static_scratch else lib.seed_accept_resample
+    _check(fn(C.byref(a), _stream_handle()))
     return outs
 
 

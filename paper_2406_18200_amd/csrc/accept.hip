@@ -8,6 +8,7 @@
 // One workgroup (16 wavefronts) per branch.  Softmax statistics are wavefront-shuffle reductions; the
 // draw is an integer fixed-point inverse CDF: weights are truncated to multiples of 2^-38 and summed
 // as 64-bit integers, so the parallel scan gives the same token as a serial one.
+#include <mutex>
 #include "seed_internal.h"
 
 namespace seedv {
@@ -537,6 +538,37 @@ static int stats_slices(int rows, int vocab, int *per) {
 }
 
 size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices * sizeof(SliceStats); }
+
+// The row statistics of the entry point that allocates nothing (seed_accept_resample_static): one copy of this
+// array per GPU, held until the process ends.  1 MiB: kStaticAcceptRows rows x 16 slices x 16 bytes.
+// Every slice entry a call reads is written by that call's row statistics launch first, so nothing here needs
+// clearing between calls; calls that overlap on one GPU would share it and race.
+static __device__ __align__(256) unsigned char scratch[(size_t)kStaticAcceptRows * kMaxSlices * sizeof(SliceStats)];
+
+// Device address of this GPU's copy of the array (the array's name is only a host-side stand-in for it).
+// Looked up once per device, with that device current; no allocation.
+int accept_static_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = -1;
+    int rc = hip_fail(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("accept: device ordinal %d is outside the table of %d", dev, kMaxDevices);
+        return SEED_E_CAPACITY;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void *p = nullptr;
+        rc = hip_fail(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc) return rc;
+        if (p == nullptr) { set_error("accept: the static scratch array has no device address"); return SEED_E_HIP; }
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return SEED_OK;
+}
 
 // scratch (optional, accept_scratch_bytes(n_branches * n_target_rows) bytes): with it the softmax statistics
 // of the rows are computed by a launch that fills the chip; without it inside the one workgroup per branch.

@@ -592,6 +592,21 @@ int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     return launch_accept(*args, nullptr, nullptr, 0, nullptr, (hipStream_t)hip_stream);
 }
 
+int seed_accept_resample_static(const seed_accept_args *args, void *hip_stream) {
+    int rc = check_accept_args(args);
+    if (rc) return rc;
+    if (args->n_branches == 0) return SEED_OK;
+    const long rows = (long)args->n_branches * args->n_target_rows;
+    if (rows > kStaticAcceptRows) {
+        set_error("accept (static scratch): %ld target rows exceed the maximum of %d", rows, kStaticAcceptRows);
+        return SEED_E_CAPACITY;
+    }
+    void *stats = nullptr;
+    rc = accept_static_scratch(&stats);
+    if (rc) return rc;
+    return launch_accept(*args, stats, nullptr, 0, nullptr, (hipStream_t)hip_stream);
+}
+
 int seed_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out, int32_t n_rows,
                       int32_t vocab, void *hip_stream) {
     if (n_rows < 0 || vocab < 1 || row_stride < vocab) {

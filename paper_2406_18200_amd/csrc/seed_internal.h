@@ -17,6 +17,8 @@ int hip_fail(hipError_t e, const char *what);
 
 // ---- accept.hip ------------------------------------------------------------------------------
 size_t accept_scratch_bytes(int max_rows);
+constexpr int kStaticAcceptRows = 4096;        // most target rows of a seed_accept_resample_static call
+int accept_static_scratch(void **out);         // this GPU's statistics array for that entry point
 int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
                   int32_t *status, hipStream_t st);   // scratch, branch_slot, status may be NULL
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
