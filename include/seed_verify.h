@@ -81,6 +81,20 @@ typedef struct {
 } seed_weights;
 
 /*
+ * Candidate tree of a draft phase (paper Section 2.2 "Tree Attention"; Section 4.1: k_config; appendix
+ * "Details of Tree Attention").  k_config = (k_1, ..., k_G): at position j every candidate of position j - 1 has
+ * k_j candidate continuations, drawn independently from the draft distribution given the path to them; (2,2,1)
+ * is 2 + 4 + 4 = 10 draft tokens.  Nodes are numbered in level order: node 0 is the root (the branch's pending
+ * token), then the k_1 nodes of position 1, then the k_1 k_2 nodes of position 2 (children of a node consecutive,
+ * in the order of their parents), and so on.  n_nodes = 1 + k_1 + k_1 k_2 + ... <= 64; n_par = the nodes that have
+ * children = n_nodes minus the last position's.  All ones is the plain chain.
+ */
+typedef struct {
+    int32_t depth;            /* G, 1..8                                   */
+    const int32_t *k_config;  /* HOST array of G entries, each >= 1        */
+} seed_tree;
+
+/*
  * Accept / reject / resample (paper Section 3.1; Algorithm 1, inner loop of the verification process).
  *   Row j of branch b holds the target distribution that verifies draft token draft_tok[b][j].
  *   accept iff  fl32(u_acc[b][j] * q[b][j][x]) < p[b][j][x]  (x = draft_tok[b][j]; one float32
@@ -96,6 +110,18 @@ typedef struct {
  *   were accepted without a bonus row); p_tok[b][j] = p(draft_tok[b][j]) as used in the test (optional).
  *   private_len (optional, in/out): Algorithm 1's validated-length bookkeeping in cache terms,
  *   private_len[b] += min(a_b + 1, n_target_rows).
+ * With a candidate tree (tree != NULL; gamma must equal tree->depth): target row r holds the distribution that
+ *   follows the path to node r; n_target_rows = n_par, or n_nodes to also draw a bonus token after a fully
+ *   accepted path; q is [N][n_par][V], row r the draft distribution from which node r's children were drawn;
+ *   draft_tok, u_acc and p_tok are [N][n_nodes - 1], entry i - 1 belonging to node i (p_tok: the target
+ *   probability at the node's parent of the node's token).  The walk starts at the root and tests the children of
+ *   the current node in order: the first as above; after i rejections at a node the target becomes the normalised
+ *   residual of the previous one minus q (fixed point, 2^-38; totals are integer sums) and candidate x is accepted
+ *   iff fl64(fl32(u q(x))) * fl64(Z_i) < fl64(R_i[x]); an accepted child becomes the current node; when all
+ *   children are rejected one token is drawn from the last residual with u_res and the walk ends.  The output law
+ *   equals the target's.  accept_len = depth reached; out_tok as above; path_node (optional) [N][gamma] = the
+ *   accepted node at each depth, then -1.  private_len[b] += number of rows kept: the root and the accepted
+ *   nodes that were fed.
  */
 typedef struct {
     int32_t n_branches;    /* N >= 0                                             */
@@ -116,6 +142,8 @@ typedef struct {
     int32_t *n_out;           /* [N]            out                              */
     float *p_tok;             /* [N][gamma]     out, may be NULL                 */
     int32_t *private_len;     /* [N]            in/out, may be NULL              */
+    const seed_tree *tree;    /* HOST, NULL = one candidate per position (chain)  */
+    int32_t *path_node;       /* [N][gamma]     out, may be NULL (tree only)      */
 } seed_accept_args;
 
 /*
@@ -139,6 +167,12 @@ typedef struct {
  *   caller's array over ALL max_branches slots; row_tok, logits_out and the accept arrays stay dense over
  *   the call's N branches.  NULL = branch b is slot b.  An out-of-range slot is clamped and sets bit 1 of
  *   the status word.
+ *   tree (optional, bf16 contexts): the rows of every branch are the first T nodes of this candidate tree
+ *   (T = n_par, or n_nodes with bonus rows) instead of a chain: row j sits at position shared_len +
+ *   private_len[b] + depth(j) and attends, among the rows of its branch, to itself and its ancestors only, i.e. it
+ *   sees exactly the sequence context + root-to-itself path.  The accept step then walks the tree (accept->tree is
+ *   taken from here) and, in every layer, moves the K/V of the rows that are kept (root + accepted path) to the
+ *   front of the branch's in-flight region, so that committing stays a length update.
  * Errors: SEED_E_CAPACITY if N, T or shared_len + T exceed what the context was created for.  A branch
  *   whose private_len would overflow max_private + max_rows_per_branch is detected on the device:
  *   its out-of-range rows are dropped and bit 0 of the status word is set (seed_verify_status).
@@ -153,6 +187,7 @@ typedef struct {
     float *logits_out;        /* [N][T][V] out, may be NULL                       */
     const seed_accept_args *accept; /* host pointer, may be NULL                  */
     const int32_t *branch_slot; /* [N] device, may be NULL: see below              */
+    const seed_tree *tree;      /* HOST, may be NULL: see below                    */
 } seed_step_args;
 
 /*

@@ -33,17 +33,42 @@ class WeightsC(C.Structure):
                 ("layers", C.POINTER(LayerWC))]
 
 
+class TreeC(C.Structure):
+    _fields_ = [("depth", C.c_int32), ("k_config", C.POINTER(C.c_int32))]
+
+
+def _tree_struct(k_config):
+    """seed_tree for a k_config tuple (None -> NULL); returns (pointer or None, keep-alive objects)."""
+    if k_config is None:
+        return None, None
+    arr = (C.c_int32 * len(k_config))(*[int(k) for k in k_config])
+    t = TreeC(len(k_config), arr)
+    return C.pointer(t), (arr, t)
+
+
+def tree_sizes(k_config):
+    """(n_nodes incl. the root, n_par = nodes that have children) of a k_config tree in level order."""
+    level, n, n_par = 1, 1, 1
+    for j, k in enumerate(k_config):
+        level *= int(k)
+        if j:
+            n_par = n
+        n += level
+    return n, (n - level)
+
+
 class AcceptArgsC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_branches", "gamma", "n_target_rows", "vocab", "probs_kind", "greedy")] + \
                [("temperature", C.c_float)] + \
                [(n, C.c_void_p) for n in ("p_or_logits", "q", "draft_tok", "u_acc", "u_res", "accept_len",
-                                          "out_tok", "n_out", "p_tok", "private_len")]
+                                          "out_tok", "n_out", "p_tok", "private_len")] + \
+               [("tree", C.POINTER(TreeC)), ("path_node", C.c_void_p)]
 
 
 class StepArgsC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_branches", "rows_per_branch", "flags", "shared_len")] + \
                [("row_tok", C.c_void_p), ("private_len", C.c_void_p), ("logits_out", C.c_void_p),
-                ("accept", C.POINTER(AcceptArgsC)), ("branch_slot", C.c_void_p)]
+                ("accept", C.POINTER(AcceptArgsC)), ("branch_slot", C.c_void_p), ("tree", C.POINTER(TreeC))]
 
 
 class DraftArgsC(C.Structure):
@@ -153,38 +178,48 @@ class ModelShape:
 
 
 def _accept_struct(n_branches, gamma, n_target_rows, vocab, probs_kind, greedy, temperature, p_or_logits, q,
-                   draft_tok, u_acc, u_res, accept_len, out_tok, n_out, p_tok, private_len):
+                   draft_tok, u_acc, u_res, accept_len, out_tok, n_out, p_tok, private_len, tree=None, path_node=None):
     return AcceptArgsC(n_branches, gamma, n_target_rows, vocab, probs_kind, int(greedy), float(temperature),
                        _ptr(p_or_logits), _ptr(q), _ptr(draft_tok), _ptr(u_acc), _ptr(u_res), _ptr(accept_len),
-                       _ptr(out_tok), _ptr(n_out), _ptr(p_tok), _ptr(private_len))
+                       _ptr(out_tok), _ptr(n_out), _ptr(p_tok), _ptr(private_len), tree, _ptr(path_node))
 
 
-def _accept_outputs(N, gamma, device, want_p_tok=True):
+def _accept_outputs(N, gamma, device, want_p_tok=True, n_drafts=None):
     import torch
     return (torch.empty(N, dtype=torch.int32, device=device),
             torch.empty((N, gamma + 1), dtype=torch.int32, device=device),
             torch.empty(N, dtype=torch.int32, device=device),
-            torch.empty((N, gamma), dtype=torch.float32, device=device) if want_p_tok else None)
+            torch.empty((N, gamma if n_drafts is None else n_drafts), dtype=torch.float32, device=device)
+            if want_p_tok else None)
 
 
 def accept_resample(p_or_logits, q, draft_tok, u_acc, u_res, *, kind="probs", temperature=1.0, greedy=False,
-                    private_len=None, static_scratch=False, outs=None):
+                    private_len=None, static_scratch=False, outs=None, k_config=None):
     """seed_accept_resample: p_or_logits float32 [N][Tp][V], q float32 [N][gamma][V], draft_tok int32
     [N][gamma], u_acc float32 [N][gamma], u_res float32 [N] (device tensors).  Returns device tensors
     (accept_len, out_tok, n_out, p_tok).  static_scratch: call seed_accept_resample_static instead (the entry
     point that allocates nothing; pass `outs`, four preallocated output tensors, to allocate nothing here either)."""
+    import torch
     lib = load_library()
     N, Tp, V = p_or_logits.shape
-    gamma = draft_tok.shape[1]
     for t in (p_or_logits, q, draft_tok, u_acc, u_res):
         assert t is None or t.is_contiguous()
+    tree, keep = _tree_struct(k_config)
+    if k_config is None:
+        gamma, path = draft_tok.shape[1], None
+    else:
+        # candidate tree: draft_tok / u_acc are [N][n_nodes - 1]; a fifth output holds the accepted nodes
+        gamma = len(k_config)
+        assert draft_tok.shape[1] == tree_sizes(k_config)[0] - 1
+        path = torch.empty((N, gamma), dtype=torch.int32, device=p_or_logits.device)
     if outs is None:
-        outs = _accept_outputs(N, gamma, p_or_logits.device)
+        outs = _accept_outputs(N, gamma, p_or_logits.device, n_drafts=draft_tok.shape[1])
     a = _accept_struct(N, gamma, Tp, V, SEED_KIND_LOGITS if kind == "logits" else SEED_KIND_PROBS, greedy,
-                       temperature, p_or_logits, q, draft_tok, u_acc, u_res, *outs, private_len)
+                       temperature, p_or_logits, q, draft_tok, u_acc, u_res, *outs[:4], private_len, tree, path)
     fn = lib.seed_accept_resample_static if static_scratch else lib.seed_accept_resample
     _check(fn(C.byref(a), _stream_handle()))
-    return outs
+    del keep
+    return outs if path is None else tuple(outs[:4]) + (path,)
 
 
 def sample_probs(probs, u):
@@ -266,21 +301,30 @@ class VerifyContext:
                                      _ptr(v_private), n_b, R))
 
     def step(self, row_tok, shared_len, private_len=None, *, flags=0, logits_out=None, accept=None,
-             branch_slot=None):
+             branch_slot=None, k_config=None):
         """seed_verify_step.  row_tok int32 [N][T].  `accept` = dict(q, draft_tok, u_acc, u_res, temperature,
         greedy=False) -> returns (accept_len, out_tok, n_out, p_tok); otherwise returns None.  branch_slot:
-        int32 [N] cache slots of the call's branches (private_len is then indexed by slot)."""
+        int32 [N] cache slots of the call's branches (private_len is then indexed by slot).  k_config: the rows of
+        every branch are the first T nodes of that candidate tree (seed_tree); draft_tok / u_acc are then
+        [N][n_nodes - 1], q is [N][n_par][V], and a fifth output holds the accepted node of every depth."""
+        import torch
         N, T = row_tok.shape
         acc_c, outs = None, None
+        tree, keep = _tree_struct(k_config)
         if accept is not None:
-            gamma = accept["draft_tok"].shape[1]
-            outs = _accept_outputs(N, gamma, row_tok.device)
+            n_drafts = accept["draft_tok"].shape[1]
+            gamma = n_drafts if k_config is None else len(k_config)
+            outs = _accept_outputs(N, gamma, row_tok.device, n_drafts=n_drafts)
+            path = None if k_config is None else torch.empty((N, gamma), dtype=torch.int32, device=row_tok.device)
             acc_c = _accept_struct(N, gamma, T, self.shape.vocab, SEED_KIND_LOGITS, accept.get("greedy", False),
                                    accept.get("temperature", 1.0), None, accept.get("q"), accept["draft_tok"],
-                                   accept.get("u_acc"), accept.get("u_res"), *outs, None)
+                                   accept.get("u_acc"), accept.get("u_res"), *outs, None, tree, path)
+            if path is not None:
+                outs = tuple(outs) + (path,)
         a = StepArgsC(N, T, flags, int(shared_len), _ptr(row_tok), _ptr(private_len), _ptr(logits_out),
-                      C.pointer(acc_c) if acc_c is not None else None, _ptr(branch_slot))
+                      C.pointer(acc_c) if acc_c is not None else None, _ptr(branch_slot), tree)
         _check(self.lib.seed_verify_step(self.handle, C.byref(a)))
+        del keep
         return outs
 
     def prefill_shared(self, tokens, shared_len=0):

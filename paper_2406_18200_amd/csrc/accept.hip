@@ -518,6 +518,287 @@ __global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Candidate trees (Section 2.2 "Tree Attention"; Section 4.1: k_config; appendix "Details of Tree Attention").
+// Nodes are numbered in level order, node 0 the root (the pending token); at position j every node of position
+// j - 1 has k_j children, consecutive.  The target row of node r holds the distribution that follows the path to
+// r; q row r is the draft distribution from which r's children were drawn, independently.
+// The walk: at the current node the children are tested in order.  The first as in the single-candidate rule,
+// fl32(u q(x)) < p(x).  After i rejections the target is the normalised i-th residual, kept in fixed point:
+//   R_2[w] = trunc(max(0, fl32(p_w - q_w)) 2^38),  Z_i = sum_w R_i[w],
+//   R_{i+1}[w] = max(0, R_i[w] - trunc(fl64(q_w) * fl64(Z_i)))                       (one float64 multiply)
+//   candidate i is accepted iff fl64(fl32(u q(x))) * fl64(Z_i) < fl64(R_i[x])         (one float64 multiply)
+// so every decision is reproducible bit for bit by a serial implementation (integer sums, IEEE products).  When all
+// children are rejected a token is drawn from the last residual (from p itself if a residual sums to zero) and
+// the walk ends.  This multi-round rule keeps the output law equal to the target's for candidates drawn with
+// replacement; with k_j = 1 everywhere it is the chain rule.
+struct TreeShape {
+    int G;                    // positions (depth of the tree), 1..kMaxTreeDepth
+    int k[kMaxTreeDepth];     // children per node at position j + 1
+    int off[kMaxTreeDepth + 2];   // first node of level j (off[0] = 0, off[1] = 1, ..., off[G + 1] = number of nodes)
+};
+__device__ __forceinline__ int tree_k(const TreeShape &t, int j) {      // k of level j (1-based): static indexing only
+    int v = 1;
+#pragma unroll
+    for (int i = 0; i < kMaxTreeDepth; ++i) v = (i == j - 1) ? t.k[i] : v;
+    return v;
+}
+__device__ __forceinline__ int tree_off(const TreeShape &t, int j) {
+    int v = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxTreeDepth + 2; ++i) v = (i == j) ? t.off[i] : v;
+    return v;
+}
+// level of node i >= 1 and its parent
+__device__ __forceinline__ void tree_parent(const TreeShape &t, int node, int &level, int &parent) {
+    level = 1;
+#pragma unroll
+    for (int j = 2; j <= kMaxTreeDepth; ++j)
+        if (j <= t.G && node >= t.off[j]) level = j;
+    parent = tree_off(t, level - 1) + (node - tree_off(t, level)) / tree_k(t, level);
+}
+
+struct TreeShared {
+    float mx[kMaxTreeNodes], inv_sum[kMaxTreeNodes];
+    int best[kMaxTreeNodes];
+    int ok1[kMaxTreeNodes];
+    unsigned long long Z[kMaxTreeNodes + 1];     // Z[i]: total of the residual after i rejections at the current node
+    unsigned long long rx;
+    int flag;
+};
+
+// R after `n_rej` rejections (n_rej >= 1) at a node, for token v
+__device__ __forceinline__ unsigned long long tree_residual(const TargetRow &row, const float *q, int v, int n_rej,
+                                                            const unsigned long long *Z) {
+    const float qv = q[v];
+    const float r = __fsub_rn(row.p(v), qv);
+    unsigned long long R = r > 0.f ? to_fixed(r) : 0ull;
+    for (int i = 1; i < n_rej; ++i) {
+        const unsigned long long Qz = (unsigned long long)__dmul_rn((double)qv, (double)Z[i]);
+        R = R > Qz ? R - Qz : 0ull;
+    }
+    return R;
+}
+
+__device__ unsigned long long block_sum_u64(unsigned long long v, Shared &sm) {
+    v = wave_sum_u64(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm.tot[threadIdx.x >> 6] = v;
+    __syncthreads();
+    unsigned long long r = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) r += sm.tot[i];
+    return r;
+}
+
+// Fixed-point inverse CDF over the residual after n_rej rejections (the scan of draw_fixed on those weights).
+__device__ int draw_tree_residual(const TargetRow &row, const float *q, int n_rej, const unsigned long long *Zs,
+                                  float u, int V, Shared &sm) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int per = (((V + kWaves - 1) / kWaves) + 63) & ~63;
+    const int base = wave * per;
+    const int end = min(V, base + per);
+    unsigned long long local = 0;
+    for (int v = base + lane; v < end; v += 64) local += tree_residual(row, q, v, n_rej, Zs);
+    local = wave_sum_u64(local);
+    __syncthreads();
+    if (lane == 0) sm.tot[wave] = local;
+    if (threadIdx.x == 0) sm.tok = -1;
+    __syncthreads();
+    unsigned long long Z = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) Z += sm.tot[i];
+    if (Z == 0) return -1;
+    const unsigned long long m24 = (unsigned long long)(__fmul_rn(u, 16777216.0f));
+    const unsigned long long t = (m24 * Z) >> 24;
+    unsigned long long run = 0;
+    int target = 0;
+    for (int i = 0; i < kWaves; ++i) {
+        unsigned long long nx = run + sm.tot[i];
+        if (t < nx) { target = i; break; }
+        run = nx;
+    }
+    if (wave == target) {
+        for (int blk = base; blk < end; blk += 64) {
+            const int v = blk + lane;
+            const unsigned long long mine = v < end ? tree_residual(row, q, v, n_rej, Zs) : 0ull;
+            unsigned long long incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                unsigned long long o = __shfl_up(incl, off);
+                if (lane >= off) incl += o;
+            }
+            const unsigned long long hit = __ballot(run + incl > t);
+            if (hit) {
+                if (lane == __ffsll((long long)hit) - 1) sm.tok = v;
+                break;
+            }
+            run += __shfl(incl, 63);
+        }
+    }
+    __syncthreads();
+    return sm.tok;
+}
+
+// One workgroup per branch.  Phase A: softmax statistics of every target row (from the slices of
+// row_stats_kernel, or computed here).  Phase B: the first-round test of every node, one thread per node.
+// Phase C: the walk, uniform over the workgroup; residual totals and the final draw use all 16 wavefronts.
+__global__ __launch_bounds__(kBlock) void accept_tree_kernel(seed_accept_args a, TreeShape t, const SliceStats *stats,
+                                                            int n_slices, const int32_t *slot, int n_slots,
+                                                            int32_t *status, int32_t *commit_rows) {
+    __shared__ Shared sm;
+    __shared__ TreeShared ts;
+    const int b = blockIdx.x;
+    const int G = t.G, Tp = a.n_target_rows, V = a.vocab;
+    const int n_nodes = tree_off(t, G + 1), n_par = tree_off(t, G);
+    const int is_logits = a.probs_kind == SEED_KIND_LOGITS;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float inv_temp = a.greedy ? 1.0f : 1.0f / a.temperature;
+    const float *rows = a.p_or_logits + (size_t)b * Tp * V;
+    // ---- phase A
+    if (is_logits || a.greedy) {
+        if (stats != nullptr) {
+            for (int r = wave; r < Tp; r += kWaves) {
+                const SliceStats *st = stats + ((size_t)b * Tp + r) * n_slices;
+                float lm = -INFINITY, ls = 0.f;
+                int li = 0x7fffffff;
+                if (lane < n_slices) {
+                    const SliceStats e = st[lane];
+                    lm = e.mx; li = e.idx; ls = e.sum;
+                }
+                float mv = lm;
+                int mi = li;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const float ov = __shfl_xor(mv, off);
+                    const int oi = __shfl_xor(mi, off);
+                    if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+                }
+                ls = lane < n_slices ? ls * exp_scaled(lm, mv, inv_temp) : 0.f;
+                float tot = 0.f;
+                for (int i = 0; i < n_slices; ++i) tot += __shfl(ls, i);          // fixed order
+                if (lane == 0) { ts.mx[r] = mv; ts.inv_sum[r] = 1.0f / tot; ts.best[r] = mi; }
+            }
+        } else {
+            for (int r = 0; r < Tp; ++r) {
+                const float *src = rows + (size_t)r * V;
+                if (a.greedy) {
+                    const int best = block_argmax(src, V, sm);
+                    if (threadIdx.x == 0) { ts.mx[r] = 0.f; ts.inv_sum[r] = 1.f; ts.best[r] = best; }
+                } else {
+                    const TargetRow row = make_row(src, 1, a.temperature, V, sm);
+                    if (threadIdx.x == 0) { ts.mx[r] = row.mx; ts.inv_sum[r] = row.inv_sum; ts.best[r] = -1; }
+                }
+                __syncthreads();
+            }
+        }
+    } else {
+        for (int r = threadIdx.x; r < Tp; r += kBlock) { ts.mx[r] = 0.f; ts.inv_sum[r] = 1.f; ts.best[r] = -1; }
+    }
+    __syncthreads();
+    auto row_of = [&](int r) { return TargetRow{rows + (size_t)r * V, is_logits, ts.mx[r], ts.inv_sum[r], inv_temp}; };
+    const int32_t *tok = a.draft_tok + (size_t)b * (n_nodes - 1);            // entry i - 1: node i
+    // ---- phase B: node i against the distribution at its parent (a token id outside [0, V) reads as token 0,
+    // counts as rejected in every round and raises bit 2 of the status word)
+    for (int i = 1 + threadIdx.x; i < n_nodes; i += kBlock) {
+        int level, par;
+        tree_parent(t, i, level, par);
+        const int x_raw = tok[i - 1];
+        const bool x_ok = (unsigned)x_raw < (unsigned)V;
+        const int x = x_ok ? x_raw : 0;
+        if (!x_ok && status != nullptr) atomicOr(status, 4);
+        int ok = 0;
+        float pj = 0.f;
+        if (a.greedy) {
+            ok = x_ok && x == ts.best[par];
+        } else {
+            pj = x_ok ? row_of(par).p(x) : 0.f;
+            ok = x_ok && __fmul_rn(a.u_acc[(size_t)b * (n_nodes - 1) + i - 1], a.q[((size_t)b * n_par + par) * V + x]) < pj;
+        }
+        ts.ok1[i] = ok;
+        if (a.p_tok != nullptr) a.p_tok[(size_t)b * (n_nodes - 1) + i - 1] = pj;
+    }
+    __syncthreads();
+    // ---- phase C
+    int cur = 0, local = 0, acc = 0, new_tok = -1;      // current node, its index within its level, accepted depth
+    for (int level = 1; level <= G; ++level) {
+        const int kj = tree_k(t, level);
+        const int c0 = tree_off(t, level) + local * kj;
+        const float *q = a.greedy ? nullptr : a.q + ((size_t)b * n_par + cur) * V;
+        const TargetRow row = row_of(cur);
+        int chosen = -1, n_rej = 0;
+        bool dead = false;                              // a residual summed to zero: stop testing, draw from p
+        for (int i = 0; i < kj; ++i) {
+            const int c = c0 + i;
+            int ok;
+            if (i == 0 || a.greedy) {
+                ok = ts.ok1[c];
+            } else {
+                if (threadIdx.x == 0) {
+                    const int x_raw = tok[c - 1];
+                    const bool x_ok = (unsigned)x_raw < (unsigned)V;
+                    const int x = x_ok ? x_raw : 0;
+                    const float uq = __fmul_rn(a.u_acc[(size_t)b * (n_nodes - 1) + c - 1], q[x]);
+                    const unsigned long long R = tree_residual(row, q, x, n_rej, ts.Z);
+                    ts.flag = x_ok && __dmul_rn((double)uq, (double)ts.Z[n_rej]) < (double)R;
+                }
+                __syncthreads();
+                ok = ts.flag;
+            }
+            if (ok) { chosen = c; break; }
+            if (a.greedy) continue;
+            // rejected: total of the next residual
+            ++n_rej;
+            unsigned long long part = 0;
+            for (int v = threadIdx.x; v < V; v += kBlock) part += tree_residual(row, q, v, n_rej, ts.Z);
+            const unsigned long long Z = block_sum_u64(part, sm);
+            __syncthreads();
+            if (threadIdx.x == 0) ts.Z[n_rej] = Z;
+            __syncthreads();
+            if (Z == 0) { dead = true; break; }
+        }
+        if (chosen < 0) {
+            if (a.greedy) {
+                new_tok = ts.best[cur];
+            } else {
+                new_tok = dead ? -1 : draw_tree_residual(row, q, n_rej, ts.Z, a.u_res[b], V, sm);
+                if (new_tok < 0) new_tok = draw_fixed<0>(row, nullptr, a.u_res[b], V, sm);
+            }
+            break;
+        }
+        if (threadIdx.x == 0) {
+            a.out_tok[(size_t)b * (G + 1) + acc] = tok[chosen - 1];
+            if (a.path_node != nullptr) a.path_node[(size_t)b * G + acc] = chosen;
+            if (commit_rows != nullptr) commit_rows[(size_t)b * (kMaxTreeDepth + 2) + 1 + acc] = chosen;
+        }
+        cur = chosen;
+        local = chosen - tree_off(t, level);
+        ++acc;
+        __syncthreads();
+    }
+    if (acc == G && Tp == n_nodes && n_par < n_nodes) {                 // bonus rows: a token after a full path
+        if (a.greedy) new_tok = ts.best[cur];
+        else new_tok = draw_fixed<0>(row_of(cur), nullptr, a.u_res[b], V, sm);
+    }
+    for (int j = acc + threadIdx.x; j <= G; j += kBlock) a.out_tok[(size_t)b * (G + 1) + j] = (j == acc) ? new_tok : -1;
+    if (a.path_node != nullptr)
+        for (int j = acc + threadIdx.x; j < G; j += kBlock) a.path_node[(size_t)b * G + j] = -1;
+    if (threadIdx.x == 0) {
+        a.accept_len[b] = acc;
+        a.n_out[b] = acc + (new_tok >= 0 ? 1 : 0);
+        // rows that stay in the cache: the root and the accepted nodes that were fed (Algorithm 1's bookkeeping)
+        const int n_commit = min(acc + 1, Tp == n_nodes ? G + 1 : G);
+        if (commit_rows != nullptr) {
+            commit_rows[(size_t)b * (kMaxTreeDepth + 2)] = n_commit;
+            commit_rows[(size_t)b * (kMaxTreeDepth + 2) + 1 + acc] = -1;
+        }
+        if (a.private_len != nullptr) {
+            const int sb = slot != nullptr ? min(max(slot[b], 0), n_slots - 1) : b;
+            a.private_len[sb] += n_commit;
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void sample_probs_kernel(const float *probs, int64_t row_stride,
                                                               const float *u, int32_t *tok_out, int V) {
     __shared__ Shared sm;
@@ -590,6 +871,29 @@ int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branc
     hipLaunchKernelGGL(accept_resample_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, stats, n_slices,
                        branch_slot, n_slots, status);
     return hip_fail(hipGetLastError(), "accept_resample launch");
+}
+
+int launch_accept_tree(const seed_accept_args &a, const TreeInfo &ti, void *scratch, const int32_t *branch_slot,
+                       int n_slots, int32_t *status, int32_t *commit_rows, hipStream_t st) {
+    if (a.n_branches == 0) return SEED_OK;
+    TreeShape t{};
+    t.G = ti.G;
+    for (int i = 0; i < kMaxTreeDepth; ++i) t.k[i] = i < ti.G ? ti.k[i] : 1;
+    for (int i = 0; i < kMaxTreeDepth + 2; ++i) t.off[i] = i <= ti.G + 1 ? ti.off[i] : ti.n_nodes;
+    const bool need_stats = a.probs_kind == SEED_KIND_LOGITS || a.greedy;
+    SliceStats *stats = nullptr;
+    int n_slices = 0;
+    if (scratch != nullptr && need_stats) {
+        const int rows = a.n_branches * a.n_target_rows;
+        int per;
+        n_slices = stats_slices(rows, a.vocab, &per);
+        stats = (SliceStats *)scratch;
+        hipLaunchKernelGGL(row_stats_kernel, dim3(rows, n_slices), dim3(256), 0, st, a.p_or_logits, a.vocab, per,
+                           a.greedy ? 1.0f : 1.0f / a.temperature, stats);
+    }
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(a.n_branches), dim3(kBlock), 0, st, a, t, stats, n_slices, branch_slot,
+                       n_slots, status, commit_rows);
+    return hip_fail(hipGetLastError(), "accept_tree launch");
 }
 
 // scratch (optional, accept_scratch_bytes(n_rows) bytes, rows contiguous: logits_stride == vocab): as in

@@ -60,6 +60,9 @@ struct AttnParams {
     int *counters;            // [H] arrival counters, zero on entry and left zero
     uint16_t *act;            // merged output, fragment-packed hi/lo activation of the O projection
     int32_t *status;
+    // candidate trees (NULL: the rows of a branch are a chain, row j at depth j seeing rows 0..j)
+    const int32_t *row_depth;             // [T] depth of row j in its branch's tree = its position offset
+    const unsigned long long *row_anc;    // [T] bit jj set: row jj is row j itself or one of its ancestors
     int Mp;
     int wave_tasks;           // several row groups: shared tasks are attn_task_lds workgroups
     int gpw, n_quads;         // row groups per such workgroup (<= 4), workgroups per (head, key range)
@@ -117,7 +120,8 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
                                          bf16x8 (&qf)[DH / 32][2]) {
     constexpr int KS = DH / 32;
     const int j = r % P.T;
-    const int pos = P.S + min(max(q.pl, 0), P.max_private) + j;
+    const int dj = P.row_depth != nullptr ? P.row_depth[j] : j;      // tree: a row sits at its depth, not its index
+    const int pos = P.S + min(max(q.pl, 0), P.max_private) + dj;
     const float *tb = P.rope + (size_t)pos * DH;
 #pragma unroll
     for (int ks = 0; ks < KS / 2; ++ks) {
@@ -558,10 +562,15 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
         return upper[i] ? x * c + y * s_ : x * c - y * s_;
     };
     const float *tb0 = P.rope + (size_t)(P.S + pl) * DH;
+    // candidate trees (Section 2.2 "Tree Attention"; appendix): row j sees, among the rows of its branch, only
+    // itself and its ancestors, and every row sits at the position of its depth
+    const bool tree = P.row_depth != nullptr;
+    const unsigned long long anc = tree ? P.row_anc[j] : ~0ull;
+    auto depth_of = [&](int jj) { return tree ? P.row_depth[jj] : jj; };
     float qv[PER], o[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        qv[i] = rotated(P.qkv + (size_t)r * 3 * HD + h * DH, tb0 + (size_t)j * DH, i);
+        qv[i] = rotated(P.qkv + (size_t)r * 3 * HD + h * DH, tb0 + (size_t)depth_of(j) * DH, i);
         o[i] = 0.f;
     }
     float m = -INFINITY, l = 0.f;
@@ -575,14 +584,14 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
             sc[u] = 0.f;
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
-                kk[u][i] = rotated(krow, tb0 + (size_t)jj * DH, i);
+                kk[u][i] = rotated(krow, tb0 + (size_t)depth_of(jj) * DH, i);
                 vv[u][i] = krow[HD + lane * PER + i];
                 sc[u] = fmaf(qv[i], kk[u][i], sc[u]);
             }
         }
 #pragma unroll
         for (int u = 0; u < kB; ++u) {
-            if (j0 + u > j) continue;
+            if (j0 + u > j || !((anc >> ((j0 + u) & 63)) & 1ull)) continue;    // (uniform over the wavefront)
             const float s = wave_reduce_sum_dpp(sc[u]) * P.scale_log2e;   // (DPP: the keys of a row are a dependent chain)
             const float m_new = fmaxf(m, s);
             const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
@@ -702,7 +711,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     // all kernel arguments in one batch of scalar loads (each separate one is a round trip to memory)
     asm volatile("" ::"s"(P.q), "s"(P.q_plane), "s"(P.k_shared), "s"(P.vt_shared), "s"(P.k_priv), "s"(P.vt_priv),
                  "s"(P.private_len), "s"(P.slot), "s"(P.n_slots), "s"(P.o_part), "s"(P.ml_part), "s"(P.qkv),
-                 "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status));
+                 "s"(P.rope), "s"(P.counters), "s"(P.act), "s"(P.status), "s"(P.row_depth), "s"(P.row_anc));
     asm volatile("" ::"s"(P.Mp), "s"(P.merge_in_launch), "s"(P.wave_tasks), "s"(P.gpw), "s"(P.n_quads), "s"(P.M), "s"(P.Mq), "s"(P.N),
                  "s"(P.T), "s"(P.H), "s"(P.S), "s"(P.prefill_shared), "s"(P.cap_s), "s"(P.cap_p), "s"(P.max_private),
                  "s"(P.n_groups), "s"(P.ks_shared), "s"(P.keys_per_range), "s"(P.keys_per_range_priv), "s"(P.ks_priv), "s"(P.groups_priv),
@@ -844,6 +853,8 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.counters = a.counters;
     P.act = (uint16_t *)a.act;
     P.status = a.status;
+    P.row_depth = a.row_depth;
+    P.row_anc = a.row_anc;
     P.M = a.M; P.Mp = a.Mp; P.Mq = a.Mq; P.N = a.N; P.T = a.T; P.H = a.H; P.S = a.S;
     P.prefill_shared = a.prefill_shared;
     P.cap_s = a.cap_s; P.cap_p = a.cap_p; P.max_private = a.max_private;

@@ -299,6 +299,69 @@ __global__ void calib_spin_kernel(unsigned long long ticks, unsigned long long m
     atomicAdd(elapsed_total, t - t0);
 }
 
+// Candidate trees: the per-row tables the attention launch reads (depth = position offset of a row, ancestor
+// mask = which rows of its branch it sees), written from a by-value copy with static indexing only.
+struct TreeTablesArg {
+    int32_t depth[kMaxTreeNodes];
+    unsigned long long anc[kMaxTreeNodes];
+};
+__global__ void tree_tables_kernel(TreeTablesArg t, int n_rows, int32_t *depth_out, unsigned long long *anc_out) {
+    const int i = threadIdx.x;
+    int32_t d = 0;
+    unsigned long long m = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxTreeNodes; ++j) {
+        d = (j == i) ? t.depth[j] : d;
+        m = (j == i) ? t.anc[j] : m;
+    }
+    if (i < n_rows) {
+        depth_out[i] = d;
+        anc_out[i] = m;
+    }
+}
+
+// After the walk of a candidate tree (bf16 caches): the rows of a branch that stay in its cache -- the root
+// and the accepted path -- sit scattered in the in-flight region in row order; they are moved to its front in
+// path order, which is where a chain would have put them, so that committing is again just the length update
+// (already done by the accept kernel: the region starts at private_len - rows kept).  One workgroup per (branch,
+// head, layer): everything is read before anything is written.
+__global__ __launch_bounds__(256) void kv_compact_kernel(uint16_t *k_priv, uint16_t *vt_priv, size_t layer_stride,
+                                                         const int32_t *commit_rows, const int32_t *private_len,
+                                                         const int32_t *slot, int n_slots, int H, int dh, int cap_p,
+                                                         int max_private) {
+    const int b = blockIdx.x / H, h = blockIdx.x - b * H, l = blockIdx.y;
+    const int32_t *cr = commit_rows + (size_t)b * (kMaxTreeDepth + 2);
+    const int n = min(max(cr[0], 0), kMaxTreeDepth + 1);
+    const int sb = slot != nullptr ? min(max(slot[b], 0), n_slots - 1) : b;
+    const int base = private_len[sb] - n;
+    if (n <= 1 || base < 0 || base > max_private) return;       // nothing to move / a flagged capacity overflow
+    uint16_t *K = k_priv + layer_stride * l + ((size_t)sb * H + h) * cap_p * dh;
+    uint16_t *Vt = vt_priv + layer_stride * l + ((size_t)sb * H + h) * dh * cap_p;
+    constexpr int kPer = (kMaxTreeDepth * 128 + 255) / 256;
+    uint16_t kv[kPer], vv[kPer];
+    const int total = (n - 1) * dh;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int e = threadIdx.x + 256 * i;
+        if (e < total) {
+            const int d = 1 + e / dh, dim = e - (d - 1) * dh;
+            const int src = base + min(max(cr[d], 0), kMaxTreeNodes - 1);
+            kv[i] = K[(size_t)src * dh + dim];
+            vv[i] = Vt[vt_offset(dim, src, dh)];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int e = threadIdx.x + 256 * i;
+        if (e < total) {
+            const int d = 1 + e / dh, dim = e - (d - 1) * dh;
+            K[(size_t)(base + d) * dh + dim] = kv[i];
+            Vt[vt_offset(dim, base + d, dh)] = vv[i];
+        }
+    }
+}
+
 __global__ void add_len_kernel(int32_t *len, int n, int delta, const int32_t *slot, int n_slots) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) len[slot != nullptr ? min(max(slot[i], 0), n_slots - 1) : i] += delta;
@@ -392,6 +455,27 @@ int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int 
     else
         hipLaunchKernelGGL((kv_import_kernel<false, false>), dim3(blocks), dim3(256), 0, st, src, dst, heads, len, dh, cap);
     return hip_fail(hipGetLastError(), "kv_import launch");
+}
+
+int launch_tree_tables(const TreeInfo &t, int n_rows, int32_t *depth_out, unsigned long long *anc_out, hipStream_t st) {
+    TreeTablesArg a{};
+    for (int i = 0; i < kMaxTreeNodes; ++i) {
+        a.depth[i] = i < t.n_nodes ? t.depth[i] : 0;
+        a.anc[i] = i < t.n_nodes ? t.anc[i] : 0ull;
+    }
+    hipLaunchKernelGGL(tree_tables_kernel, dim3(1), dim3(kMaxTreeNodes), 0, st, a, n_rows, depth_out, anc_out);
+    return hip_fail(hipGetLastError(), "tree tables launch");
+}
+
+int launch_kv_compact(void *k_priv, void *vt_priv, size_t layer_stride_bytes, int n_layers, const int32_t *commit_rows,
+                      const int32_t *private_len, const int32_t *branch_slot, int n_slots, int n_branches, int H, int dh,
+                      int cap_p, int max_private, hipStream_t st) {
+    if (n_branches == 0) return SEED_OK;
+    if (dh > 128) { set_error("kv compaction supports head_dim <= 128"); return SEED_E_SHAPE; }
+    hipLaunchKernelGGL(kv_compact_kernel, dim3(n_branches * H, n_layers), dim3(256), 0, st, (uint16_t *)k_priv,
+                       (uint16_t *)vt_priv, layer_stride_bytes / 2, commit_rows, private_len, branch_slot, n_slots, H, dh,
+                       cap_p, max_private);
+    return hip_fail(hipGetLastError(), "kv compaction launch");
 }
 
 int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st) {

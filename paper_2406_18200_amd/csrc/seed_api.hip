@@ -25,6 +25,39 @@ int hip_fail(hipError_t e, const char *what) {
     return SEED_E_HIP;
 }
 
+int expand_tree(const seed_tree *t, TreeInfo *out) {
+    if (t == nullptr || out == nullptr) { set_error("tree is NULL"); return SEED_E_NULL_PTR; }
+    if (t->depth < 1 || t->depth > kMaxTreeDepth) { set_error("tree: depth must be 1..%d", kMaxTreeDepth); return SEED_E_CAPACITY; }
+    if (t->k_config == nullptr) { set_error("tree: k_config is NULL"); return SEED_E_NULL_PTR; }
+    TreeInfo ti{};
+    ti.G = t->depth;
+    ti.off[0] = 0;
+    ti.off[1] = 1;
+    long level = 1;
+    for (int j = 1; j <= ti.G; ++j) {
+        const int k = t->k_config[j - 1];
+        if (k < 1) { set_error("tree: k_config[%d] = %d must be >= 1", j - 1, k); return SEED_E_INVALID_ARG; }
+        level *= k;
+        if (ti.off[j] + level > kMaxTreeNodes) { set_error("tree: more than %d nodes", kMaxTreeNodes); return SEED_E_CAPACITY; }
+        ti.k[j - 1] = k;
+        ti.off[j + 1] = ti.off[j] + (int)level;
+    }
+    for (int j = ti.G + 2; j < kMaxTreeDepth + 2; ++j) ti.off[j] = ti.off[ti.G + 1];
+    ti.n_nodes = ti.off[ti.G + 1];
+    ti.n_par = ti.off[ti.G];
+    ti.parent[0] = -1;
+    ti.depth[0] = 0;
+    ti.anc[0] = 1ull;
+    for (int j = 1; j <= ti.G; ++j)
+        for (int i = ti.off[j]; i < ti.off[j + 1]; ++i) {
+            ti.parent[i] = ti.off[j - 1] + (i - ti.off[j]) / ti.k[j - 1];
+            ti.depth[i] = j;
+            ti.anc[i] = ti.anc[ti.parent[i]] | (1ull << i);
+        }
+    *out = ti;
+    return SEED_OK;
+}
+
 namespace {
 
 constexpr int kMaxCounters = 4096;
@@ -43,7 +76,8 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, o_part, ml_part, logits, acc_stats, status;
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, o_part, ml_part, logits, acc_stats, status,
+        tree_depth, tree_anc, commit_rows;
     int n_pos;
     size_t part_floats;
     size_t total;
@@ -158,6 +192,9 @@ Layout make_layout(const seed_model_cfg &c) {
     L.logits = take((size_t)L.M_cap * V * 4);
     L.acc_stats = take(accept_scratch_bytes(L.M_cap));
     L.status = take(256);
+    L.tree_depth = take(kMaxTreeNodes * 4);
+    L.tree_anc = take(kMaxTreeNodes * 8);
+    L.commit_rows = take((size_t)c.max_branches * (kMaxTreeDepth + 2) * 4);
     L.total = off;
     return L;
 }
@@ -196,7 +233,16 @@ int check_accept_args(const seed_accept_args *a) {
         set_error("accept: need n_branches >= 0, gamma >= 1, vocab >= 1");
         return SEED_E_INVALID_ARG;
     }
-    if (a->n_target_rows != a->gamma && a->n_target_rows != a->gamma + 1) {
+    if (a->tree != nullptr) {
+        TreeInfo ti;
+        const int rc = expand_tree(a->tree, &ti);
+        if (rc) return rc;
+        if (a->gamma != ti.G) { set_error("accept: gamma %d must equal the tree's depth %d", a->gamma, ti.G); return SEED_E_SHAPE; }
+        if (a->n_target_rows != ti.n_par && a->n_target_rows != ti.n_nodes) {
+            set_error("accept: n_target_rows must be %d (nodes with children) or %d (all nodes)", ti.n_par, ti.n_nodes);
+            return SEED_E_SHAPE;
+        }
+    } else if (a->n_target_rows != a->gamma && a->n_target_rows != a->gamma + 1) {
         set_error("accept: n_target_rows must be gamma or gamma + 1");
         return SEED_E_SHAPE;
     }
@@ -262,7 +308,7 @@ KvPtrs kv_layer(const seed_ctx *c, int l) {
 // bf16 path: projections with fused epilogues (see gemm_bf16.hip); 5 launches per layer in a verify / decode
 // step (6 above 16 rows), 7 in the shared-prefix prefill.
 int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
-                     const int32_t *private_len, const int32_t *branch_slot, float *logits) {
+                     const int32_t *private_len, const int32_t *branch_slot, const TreeInfo *tree, float *logits) {
     const seed_model_cfg &g = c->cfg;
     const Layout &L = c->L;
     hipStream_t st = c->stream;
@@ -304,6 +350,15 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         return SEED_E_CAPACITY;
     }
 
+    const int32_t *row_depth = nullptr;
+    const unsigned long long *row_anc = nullptr;
+    if (tree != nullptr) {
+        // the per-row tables of the candidate tree: position offsets and who sees whom among a branch's rows
+        rc = launch_tree_tables(*tree, T, (int32_t *)at(c, L.tree_depth), (unsigned long long *)at(c, L.tree_anc), st);
+        if (rc) return rc;
+        row_depth = (const int32_t *)at(c, L.tree_depth);
+        row_anc = (const unsigned long long *)at(c, L.tree_anc);
+    }
     rc = launch_embed_norm(row_tok, at(c, L.emb), V, layer_w(c, 0, L.g_attn), x, at(c, L.act_d), ssq, M, d, status, st);
     if (rc) return rc;
     for (int l = 0; l < g.n_layers; ++l) {
@@ -333,6 +388,8 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         at_.counters = (int *)at(c, L.attn_counters);
         at_.act = at(c, L.act_hd);
         at_.status = status;
+        at_.row_depth = row_depth;
+        at_.row_anc = row_anc;
         at_.M = M; at_.Mp = Mp; at_.Mq = Mq; at_.N = N; at_.T = T; at_.H = H; at_.S = S;
         at_.prefill_shared = prefill_shared;
         at_.cap_s = L.cap_s; at_.cap_p = L.cap_p; at_.max_private = g.max_private;
@@ -422,12 +479,12 @@ int run_forward_f32(seed_ctx *c, int N, int T, int S, int prefill_shared, const 
 }
 
 int run_forward(seed_ctx *c, int N, int T, int S, int prefill_shared, const int32_t *row_tok,
-                const int32_t *private_len, const int32_t *branch_slot, float *logits) {
-    if (branch_slot != nullptr && (!c->bf16 || prefill_shared)) {
-        set_error("branch_slot needs a bf16 context and a verify / decode step");
+                const int32_t *private_len, const int32_t *branch_slot, const TreeInfo *tree, float *logits) {
+    if ((branch_slot != nullptr || tree != nullptr) && (!c->bf16 || prefill_shared)) {
+        set_error("branch_slot and candidate trees need a bf16 context and a verify / decode step");
         return SEED_E_UNSUPPORTED_DTYPE;
     }
-    return c->bf16 ? run_forward_bf16(c, N, T, S, prefill_shared, row_tok, private_len, branch_slot, logits)
+    return c->bf16 ? run_forward_bf16(c, N, T, S, prefill_shared, row_tok, private_len, branch_slot, tree, logits)
                    : run_forward_f32(c, N, T, S, prefill_shared, row_tok, private_len, logits);
 }
 
@@ -589,6 +646,11 @@ int seed_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *hip_str
 int seed_accept_resample(const seed_accept_args *args, void *hip_stream) {
     int rc = check_accept_args(args);
     if (rc) return rc;
+    if (args->tree != nullptr) {
+        TreeInfo ti;
+        if ((rc = expand_tree(args->tree, &ti))) return rc;
+        return launch_accept_tree(*args, ti, nullptr, nullptr, 0, nullptr, nullptr, (hipStream_t)hip_stream);
+    }
     return launch_accept(*args, nullptr, nullptr, 0, nullptr, (hipStream_t)hip_stream);
 }
 
@@ -604,6 +666,11 @@ int seed_accept_resample_static(const seed_accept_args *args, void *hip_stream) 
     void *stats = nullptr;
     rc = accept_static_scratch(&stats);
     if (rc) return rc;
+    if (args->tree != nullptr) {
+        TreeInfo ti;
+        if ((rc = expand_tree(args->tree, &ti))) return rc;
+        return launch_accept_tree(*args, ti, stats, nullptr, 0, nullptr, nullptr, (hipStream_t)hip_stream);
+    }
     return launch_accept(*args, stats, nullptr, 0, nullptr, (hipStream_t)hip_stream);
 }
 
@@ -658,6 +725,17 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
         if (a->private_len == nullptr) { set_error("step: private_len is NULL"); return SEED_E_NULL_PTR; }
     }
     if (a->row_tok == nullptr) { set_error("step: row_tok is NULL"); return SEED_E_NULL_PTR; }
+    TreeInfo tree;
+    const bool has_tree = a->tree != nullptr;
+    if (has_tree) {
+        int rc = expand_tree(a->tree, &tree);
+        if (rc) return rc;
+        if (prefill || (a->flags & SEED_STEP_COMMIT_ALL)) { set_error("step: a candidate tree cannot be combined with PREFILL_SHARED or COMMIT_ALL"); return SEED_E_INVALID_ARG; }
+        if (T != tree.n_par && T != tree.n_nodes) {
+            set_error("step: with this tree rows_per_branch must be %d (nodes with children) or %d (all nodes), not %d", tree.n_par, tree.n_nodes, T);
+            return SEED_E_SHAPE;
+        }
+    }
     seed_accept_args acc;
     if (a->accept != nullptr) {
         if (a->flags & SEED_STEP_COMMIT_ALL) { set_error("step: COMMIT_ALL cannot be combined with accept"); return SEED_E_INVALID_ARG; }
@@ -667,6 +745,7 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
         acc.vocab = g.vocab;
         acc.probs_kind = SEED_KIND_LOGITS;
         acc.greedy = (a->flags & SEED_STEP_GREEDY) ? 1 : acc.greedy;
+        acc.tree = a->tree;
         acc.p_or_logits = a->logits_out ? a->logits_out : (const float *)at(c, c->L.logits);
         if (acc.private_len == nullptr) acc.private_len = a->private_len;
         int rc = check_accept_args(&acc);
@@ -674,8 +753,20 @@ int seed_verify_step(seed_ctx *c, const seed_step_args *a) {
     }
     const bool want_logits = a->logits_out != nullptr || a->accept != nullptr;
     float *logits = want_logits ? (a->logits_out ? a->logits_out : (float *)at(c, c->L.logits)) : nullptr;
-    int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, a->branch_slot, logits);
+    int rc = run_forward(c, N, T, a->shared_len, prefill, a->row_tok, a->private_len, a->branch_slot,
+                         has_tree ? &tree : nullptr, logits);
     if (rc) return rc;
+    if (a->accept != nullptr && has_tree) {
+        int32_t *commit_rows = (int32_t *)at(c, c->L.commit_rows);
+        rc = launch_accept_tree(acc, tree, at(c, c->L.acc_stats), a->branch_slot, g.max_branches,
+                                (int32_t *)at(c, c->L.status), commit_rows, c->stream);
+        if (rc) return rc;
+        if (acc.private_len == nullptr) return SEED_OK;      // nothing committed: nothing to move
+        // the rows that are kept go to the front of each branch's in-flight region, in every layer
+        return launch_kv_compact(c->ws + c->L.kp, c->ws + c->L.vp, c->L.kp_stride, g.n_layers, commit_rows, acc.private_len,
+                                 a->branch_slot, g.max_branches, N, g.n_heads, g.head_dim, c->L.cap_p, g.max_private,
+                                 c->stream);
+    }
     if (a->accept != nullptr)
         return launch_accept(acc, at(c, c->L.acc_stats), a->branch_slot, g.max_branches, (int32_t *)at(c, c->L.status),
                              c->stream);
@@ -701,7 +792,7 @@ int seed_draft_step(seed_ctx *c, const seed_draft_args *a) {
     if (a->q_out != nullptr && a->q_stride < g.vocab) { set_error("draft: q_stride < vocab"); return SEED_E_INVALID_ARG; }
     if (a->tok_stride < 1) { set_error("draft: tok_stride must be >= 1"); return SEED_E_INVALID_ARG; }
     float *logits = a->logits_out ? a->logits_out : (float *)at(c, c->L.logits);
-    int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, a->branch_slot, logits);
+    int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, a->branch_slot, nullptr, logits);
     if (rc) return rc;
     return launch_softmax_sample(logits, g.vocab, a->temperature, greedy, a->u, a->q_out, a->q_stride, a->tok_out,
                                  a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats), a->branch_slot,

@@ -15,12 +15,28 @@ hipStream_t seed_ctx_stream(const seed_ctx *c);
 const seed_model_cfg &seed_ctx_cfg(const seed_ctx *c);
 int hip_fail(hipError_t e, const char *what);
 
+// ---- candidate trees ----------------------------------------------------------------------------
+constexpr int kMaxTreeDepth = 8;               // positions of a draft phase
+constexpr int kMaxTreeNodes = 64;              // nodes of a branch's tree, root included (64-bit ancestor masks)
+struct TreeInfo {                              // host-side expansion of a seed_tree
+    int G, n_nodes, n_par;                     // positions; nodes (root included); nodes that have children
+    int k[kMaxTreeDepth];
+    int off[kMaxTreeDepth + 2];                // first node of each level; off[G + 1] = n_nodes
+    int parent[kMaxTreeNodes], depth[kMaxTreeNodes];
+    unsigned long long anc[kMaxTreeNodes];     // bit j: node j is the node itself or an ancestor
+};
+int expand_tree(const seed_tree *t, TreeInfo *out);   // validates; SEED_OK or an error code (message set)
+
 // ---- accept.hip ------------------------------------------------------------------------------
 size_t accept_scratch_bytes(int max_rows);
 constexpr int kStaticAcceptRows = 4096;        // most target rows of a seed_accept_resample_static call
 int accept_static_scratch(void **out);         // this GPU's statistics array for that entry point
 int launch_accept(const seed_accept_args &a, void *scratch, const int32_t *branch_slot, int n_slots,
                   int32_t *status, hipStream_t st);   // scratch, branch_slot, status may be NULL
+// commit_rows (optional, [n_branches][kMaxTreeDepth + 2] ints): per branch the number of rows that stay in the
+// cache, then the accepted node at each depth (the root, row 0, is implied)
+int launch_accept_tree(const seed_accept_args &a, const TreeInfo &t, void *scratch, const int32_t *branch_slot,
+                       int n_slots, int32_t *status, int32_t *commit_rows, hipStream_t st);
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
@@ -75,6 +91,10 @@ int launch_kv_import(bool bf16, bool transpose, const void *src, void *dst, int 
                      hipStream_t st);
 int launch_hbm_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t st);
 int launch_calib_spin(unsigned long long ticks, unsigned long long *elapsed_total, hipStream_t st);
+int launch_tree_tables(const TreeInfo &t, int n_rows, int32_t *depth_out, unsigned long long *anc_out, hipStream_t st);
+int launch_kv_compact(void *k_priv, void *vt_priv, size_t layer_stride_bytes, int n_layers, const int32_t *commit_rows,
+                      const int32_t *private_len, const int32_t *branch_slot, int n_slots, int n_branches, int H, int dh,
+                      int cap_p, int max_private, hipStream_t st);
 int launch_add_len(int32_t *len, int n, int delta, const int32_t *branch_slot, int n_slots, hipStream_t st);
 // ---- attention_bf16.hip ----------------------------------------------------------------------------
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
@@ -95,6 +115,8 @@ struct AttnBf16Args {
     int *counters;
     void *act;
     int32_t *status;
+    const int32_t *row_depth;                // candidate trees: depth and ancestor mask of the T rows of a branch
+    const unsigned long long *row_anc;       //   (both NULL: chain)
     int M, Mp, Mq, N, T, H, S, prefill_shared, cap_s, cap_p, max_private, ks_shared, keys_per_range, ks_priv,
         keys_per_range_priv;
 };
