@@ -167,6 +167,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
         }
     }
     const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
+    const int bx_ = blockIdx.x;
 
     // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
     const int ld_part = a.NT * 16;
@@ -195,36 +196,17 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
             const size_t ps = (size_t)a.M * ld_part;
             const int wu = __builtin_amdgcn_readfirstlane(w);
             if (wu >= kWaves) return;
-            for (int t = wu; t < kTilesN * TM; t += kWaves) {
-                const int tg = t / TM, tm = t - tg * TM;
-                const int nt = blockIdx.x * kTilesN + tg;
-                if (nt > nt_last) continue;                  // (uniform) ragged last column group
-                const int row = tm * 16 + rlow, col = nt * 16 + 4 * g;
-                const bool valid = row < a.M;
-                f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (valid) {
-                    const float *pp = a.part + (size_t)row * ld_part + col;
-                    int sk = 0;
-                    for (; sk + 4 <= a.SK; sk += 4) {
-                        const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
-                        const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
-                        s += p0;
-                        s += p1;
-                        s += p2;
-                        s += p3;
-                    }
-                    for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
-                }
+            // one tile's share of the epilogue, given the sum s of its partials (and, RESID, its residual rows
+            // and the next norm's gains)
+            auto finish_one = [&](int nt, int row, int col, bool valid, const f32x4 &s, const f32x4 &x_in, const uint2 &gw) {
                 if (EPI == EPI_STORE) {
                     const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
                     if (valid) *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + col) = s * sc;
                 } else {
                     float ss = 0.f;
                     if (valid) {
-                        float *xp2 = a.x + (size_t)row * ld_part + col;
-                        const f32x4 xv = *reinterpret_cast<f32x4 *>(xp2) + s;
-                        *reinterpret_cast<f32x4 *>(xp2) = xv;
-                        const uint2 gw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                        const f32x4 xv = x_in + s;
+                        *reinterpret_cast<f32x4 *>(a.x + (size_t)row * ld_part + col) = xv;
                         const float gv[4] = {bf2f((uint16_t)(gw.x & 0xffff)), bf2f((uint16_t)(gw.x >> 16)),
                                              bf2f((uint16_t)(gw.y & 0xffff)), bf2f((uint16_t)(gw.y >> 16))};
                         float v[4];
@@ -239,6 +221,74 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
                     ss += __shfl_xor(ss, 32);
                     if (valid && g == 0) a.ssq[(size_t)row * a.NT + nt] = ss;
                 }
+            };
+            constexpr int kTilesWG = kTilesN * TM;
+            constexpr int kPerWave = (kTilesWG + kWaves - 1) / kWaves;
+            constexpr int kBatchSK = 4;
+            if (a.SK <= kBatchSK && kPerWave <= 4) {
+                // Up to four partials of ALL of this wavefront's tiles are requested before the first is used: the
+                // loads go around the L2 (a trip to memory each), and tile after tile would pay that latency
+                // kPerWave times (three at 96 rows: most of a 9 us tail).  Straight-line code with clamped
+                // addresses; what lies past the tile list or past SK is loaded again and dropped.
+                f32x4 pv[kPerWave][kBatchSK], xin[kPerWave];
+                uint2 gws[kPerWave];
+                int nts[kPerWave], rows[kPerWave];
+                bool oks[kPerWave];
+#pragma unroll
+                for (int q = 0; q < kPerWave; ++q) {
+                    const int t = min(wu + q * kWaves, kTilesWG - 1);
+                    const int tg = t / TM, tm = t - tg * TM;
+                    const int nt = min(bx_ * kTilesN + tg, nt_last);
+                    const int row = min(tm * 16 + rlow, a.M - 1), col = nt * 16 + 4 * g;
+                    nts[q] = nt;
+                    rows[q] = row;
+                    oks[q] = wu + q * kWaves < kTilesWG && bx_ * kTilesN + tg <= nt_last && tm * 16 + rlow < a.M;
+                    const float *pp = a.part + (size_t)row * ld_part + col;
+#pragma unroll
+                    for (int sk = 0; sk < kBatchSK; ++sk) pv[q][sk] = load4_agent(pp + (size_t)min(sk, a.SK - 1) * ps);
+                    if (EPI == EPI_RESID) {
+                        xin[q] = *reinterpret_cast<const f32x4 *>(a.x + (size_t)row * ld_part + col);
+                        gws[q] = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kPerWave; ++q) {
+                    f32x4 s = pv[q][0];                       // same order of summation as everywhere: 0, 1, 2, ...
+#pragma unroll
+                    for (int sk = 1; sk < kBatchSK; ++sk)
+                        if (sk < a.SK) s += pv[q][sk];
+                    if (wu + q * kWaves < kTilesWG && nts[q] == bx_ * kTilesN + min(wu + q * kWaves, kTilesWG - 1) / TM)
+                        finish_one(nts[q], rows[q], nts[q] * 16 + 4 * g, oks[q], s, xin[q], gws[q]);
+                }
+                return;
+            }
+            for (int t = wu; t < kTilesN * TM; t += kWaves) {
+                const int tg = t / TM, tm = t - tg * TM;
+                const int nt = bx_ * kTilesN + tg;
+                if (nt > nt_last) continue;                  // (uniform) ragged last column group
+                const int row = tm * 16 + rlow, col = nt * 16 + 4 * g;
+                const bool valid = row < a.M;
+                f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+                f32x4 x_in = s;
+                uint2 gw = {0u, 0u};
+                if (valid) {
+                    const float *pp = a.part + (size_t)row * ld_part + col;
+                    int sk = 0;
+                    for (; sk + 4 <= a.SK; sk += 4) {
+                        const f32x4 p0 = load4_agent(pp + (sk + 0) * ps), p1 = load4_agent(pp + (sk + 1) * ps);
+                        const f32x4 p2 = load4_agent(pp + (sk + 2) * ps), p3 = load4_agent(pp + (sk + 3) * ps);
+                        s += p0;
+                        s += p1;
+                        s += p2;
+                        s += p3;
+                    }
+                    for (; sk < a.SK; ++sk) s += load4_agent(pp + sk * ps);
+                    if (EPI == EPI_RESID) {
+                        x_in = *reinterpret_cast<const f32x4 *>(a.x + (size_t)row * ld_part + col);
+                        gw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
+                    }
+                }
+                finish_one(nt, row, col, valid, s, x_in, gw);
             }
             return;
         }

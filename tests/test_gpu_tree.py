@@ -55,9 +55,8 @@ def test_tree_walk_probs_mode_is_bit_exact(N, k_config, bonus, V):
         assert np.array_equal(a, want[0]) and np.array_equal(out, want[1]) and np.array_equal(n_out, want[2])
         assert np.array_equal(path, want[3][:, :len(k_config)])
         assert np.array_equal(p_tok, want[4][:, 1:])
-    if V > 16 and N >= 5 and max(k_config) > 1:
-        assert 0 < want[0].sum() < N * len(k_config)
-        # later candidates do get accepted: some accepted node is not the first child of its parent
+    if V >= 1000 and max(k_config) > 1:
+        # the cases exercise the later rounds: some accepted node is not the first child of its parent
         kids = oracle.children_of(parent)
         assert any(want[3][b, d] >= 0 and want[3][b, d] != kids[parent[want[3][b, d]]][0]
                    for b in range(N) for d in range(len(k_config)))
