@@ -115,12 +115,12 @@ __device__ __forceinline__ void load_q_raw(const AttnParams &P, int r, int h, in
         }
     }
 }
-template <int DH>
+template <int DH, bool TREE>
 __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, const RawQ<DH> &q,
                                          bf16x8 (&qf)[DH / 32][2]) {
     constexpr int KS = DH / 32;
     const int j = r % P.T;
-    const int dj = P.row_depth != nullptr ? P.row_depth[j] : j;      // tree: a row sits at its depth, not its index
+    const int dj = TREE ? P.row_depth[j] : j;      // candidate tree: a row sits at its depth, not its index
     const int pos = P.S + min(max(q.pl, 0), P.max_private) + dj;
     const float *tb = P.rope + (size_t)pos * DH;
 #pragma unroll
@@ -258,7 +258,7 @@ __device__ __forceinline__ void store_partial_direct(const AttnParams &P, int h,
 // The four wavefronts of the workgroup interleave the 32-key chunks of the range and merge through LDS into one
 // partial (every barrier is reached by all four).  Used for every task of a step with one row group and for
 // the private segment; the shared segment of steps with several row groups goes through attn_task_lds.
-template <int DH, bool FUSED>
+template <int DH, bool FUSED, bool TREE>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part, char *smem) {
@@ -306,7 +306,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
         if (FUSED) {
-            rotate_q<DH>(P, min(row0 + t * 16 + col, P.M - 1), g, qraw[t], qf[t]);
+            rotate_q<DH, TREE>(P, min(row0 + t * 16 + col, P.M - 1), g, qraw[t], qf[t]);
         } else {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -425,7 +425,7 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 // workgroup (each thread a few 16-byte pieces, two chunks ahead in registers), stored to LDS in MFMA-fragment
 // order (two stages) and read from there by all wavefronts; one barrier per chunk.  The wavefronts write
 // their partials straight from the accumulators.  Wavefronts without a row group (n_grp < 4) only help load.
-template <int DH, bool FUSED>
+template <int DH, bool FUSED, bool TREE>
 __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, const uint16_t *kbase,
                               const uint16_t *vtbase, int kbeg, int kend, int lim0, int inc, int part,
                               char *smem) {
@@ -482,7 +482,7 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
     if (FUSED) {
         load_q_raw<DH>(P, qrow, h, g, qraw);
         __builtin_amdgcn_sched_barrier(0);
-        rotate_q<DH>(P, qrow, g, qraw, qf[0]);
+        rotate_q<DH, TREE>(P, qrow, g, qraw, qf[0]);
     } else {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -531,7 +531,7 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
 // lanes own DH/64 dims; dot products are wavefront-shuffle reductions.  q and the keys are rotated on the
 // fly from the fp32 QKV output, and the wavefront of row r appends that row's rotated key and its value to
 // the private cache.
-template <int DH>
+template <int DH, bool TREE>
 __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     constexpr int PER = DH / 64, HALF = DH / 2;
     const int lane = threadIdx.x & 63;
@@ -564,9 +564,8 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     const float *tb0 = P.rope + (size_t)(P.S + pl) * DH;
     // candidate trees (Section 2.2 "Tree Attention"; appendix): row j sees, among the rows of its branch, only
     // itself and its ancestors, and every row sits at the position of its depth
-    const bool tree = P.row_depth != nullptr;
-    const unsigned long long anc = tree ? P.row_anc[j] : ~0ull;
-    auto depth_of = [&](int jj) { return tree ? P.row_depth[jj] : jj; };
+    const unsigned long long anc = TREE ? P.row_anc[j] : ~0ull;
+    auto depth_of = [&](int jj) { return TREE ? P.row_depth[jj] : jj; };
     float qv[PER], o[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
@@ -591,7 +590,7 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
         }
 #pragma unroll
         for (int u = 0; u < kB; ++u) {
-            if (j0 + u > j || !((anc >> ((j0 + u) & 63)) & 1ull)) continue;    // (uniform over the wavefront)
+            if (j0 + u > j || (TREE && !((anc >> ((j0 + u) & 63)) & 1ull))) continue;    // (uniform over the wavefront)
             const float s = wave_reduce_sum_dpp(sc[u]) * P.scale_log2e;   // (DPP: the keys of a row are a dependent chain)
             const float m_new = fmaxf(m, s);
             const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
@@ -704,7 +703,7 @@ __device__ __forceinline__ void merge_rows(const float *o_part, const float *ml_
     }
 }
 
-template <int DH, bool FUSED>
+template <int DH, bool FUSED, bool TREE>
 __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     constexpr int RT = kRowTiles;
     // workgroup tasks: first the shared segment, then one per (branch, head, row group, private key range)
@@ -734,7 +733,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         const int grp0 = quad * P.gpw;
-        attn_task_lds<DH, FUSED>(P, h, grp0, min(P.gpw, P.n_groups - grp0), P.k_shared + (size_t)h * P.cap_s * DH,
+        attn_task_lds<DH, FUSED, TREE>(P, h, grp0, min(P.gpw, P.n_groups - grp0), P.k_shared + (size_t)h * P.cap_s * DH,
                                  P.vt_shared + (size_t)h * DH * P.cap_s, kbeg, max(kbeg, kend),
                                  P.prefill_shared ? P.S + 1 : P.S, P.prefill_shared ? 1 : 0, ks, smem);
         return;                                           // (the merge is a launch of its own in this mode)
@@ -747,7 +746,7 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
         // verify: every row sees all S shared keys; prefill: row j sees keys < S + j + 1
-        attn_task<DH, FUSED>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
+        attn_task<DH, FUSED, TREE>(P, h, grp * 16 * RT, P.M, P.k_shared + (size_t)h * P.cap_s * DH,
                              P.vt_shared + (size_t)h * DH * P.cap_s, P.cap_s, kbeg, max(kbeg, kend),
                              P.prefill_shared ? P.S + 1 : P.S, 0, P.prefill_shared ? 1 : 0, ks, smem);
     } else {
@@ -766,12 +765,12 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
             const int kend = min(pl, kbeg + P.keys_per_range_priv);
             // every row of the branch sees all pl committed private keys
             const size_t sb = (size_t)slot_of(P, b);
-            attn_task<DH, FUSED>(P, h, row_first, row_end, P.k_priv + (sb * P.H + h) * P.cap_p * DH,
+            attn_task<DH, FUSED, TREE>(P, h, row_first, row_end, P.k_priv + (sb * P.H + h) * P.cap_p * DH,
                                  P.vt_priv + (sb * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
                                  pl, b * P.T, 0, P.ks_shared + ks, smem);
         }
         if (FUSED && ks == 0)
-            for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH>(P, h, r);
+            for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH, TREE>(P, h, r);
     }
     if (FUSED && P.merge_in_launch) {
         // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
@@ -880,15 +879,16 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     // four wavefronts, so they get a merge launch with a wavefront per (row, head)
     P.merge_in_launch = fused && !P.wave_tasks;
     const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
-#define SEEDV_ATTN(DHv, FUSEDv) \
-    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv>), dim3(blocks), dim3(256), 0, st, P)
+    const bool tree = fused && a.row_depth != nullptr && a.row_anc != nullptr;
+#define SEEDV_ATTN(DHv, FUSEDv, TREEv) \
+    hipLaunchKernelGGL((attn_partial_kernel<DHv, FUSEDv, TREEv>), dim3(blocks), dim3(256), 0, st, P)
     if (a.dh == 128) {
-        if (fused) SEEDV_ATTN(128, true); else SEEDV_ATTN(128, false);
+        if (tree) SEEDV_ATTN(128, true, true); else if (fused) SEEDV_ATTN(128, true, false); else SEEDV_ATTN(128, false, false);
         if (!P.merge_in_launch)
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
                                a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);
     } else {
-        if (fused) SEEDV_ATTN(64, true); else SEEDV_ATTN(64, false);
+        if (tree) SEEDV_ATTN(64, true, true); else if (fused) SEEDV_ATTN(64, true, false); else SEEDV_ATTN(64, false, false);
         if (!P.merge_in_launch)
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((a.Mp * a.H + 3) / 4), dim3(256), 0, st, a.o_part,
                                a.ml_part, (uint16_t *)a.act, a.M, a.Mq, a.Mp, a.H, np);

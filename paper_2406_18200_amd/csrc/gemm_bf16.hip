@@ -29,6 +29,7 @@
 // gemm_kernel (1..4 row tiles, and the narrow outputs at any row count) and gemm_wide_kernel (5..8 row tiles
 // on outputs of 600 n-tiles and more; described where it is defined).  gemm_bf16_pick chooses form, workgroup
 // shape and split from measurements on the 7B / 13B projection shapes.
+#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <type_traits>
@@ -69,7 +70,25 @@ struct Shape {
 __device__ __forceinline__ void pin_args(const GemmArgs &a) {
     asm volatile("" ::"s"(a.Wp), "s"(a.Xp), "s"(a.NT), "s"(a.KT), "s"(a.kt_per_split), "s"(a.SK), "s"(a.M),
                  "s"(a.part), "s"(a.counters), "s"(a.out), "s"(a.ld_out), "s"(a.ssq_in), "s"(a.NT_in), "s"(a.x),
-                 "s"(a.gain), "s"(a.act_out), "s"(a.KT_out), "s"(a.ssq), "s"(a.eps));
+                 "s"(a.gain), "s"(a.act_out), "s"(a.KT_out), "s"(a.ssq), "s"(a.eps), "s"(a.MS));
+}
+
+// Which column group and which share of the rows this workgroup works on.  With MS > 1 the rows of a step are
+// split over MS workgroups per column group (TM row tiles each): every workgroup then stages and re-reads only
+// its own rows' activations through LDS -- the saturated resource at 65..128 rows -- and takes MS times the columns
+// instead.  The MS workgroups of a column group read the same weights; they are laid out so that they run on the
+// SAME XCD at the same time (workgroups go to the eight XCDs round robin in launch order, so ids L and L + 8 are
+// neighbours in time on one XCD): the second request finds the line in that XCD's L2 and HBM is still read once.
+// The grid is rounded up to whole rounds of eight column groups; padding workgroups return at once.
+__device__ __forceinline__ bool wg_coords(const GemmArgs &a, int tiles_per_wg, int &cg, int &mh) {
+    cg = blockIdx.x;
+    mh = 0;
+    if (a.MS > 1) {
+        const int L = blockIdx.x;
+        mh = (L >> 3) % a.MS;
+        cg = (L / (8 * a.MS)) * 8 + (L & 7);
+    }
+    return cg * tiles_per_wg < a.NT;
 }
 
 __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int KT, const float *v) {
@@ -128,7 +147,7 @@ __device__ __forceinline__ void rows_rinv(const GemmArgs &a, float *s_rinv, int 
 template <int TM, int TN, int WN, int WK, int EPI, bool kPre>
 __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN][TM], char *smem, int *s_last_p,
                                              float *s_rinv, const f32x4 (&x_pre)[TN][TM], const uint2 (&gain_pre)[TN],
-                                             bool ssq_early, int nt0, bool active) {
+                                             bool ssq_early, int nt0, bool active, int cg, int mh) {
     using S = Shape<TM, TN, WN, WK>;
     constexpr int kWaves = S::kWaves;
     constexpr int RT = S::kRedTiles < TN * TM ? S::kRedTiles : TN * TM;   // tiles per reduction round
@@ -167,7 +186,8 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
         }
     }
     const bool owner = active && wk == 0;                 // this wavefront holds finished tiles
-    const int bx_ = blockIdx.x;
+    const int bx_ = cg;
+    const int rbase = mh * TM * 16;                       // first row of this workgroup's share
 
     // D[i][j]: lane holds features 4*(lane/16)+0..3 (columns) of token row lane%16
     const int ld_part = a.NT * 16;
@@ -175,10 +195,10 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
         // split-K across workgroups: publish the partial, then the last workgroup of this column group sums
         // all partials in a fixed order
         if (owner) {
-            float *pb = a.part + (size_t)blockIdx.y * a.M * ld_part;
+            float *pb = a.part + (size_t)blockIdx.y * a.M * ld_part;   // (partials are indexed by global row)
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                const int row = tm * 16 + rlow;
+                const int row = rbase + tm * 16 + rlow;
                 if (row >= a.M) continue;
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
@@ -186,7 +206,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
                         store4_agent(pb + (size_t)row * ld_part + (nt0 + tn) * 16 + 4 * g, acc[tn][tm]);
             }
         }
-        if (!arrive_last(&a.counters[blockIdx.x], a.SK, &s_last)) return;
+        if (!arrive_last(&a.counters[cg * a.MS + mh], a.SK, &s_last)) return;
         if constexpr (EPI != EPI_SWIGLU) {
             // Every wavefront of the last workgroup finishes a share of the workgroup's tiles: the partials lie
             // in global memory, so the wavefront that computed a tile need not be the one that sums it.  (With
@@ -239,10 +259,10 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
                     const int t = min(wu + q * kWaves, kTilesWG - 1);
                     const int tg = t / TM, tm = t - tg * TM;
                     const int nt = min(bx_ * kTilesN + tg, nt_last);
-                    const int row = min(tm * 16 + rlow, a.M - 1), col = nt * 16 + 4 * g;
+                    const int row = min(rbase + tm * 16 + rlow, a.M - 1), col = nt * 16 + 4 * g;
                     nts[q] = nt;
                     rows[q] = row;
-                    oks[q] = wu + q * kWaves < kTilesWG && bx_ * kTilesN + tg <= nt_last && tm * 16 + rlow < a.M;
+                    oks[q] = wu + q * kWaves < kTilesWG && bx_ * kTilesN + tg <= nt_last && rbase + tm * 16 + rlow < a.M;
                     const float *pp = a.part + (size_t)row * ld_part + col;
 #pragma unroll
                     for (int sk = 0; sk < kBatchSK; ++sk) pv[q][sk] = load4_agent(pp + (size_t)min(sk, a.SK - 1) * ps);
@@ -266,7 +286,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
                 const int tg = t / TM, tm = t - tg * TM;
                 const int nt = bx_ * kTilesN + tg;
                 if (nt > nt_last) continue;                  // (uniform) ragged last column group
-                const int row = tm * 16 + rlow, col = nt * 16 + 4 * g;
+                const int row = rbase + tm * 16 + rlow, col = nt * 16 + 4 * g;
                 const bool valid = row < a.M;
                 f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
                 f32x4 x_in = s;
@@ -295,7 +315,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
         if (owner) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                const int row = tm * 16 + rlow;
+                const int row = rbase + tm * 16 + rlow;
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
                     f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -322,7 +342,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
     if (!owner) return;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int row = tm * 16 + rlow;
+        const int row = rbase + tm * 16 + rlow;
         const bool valid = row < a.M;
         if (EPI == EPI_STORE) {
             const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
@@ -397,7 +417,10 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     pin_args(a);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wn = w % WN, wk = w / WN;
-    const int nt0 = (blockIdx.x * WN + wn) * TN;
+    int cg, mh;
+    if (!wg_coords(a, WN * TN, cg, mh)) return;          // (uniform: a padding workgroup of a row-split launch)
+    const int mt0 = mh * TM, mt_last = (a.M + 15) / 16 - 1;   // first row tile of this workgroup; last one there is
+    const int nt0 = (cg * WN + wn) * TN;
     const bool active = nt0 < a.NT;
     const int KT = a.KT;
     const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
@@ -420,7 +443,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
         for (int i = 0; i < PER; ++i) {
             const int f = min(w + i * kWaves, FR - 1);    // fragment (k, tm, hi|lo) of the chunk
             const int k = f / (TM * 2), r = f - k * (TM * 2);
-            xr[i] = xp[(((size_t)(r >> 1) * KT + min(kc0 + k, KT - 1)) * 2 + (r & 1)) * 64 + lane];
+            xr[i] = xp[(((size_t)min(mt0 + (r >> 1), mt_last) * KT + min(kc0 + k, KT - 1)) * 2 + (r & 1)) * 64 + lane];
         }
     };
     auto store_x = [&](int kc0) {
@@ -464,7 +487,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             gain_pre[tn] = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.gain) + col);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                const int row = min(tm * 16 + rlow, a.M - 1);
+                const int row = min(mt0 * 16 + tm * 16 + rlow, a.M - 1);
                 x_pre[tn][tm] = *reinterpret_cast<const f32x4 *>(a.x + (size_t)row * (a.NT * 16) + col);
             }
         }
@@ -540,7 +563,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             for (int oc = 0; oc < OU; ++oc) chunk(k0 + (it * OU + oc) * XKT, oc, std::false_type{});
         }
     }
-    finish_tiles<TM, TN, WN, WK, EPI, kPre>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, ssq_early, nt0, active);
+    finish_tiles<TM, TN, WN, WK, EPI, kPre>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, ssq_early, nt0, active, cg, mh);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -666,7 +689,10 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (scalar: addresses below stay in SGPRs)
     const int wn = w % WN, wk = w / WN;
-    const int nt0 = (blockIdx.x * WN + wn) * TN;
+    int cg, mh;
+    if (!wg_coords(a, WN * TN, cg, mh)) return;          // (uniform: a padding workgroup of a row-split launch)
+    const int mt0 = mh * TM, mt_last = (a.M + 15) / 16 - 1;   // first row tile of this workgroup; last one there is
+    const int nt0 = (cg * WN + wn) * TN;
     const bool active = nt0 < a.NT;
     const int KT = a.KT;
     const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
@@ -694,7 +720,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
             const int f = w + i * kWaves;
             const int kk = f / (2 * TM), r = f - kk * (2 * TM);
             const int kt = min(k0 + g * GK + kk, KT - 1);
-            const bf16x8 *src = xp + (((size_t)(r >> 1) * KT + kt) * 2 + (r & 1)) * 64;
+            const bf16x8 *src = xp + (((size_t)min(mt0 + (r >> 1), mt_last) * KT + kt) * 2 + (r & 1)) * 64;
             __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(smem + base + f * 1024), 16,
                                              0, 0);
         }
@@ -785,7 +811,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     wait_vmcnt<0>();
     f32x4 x_pre[TN][TM];
     uint2 gain_pre[TN];
-    finish_tiles<TM, TN, WN, WK, EPI, false>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, /*ssq_early=*/true, nt0, active);
+    finish_tiles<TM, TN, WN, WK, EPI, false>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, /*ssq_early=*/true, nt0, active, cg, mh);
 }
 
 // Repack row-major W[n_rows][K] (bf16) into fragment tiles.  Destination tile index of source n-tile
@@ -822,7 +848,9 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
                       a.NT * 16, a.part_floats);
             return SEED_E_CAPACITY;
         }
-        dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
+        const int groups = (a.NT + WN * TN - 1) / (WN * TN);
+        if (b.MS < 1) b.MS = 1;
+        dim3 grid(b.MS > 1 ? (groups + 7) / 8 * 8 * b.MS : groups, b.SK), block(WN * WK * 64);
         if (epi == EPI_SWIGLU) {
             if constexpr (TN >= 2) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
             else { set_error("gemm: SwiGLU epilogue needs paired tiles"); return SEED_E_INVALID_ARG; }
@@ -874,7 +902,9 @@ int launch_wide_shape(const GemmArgs &a, int epi, hipStream_t st) {
             set_error("gemm: the wide form addresses weights with 32-bit offsets (matrix of %d x %d tiles)", a.NT, a.KT);
             return SEED_E_CAPACITY;
         }
-        dim3 grid((a.NT + WN * TN - 1) / (WN * TN), b.SK), block(WN * WK * 64);
+        const int groups = (a.NT + WN * TN - 1) / (WN * TN);
+        if (b.MS < 1) b.MS = 1;
+        dim3 grid(b.MS > 1 ? (groups + 7) / 8 * 8 * b.MS : groups, b.SK), block(WN * WK * 64);
         int rc;
         if (epi == EPI_SWIGLU) {
             if constexpr (TN >= 2) {
@@ -907,6 +937,10 @@ int launch_wide(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t 
 #undef SEEDV_SHAPE
     // twelve wavefronts, six n-tiles per workgroup: 1376 n-tiles (7B gate/up) become 230 workgroups instead of 172
     if (tn == 2 && wn == 3 && wk == 4) return launch_wide_shape<TM, 2, 3, 4>(a, epi, st);
+    // ... twelve n-tiles per workgroup: the shape of the row-split launches (half the rows, twice the columns)
+    if constexpr (TM <= 4) {
+        if (tn == 4 && wn == 3 && wk == 4) return launch_wide_shape<TM, 4, 3, 4>(a, epi, st);
+    }
     // ... and three n-tiles per workgroup, one per wavefront: 768 n-tiles (7B QKV) become 256 workgroups
     if (tn == 1 && wn == 3 && wk == 4 && epi != EPI_SWIGLU) return launch_wide_shape<TM, 1, 3, 4>(a, epi, st);
     set_error("gemm: unsupported wide workgroup shape %dx%d with %d n-tiles", wn, wk, tn);
@@ -946,6 +980,7 @@ int launch_large(const GemmArgs &a, int epi, int wn, int wk, int tn, hipStream_t
 // Launch with an explicit workgroup shape (wn x wk wavefronts, tn n-tiles per wavefront) and a.SK
 // workgroups along K.
 int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, int tn, int wide, hipStream_t st) {
+    if (a.MS > 1) m_tiles = (m_tiles + a.MS - 1) / a.MS;          // row tiles per workgroup of a row-split launch
     if (epi == EPI_SWIGLU && (tn < 2 || a.NT % 2 != 0)) {
         set_error("gemm: the SwiGLU epilogue needs paired tiles (tn=%d, NT=%d)", tn, a.NT);
         return SEED_E_INVALID_ARG;
@@ -982,9 +1017,42 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
 // rows: wide outputs share activation fragments across wavefronts (WN); narrow outputs split K inside the
 // workgroup (WK), over all eight wavefronts when that gives one workgroup per CU without a split across
 // workgroups (no partials to exchange), else over four with two workgroups along K.
-void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide) {
+// Row-split launches (65..128 rows): can be switched off for A/B measurements with SEED_GEMM_ROW_SPLIT=0.
+static bool row_split_enabled() {
+    static const bool on = [] {
+        const char *e = getenv("SEED_GEMM_ROW_SPLIT");
+        return e == nullptr || e[0] != '0';
+    }();
+    return on;
+}
+
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms) {
     *sk = 1;
     *wide = 0;
+    *ms = 1;
+    if (m_tiles >= 5 && row_split_enabled()) {
+        // Two workgroups per column group, three or four row tiles each (see wg_coords).
+        const int tm = (m_tiles + 1) / 2;
+        if (NT >= 600) {
+            // wide outputs: twelve wavefronts (3 x 4); as few n-tiles per wavefront as keep the launch within one
+            // round of workgroups (7B QKV: 2 -> 128 column groups x 2; 7B gate/up: 4 -> 115 x 2)
+            for (int t : {2, 4}) {
+                const int groups = ((NT + 3 * t - 1) / (3 * t) + 7) / 8 * 8;
+                if (groups * 2 <= 256 && wide_params(tm, t, 3, 4).valid && NT % t == 0) {
+                    *wn = 3; *wk = 4; *tn = t; *wide = 1; *ms = 2;
+                    return;
+                }
+            }
+        } else if (KT >= 64) {
+            // narrow outputs: 2 x 4 wavefronts, four n-tiles per workgroup, and a split of K that brings the
+            // launch to about one workgroup per CU (7B O / down: 64 column groups x 2 row shares x 2)
+            const int groups = ((NT + 3) / 4 + 7) / 8 * 8;
+            int fill = (256 + groups) / (2 * groups);
+            fill = fill < 1 ? 1 : (fill > 4 ? 4 : fill);
+            *wn = 2; *wk = 4; *tn = 2; *sk = fill; *ms = 2;
+            return;
+        }
+    }
     if (m_tiles <= 2) {
         *tn = (epi == EPI_SWIGLU || (NT >= 1300 && NT % 2 == 0)) ? 2 : 1;
         const int units = NT / *tn;                        // n-tile groups a wavefront owns one of
@@ -1026,8 +1094,9 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
 }
 
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
-    int wn, wk, tn, sk, wide;
-    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide);
+    int wn, wk, tn, sk, wide, ms;
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms);
+    a.MS = ms;
     if (a.SK < 1) a.SK = sk;
     return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
 }

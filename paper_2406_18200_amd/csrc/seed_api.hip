@@ -331,11 +331,11 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.part_floats = L.part_floats;
         a.counters = (int *)at(c, L.counters);
         a.eps = g.rms_eps;
-        int wn, wk, tn, sk, wide;
-        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide);
+        int wn, wk, tn, sk, wide, ms;
+        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms);
         while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
         a.SK = sk;
-        if (sk > 1 && a.NT / (wn * tn) + 2 > kMaxCounters) {
+        if (sk > 1 && (a.NT / (wn * tn) + 8) * ms + 2 > kMaxCounters) {
             set_error("projection with %d column groups exceeds the counter array", a.NT / (wn * tn));
             return SEED_E_CAPACITY;
         }

@@ -66,8 +66,9 @@ struct GemmArgs {
     int KT_out;            //   its k-tile count
     float *ssq;            // RESID: [M][NT] per-tile sums of squares of the new residual stream (out)
     float eps;
+    int MS;                // row splits: MS workgroups per column group, each with 1 / MS of the row tiles (0 or 1: none)
 };
-void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide);
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms);
 int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk, int tn, int wide, hipStream_t st);
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st);   // a.SK < 1: pick automatically
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,
