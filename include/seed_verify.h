@@ -20,8 +20,12 @@
  *     kernel is launched.  Nothing throws or aborts across this boundary.
  *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
  *   - Matrices are row-major [out][in].  dtype 0: float32 weights and KV cache; dtype 1: bfloat16
- *     weights and KV cache.  Logits, probabilities and uniforms are always float32; token ids and
- *     lengths are int32.
+ *     weights and KV cache; dtype 2: as 1, but the seven projection matrices of every layer and the LM head are
+ *     given as OCP e4m3 codes (uint8: sign, 4 exponent bits of bias 7, 3 mantissa bits, no infinities; the code
+ *     0x7f / 0xff is not a number and must not occur) with one float32 scale per output row, W[o][i] =
+ *     scale[o] * value(code[o][i]): half the bytes of the weight stream that bounds a step.  Embedding, RMSNorm
+ *     gains and the KV cache stay bfloat16.  Logits, probabilities and uniforms are always float32; token ids
+ *     and lengths are int32.
  */
 #ifndef SEED_VERIFY_H
 #define SEED_VERIFY_H
@@ -44,6 +48,7 @@ extern "C" {
 
 #define SEED_DTYPE_F32 0
 #define SEED_DTYPE_BF16 1
+#define SEED_DTYPE_BF16_W8 2 /* as BF16, but the projection matrices are one byte per weight (see seed_layer_w) */
 
 /* seed_accept_args.probs_kind */
 #define SEED_KIND_LOGITS 0 /* p_or_logits holds raw logits; the kernel applies softmax(logits / temperature) */
@@ -71,6 +76,8 @@ typedef struct {
     const void *wq, *wk, *wv, *wo;      /* [H*dh][d], [H*dh][d], [H*dh][d], [d][H*dh] */
     const void *wgate, *wup, *wdown;    /* [F][d], [F][d], [d][F]                     */
     const void *norm_attn, *norm_ffn;   /* [d] RMSNorm gains                          */
+    /* dtype SEED_DTYPE_BF16_W8 only (else ignored, may be NULL): float32 scale per output row of each matrix */
+    const float *sq, *sk, *sv, *so, *sgate, *sup, *sdown;
 } seed_layer_w;
 
 typedef struct {
@@ -78,6 +85,7 @@ typedef struct {
     const void *norm_final;     /* [d]                                       */
     const void *lm_head;        /* [V][d] (untied)                           */
     const seed_layer_w *layers; /* HOST array of n_layers entries            */
+    const float *lm_head_scale; /* [V], dtype SEED_DTYPE_BF16_W8 only        */
 } seed_weights;
 
 /*

@@ -25,12 +25,13 @@ class ModelCfgC(C.Structure):
 
 
 class LayerWC(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm_attn", "norm_ffn")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm_attn", "norm_ffn",
+                                          "sq", "sk", "sv", "so", "sgate", "sup", "sdown")]
 
 
 class WeightsC(C.Structure):
     _fields_ = [("tok_emb", C.c_void_p), ("norm_final", C.c_void_p), ("lm_head", C.c_void_p),
-                ("layers", C.POINTER(LayerWC))]
+                ("layers", C.POINTER(LayerWC)), ("lm_head_scale", C.c_void_p)]
 
 
 class TreeC(C.Structure):
@@ -163,7 +164,7 @@ class ModelShape:
     head_dim: int
     d_ff: int
     vocab: int
-    dtype: str                    # "fp32" | "bf16"
+    dtype: str                    # "fp32" | "bf16" | "bf16w8" (projection matrices as e4m3 codes + row scales)
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     max_branches: int = 16
@@ -173,7 +174,7 @@ class ModelShape:
 
     def to_c(self):
         return ModelCfgC(self.n_layers, self.d_model, self.n_heads, self.head_dim, self.d_ff, self.vocab,
-                         1 if self.dtype == "bf16" else 0, self.rms_eps, self.rope_theta, self.max_branches,
+                         {"fp32": 0, "bf16": 1, "bf16w8": 2}[self.dtype], self.rms_eps, self.rope_theta, self.max_branches,
                          self.max_rows_per_branch, self.max_shared, self.max_private)
 
 
@@ -268,9 +269,11 @@ class VerifyContext:
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         layers = (LayerWC * shape.n_layers)()
         for l, lw in enumerate(weights["layers"]):
-            layers[l] = LayerWC(*[_ptr(lw[n]) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown",
-                                                          "norm_attn", "norm_ffn")])
-        w = WeightsC(_ptr(weights["tok_emb"]), _ptr(weights["norm_final"]), _ptr(weights["lm_head"]), layers)
+            layers[l] = LayerWC(*[_ptr(lw.get(n)) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown",
+                                                              "norm_attn", "norm_ffn", "sq", "sk", "sv", "so",
+                                                              "sgate", "sup", "sdown")])
+        w = WeightsC(_ptr(weights["tok_emb"]), _ptr(weights["norm_final"]), _ptr(weights["lm_head"]), layers,
+                     _ptr(weights.get("lm_head_scale")))
         self.handle = C.c_void_p()
         self.stream = torch.cuda.current_stream(self.device)
         _check(self.lib.seed_verify_init(C.byref(self.handle), C.byref(self.cfg), C.byref(w),

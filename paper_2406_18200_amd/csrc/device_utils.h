@@ -9,6 +9,7 @@ namespace seedv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 // float -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint16_t f2bf(float f) {

@@ -70,7 +70,25 @@ struct Shape {
 __device__ __forceinline__ void pin_args(const GemmArgs &a) {
     asm volatile("" ::"s"(a.Wp), "s"(a.Xp), "s"(a.NT), "s"(a.KT), "s"(a.kt_per_split), "s"(a.SK), "s"(a.M),
                  "s"(a.part), "s"(a.counters), "s"(a.out), "s"(a.ld_out), "s"(a.ssq_in), "s"(a.NT_in), "s"(a.x),
-                 "s"(a.gain), "s"(a.act_out), "s"(a.KT_out), "s"(a.ssq), "s"(a.eps), "s"(a.MS));
+                 "s"(a.gain), "s"(a.act_out), "s"(a.KT_out), "s"(a.ssq), "s"(a.eps), "s"(a.MS), "s"(a.w_scale));
+}
+
+// 8-bit weights (context dtype SEED_DTYPE_BF16_W8): the same tiles with one byte per weight, an OCP e4m3 code
+// (sign, 4 exponent bits of bias 7, 3 mantissa bits; no infinities), and one float scale per output feature:
+// tile (nt, kt) is 512 bytes, lane l holding the 8 codes of W[nt*16 + l%16][kt*32 + 8*(l/16) .. +8].  Half the
+// bytes cross HBM; on the way into the MFMA every code is widened to the bf16 of the same value (exact: three
+// mantissa bits) with the hardware's packed fp8 -> float32 conversion, and the scale multiplies the fp32 sums once,
+// after the k loop (before anything is exchanged or reduced: scaling is linear).
+__device__ __forceinline__ bf16x8 widen_e4m3(u32x2 c) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t src = (i < 2) ? c[0] : c[1];
+        const auto f = (i & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true) : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
+        // the bf16 of a float32 that has at most four significant bits is its upper half
+        r[i] = (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+    }
+    return __builtin_bit_cast(bf16x8, r);
 }
 
 // Which column group and which share of the rows this workgroup works on.  With MS > 1 the rows of a step are
@@ -397,7 +415,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
     }
 }
 
-template <int TM, int TN, int WN, int WK, int EPI>
+template <int TM, int TN, int WN, int WK, int EPI, bool W8>
 __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     using S = Shape<TM, TN, WN, WK>;
     constexpr int U = S::U, KC = S::KC, D = S::D, XG = S::XG, kWaves = S::kWaves;
@@ -431,7 +449,6 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const bf16x8 *wbase = reinterpret_cast<const bf16x8 *>(a.Wp) + lane;
     const int nt_last = a.NT - 1;                        // a ragged last group re-reads the last tile (never stored)
     const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(a.Xp);
     // The k loop is straight-line code (no data-dependent branches, clamped addresses), so that the compiler
@@ -458,14 +475,16 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             }
         }
     };
-    bf16x8 ring[D][U][TN];                                // weight fragments in flight: D chunks ahead
-    auto load_a = [&](bf16x8 (&dst)[U][TN], int k) {      // this wavefront's U k-tiles of the chunk at k
+    using WFrag = std::conditional_t<W8, u32x2, bf16x8>;   // a lane's piece of a weight tile: 8 codes or 8 bf16
+    const WFrag *wbase_f = reinterpret_cast<const WFrag *>(a.Wp) + lane;
+    WFrag ring[D][U][TN];                                 // weight fragments in flight: D chunks ahead
+    auto load_a = [&](WFrag (&dst)[U][TN], int k) {       // this wavefront's U k-tiles of the chunk at k
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
                 dst[u][tn] = __builtin_nontemporal_load(
-                    wbase + ((size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1)) * 64);
+                    wbase_f + ((size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1)) * 64);
     };
     // Prologue order: the first weight groups and the first activation chunk are requested at once; the
     // epilogue operands that do not depend on this launch follow (vector loads complete in order, so they are
@@ -543,12 +562,18 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                     bh[tm] = xs[gq * KC + wk * U + u][tm][0][lane];
                     bl[tm] = xs[gq * KC + wk * U + u][tm][1][lane];
                 }
+                bf16x8 wa[TN];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    if constexpr (W8) wa[tn] = widen_e4m3(ring[dd][u][tn]);
+                    else wa[tn] = ring[dd][u][tn];
+                }
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) {
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bl[tm], acc[tn][tm], 0, 0, 0);
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[dd][u][tn], bh[tm], acc[tn][tm], 0, 0, 0);
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[tn], bl[tm], acc[tn][tm], 0, 0, 0);
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[tn], bh[tm], acc[tn][tm], 0, 0, 0);
                     }
             }
             if (!LAST || gq + D < XG) load_a(ring[dd], kc + D * KC);   // refill this slot D groups ahead (clamped)
@@ -561,6 +586,15 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
         for (int it = 0; it < n_outer; ++it) {
 #pragma unroll
             for (int oc = 0; oc < OU; ++oc) chunk(k0 + (it * OU + oc) * XKT, oc, std::false_type{});
+        }
+    }
+    if constexpr (W8) {
+        // one scale per output feature: lane (., g) holds features 4g .. 4g + 3 of each of its n-tiles
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const f32x4 sc = *reinterpret_cast<const f32x4 *>(a.w_scale + (size_t)min(nt0 + tn, nt_last) * 16 + 4 * g);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) acc[tn][tm] *= sc;
         }
     }
     finish_tiles<TM, TN, WN, WK, EPI, kPre>(a, acc, smem, &s_last, s_rinv, x_pre, gain_pre, ssq_early, nt0, active, cg, mh);
@@ -830,6 +864,26 @@ __global__ void pack_weight_kernel(const uint16_t *__restrict__ W, u32x4 *__rest
     dst[(((size_t)(dst_tile0 + nt * dst_tile_step)) * KT + kt) * 64 + lane] = v;
 }
 
+// The same repacking for one-byte weights: row-major codes [n_rows][K] into 512-byte tiles, and the per-row
+// scales into the order of the packed tiles.
+__global__ void pack_weight8_kernel(const uint8_t *__restrict__ W, uint2 *__restrict__ dst, int n_tiles, int K, int KT,
+                                    int dst_tile0, int dst_tile_step) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 8-byte fragment each
+    const size_t total = (size_t)n_tiles * KT * 64;
+    if (idx >= total) return;
+    const int lane = idx & 63;
+    const size_t tile = idx >> 6;
+    const int kt = tile % KT;
+    const int nt = tile / KT;
+    const uint8_t *src = W + (size_t)(nt * 16 + (lane & 15)) * K + kt * 32 + 8 * (lane >> 4);
+    dst[(((size_t)(dst_tile0 + nt * dst_tile_step)) * KT + kt) * 64 + lane] = *reinterpret_cast<const uint2 *>(src);
+}
+__global__ void pack_scale_kernel(const float *__restrict__ src, float *__restrict__ dst, int n_rows, int dst_tile0,
+                                  int dst_tile_step) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < n_rows) dst[(size_t)(dst_tile0 + (r >> 4) * dst_tile_step) * 16 + (r & 15)] = src[r];
+}
+
 template <int TM, int TN, int WN, int WK>
 int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
     using S = Shape<TM, TN, WN, WK>;
@@ -851,13 +905,18 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         const int groups = (a.NT + WN * TN - 1) / (WN * TN);
         if (b.MS < 1) b.MS = 1;
         dim3 grid(b.MS > 1 ? (groups + 7) / 8 * 8 * b.MS : groups, b.SK), block(WN * WK * 64);
+        const bool w8 = b.w_scale != nullptr;
         if (epi == EPI_SWIGLU) {
-            if constexpr (TN >= 2) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU>), grid, block, 0, st, b);
-            else { set_error("gemm: SwiGLU epilogue needs paired tiles"); return SEED_E_INVALID_ARG; }
+            if constexpr (TN >= 2) {
+                if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU, true>), grid, block, 0, st, b);
+                else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU, false>), grid, block, 0, st, b);
+            } else { set_error("gemm: SwiGLU epilogue needs paired tiles"); return SEED_E_INVALID_ARG; }
         } else if (epi == EPI_RESID) {
-            hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID>), grid, block, 0, st, b);
+            if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID, true>), grid, block, 0, st, b);
+            else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID, false>), grid, block, 0, st, b);
         } else {
-            hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE>), grid, block, 0, st, b);
+            if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE, true>), grid, block, 0, st, b);
+            else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE, false>), grid, block, 0, st, b);
         }
         return hip_fail(hipGetLastError(), "gemm launch");
     }
@@ -898,6 +957,7 @@ int launch_wide_shape(const GemmArgs &a, int epi, hipStream_t st) {
                       a.NT * 16, a.part_floats);
             return SEED_E_CAPACITY;
         }
+        if (a.w_scale != nullptr) { set_error("gemm: the wide form streams bf16 weights only"); return SEED_E_UNSUPPORTED_DTYPE; }
         if ((size_t)a.NT * a.KT * 1024 >= ((size_t)1 << 32)) {
             set_error("gemm: the wide form addresses weights with 32-bit offsets (matrix of %d x %d tiles)", a.NT, a.KT);
             return SEED_E_CAPACITY;
@@ -1026,10 +1086,31 @@ static bool row_split_enabled() {
     return on;
 }
 
-void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms) {
+void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
+                    int w8) {
     *sk = 1;
     *wide = 0;
     *ms = 1;
+    if (w8) {
+        // one-byte weights run in the first form only (with row shares from five row tiles on)
+        *tn = (m_tiles > 2 || epi == EPI_SWIGLU || (NT >= 1300 && NT % 2 == 0)) ? 2 : 1;
+        if (m_tiles >= 5) *ms = 2;
+        const int units = NT / *tn;
+        if (m_tiles <= 2 && units >= 600) { *wn = 4; *wk = 2; }
+        else if (m_tiles == 1 && NT <= 256) { *wn = 1; *wk = 8; }
+        else if (m_tiles > 2 && NT >= 1300) { *wn = 4; *wk = 2; }
+        else {
+            *wn = 2; *wk = 4;
+            if (NT < 600) {
+                const int groups = (NT + *tn * 2 - 1) / (*tn * 2) * *ms;
+                const int fill = (256 + groups / 2) / groups;
+                *sk = fill < 1 ? 1 : (fill > 4 ? 4 : fill);
+                if (m_tiles <= 2) *sk = NT <= 256 ? 2 : 1;
+            }
+        }
+        if (KT < 64) *sk = 1;
+        return;
+    }
     if (m_tiles >= 5 && row_split_enabled()) {
         // Two workgroups per column group, three or four row tiles each (see wg_coords).
         const int tm = (m_tiles + 1) / 2;
@@ -1095,10 +1176,21 @@ void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int 
 
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
     int wn, wk, tn, sk, wide, ms;
-    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms);
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, a.w_scale != nullptr);
     a.MS = ms;
     if (a.SK < 1) a.SK = sk;
     return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
+}
+
+int launch_pack_weight8(const void *codes, const float *scale, void *dst, float *scale_dst, int n_rows, int K,
+                        int dst_tile0, int dst_tile_step, hipStream_t st) {
+    const int n_tiles = n_rows / 16, KT = K / 32;
+    const size_t total = (size_t)n_tiles * KT * 64;
+    hipLaunchKernelGGL(pack_weight8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t *)codes, (uint2 *)dst, n_tiles, K, KT, dst_tile0, dst_tile_step);
+    hipLaunchKernelGGL(pack_scale_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, scale, scale_dst, n_rows,
+                       dst_tile0, dst_tile_step);
+    return hip_fail(hipGetLastError(), "pack launch");
 }
 
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,

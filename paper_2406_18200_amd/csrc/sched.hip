@@ -127,7 +127,7 @@ int seed_sched_run(seed_ctx *target, seed_ctx *draft, const seed_sched_args *a) 
         set_error("sched: need 1 <= n_branches <= %d, gamma >= 1, max_new >= 1", kMaxN);
         return SEED_E_INVALID_ARG;
     }
-    if (gt.dtype != SEED_DTYPE_BF16 || gd.dtype != SEED_DTYPE_BF16) {
+    if (gt.dtype == SEED_DTYPE_F32 || gd.dtype == SEED_DTYPE_F32) {
         set_error("sched: both contexts must be bf16 contexts");
         return SEED_E_UNSUPPORTED_DTYPE;
     }

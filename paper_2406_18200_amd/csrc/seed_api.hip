@@ -71,8 +71,8 @@ struct Layout {
     size_t es;                    // bytes per weight / KV element
     int HD, M_cap, Mp_cap, Mq_cap, cap_s, cap_p;
     // weights
-    size_t w_qkv, w_o, w_gu, w_d, g_attn, g_ffn, layer_stride, layers0;
-    size_t emb, g_final, lm;
+    size_t w_qkv, w_o, w_gu, w_d, s_qkv, s_o, s_gu, s_d, g_attn, g_ffn, layer_stride, layers0;
+    size_t emb, g_final, lm, s_lm;
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
@@ -85,7 +85,7 @@ struct Layout {
 
 int validate_cfg(const seed_model_cfg *c) {
     if (c == nullptr) { set_error("cfg is NULL"); return SEED_E_NULL_PTR; }
-    if (c->dtype != SEED_DTYPE_F32 && c->dtype != SEED_DTYPE_BF16) {
+    if (c->dtype != SEED_DTYPE_F32 && c->dtype != SEED_DTYPE_BF16 && c->dtype != SEED_DTYPE_BF16_W8) {
         set_error("unsupported dtype %d", c->dtype);
         return SEED_E_UNSUPPORTED_DTYPE;
     }
@@ -100,7 +100,7 @@ int validate_cfg(const seed_model_cfg *c) {
     }
     const long HD = (long)c->n_heads * c->head_dim;
     if (c->head_dim % 2) { set_error("head_dim must be even"); return SEED_E_SHAPE; }
-    if (c->dtype == SEED_DTYPE_BF16) {
+    if (c->dtype != SEED_DTYPE_F32) {
         if (c->d_model % 32 || c->d_ff % 32 || HD % 32 || c->vocab % 16) {
             set_error("bf16 path needs d_model, d_ff, n_heads*head_dim multiples of 32 and vocab a multiple of 16");
             return SEED_E_SHAPE;
@@ -137,8 +137,10 @@ int validate_cfg(const seed_model_cfg *c) {
 
 Layout make_layout(const seed_model_cfg &c) {
     Layout L{};
-    const bool bf = c.dtype == SEED_DTYPE_BF16;
+    const bool bf = c.dtype != SEED_DTYPE_F32;
+    const bool w8 = c.dtype == SEED_DTYPE_BF16_W8;
     L.es = bf ? 2 : 4;
+    const size_t ws = w8 ? 1 : L.es;                // bytes per projection weight
     const size_t d = c.d_model, F = c.d_ff, V = c.vocab, H = c.n_heads, dh = c.head_dim;
     L.HD = (int)(H * dh);
     const size_t HD = L.HD;
@@ -152,17 +154,23 @@ Layout make_layout(const seed_model_cfg &c) {
     // one layer's weights
     size_t lo = 0;
     auto ltake = [&](size_t bytes) { size_t o = lo; lo = align_up(lo + bytes, 256); return o; };
-    L.w_qkv = ltake(3 * HD * d * L.es);
-    L.w_o = ltake(d * HD * L.es);
-    L.w_gu = ltake(2 * F * d * L.es);
-    L.w_d = ltake(d * F * L.es);
+    L.w_qkv = ltake(3 * HD * d * ws);
+    L.w_o = ltake(d * HD * ws);
+    L.w_gu = ltake(2 * F * d * ws);
+    L.w_d = ltake(d * F * ws);
+    // (one-byte weights: per-output-row scales, in the order of the packed tiles)
+    L.s_qkv = ltake(w8 ? 3 * HD * 4 : 0);
+    L.s_o = ltake(w8 ? d * 4 : 0);
+    L.s_gu = ltake(w8 ? 2 * F * 4 : 0);
+    L.s_d = ltake(w8 ? d * 4 : 0);
     L.g_attn = ltake(d * L.es);
     L.g_ffn = ltake(d * L.es);
     L.layer_stride = lo;
     L.layers0 = take(L.layer_stride * c.n_layers);
     L.emb = take(V * d * L.es);
     L.g_final = take(d * L.es);
-    L.lm = take(V * d * L.es);
+    L.lm = take(V * d * ws);
+    L.s_lm = take(w8 ? V * 4 : 256);
     L.ks_stride = align_up(H * L.cap_s * dh * L.es, 256);
     L.kp_stride = align_up((size_t)c.max_branches * H * L.cap_p * dh * L.es, 256);
     L.ks = take(L.ks_stride * c.n_layers);
@@ -210,6 +218,7 @@ struct seed_ctx {
     char *ws;
     hipStream_t stream;
     bool bf16;
+    bool w8;                             // projection matrices as e4m3 codes + per-row scales
     // projection-kernel profiling (seed_verify_profile_*)
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;     // start/stop pairs, reused
@@ -321,8 +330,9 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
     const size_t q_plane = (size_t)L.Mq_cap * HD;
     int rc;
 
-    auto gemm = [&](int epi, const void *W, int Nout, int K, const void *Xp, GemmArgs a) -> int {
+    auto gemm = [&](int epi, const void *W, const void *scale, int Nout, int K, const void *Xp, GemmArgs a) -> int {
         a.Wp = W;
+        a.w_scale = c->w8 ? (const float *)scale : nullptr;
         a.Xp = Xp;
         a.NT = Nout / 16;
         a.KT = K / 32;
@@ -332,14 +342,14 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.counters = (int *)at(c, L.counters);
         a.eps = g.rms_eps;
         int wn, wk, tn, sk, wide, ms;
-        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms);
+        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, c->w8);
         while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
         a.SK = sk;
         if (sk > 1 && (a.NT / (wn * tn) + 8) * ms + 2 > kMaxCounters) {
             set_error("projection with %d column groups exceeds the counter array", a.NT / (wn * tn));
             return SEED_E_CAPACITY;
         }
-        return profiled(c, (double)Nout * K * 2.0, [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
+        return profiled(c, (double)Nout * K * (c->w8 ? 1.0 : 2.0), [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
     };
 
     int ks_shared = 1, keys_per_range = 32, ks_priv = 0, keys_per_range_priv = 128;
@@ -367,7 +377,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.ld_out = 3 * HD;
         a.ssq_in = ssq;
         a.NT_in = d / 16;
-        rc = gemm(EPI_STORE, layer_w(c, l, L.w_qkv), 3 * HD, d, at(c, L.act_d), a);
+        rc = gemm(EPI_STORE, layer_w(c, l, L.w_qkv), layer_w(c, l, L.s_qkv), 3 * HD, d, at(c, L.act_d), a);
         if (rc) return rc;
         const KvPtrs kv = kv_layer(c, l);
         if (prefill_shared) {
@@ -403,18 +413,18 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         o.act_out = (uint16_t *)at(c, L.act_d);
         o.KT_out = d / 32;
         o.ssq = ssq;
-        rc = gemm(EPI_RESID, layer_w(c, l, L.w_o), d, HD, at(c, L.act_hd), o);
+        rc = gemm(EPI_RESID, layer_w(c, l, L.w_o), layer_w(c, l, L.s_o), d, HD, at(c, L.act_hd), o);
         if (rc) return rc;
         GemmArgs gu{};
         gu.ssq_in = ssq;
         gu.NT_in = d / 16;
         gu.act_out = (uint16_t *)at(c, L.act_f);
         gu.KT_out = F / 32;
-        rc = gemm(EPI_SWIGLU, layer_w(c, l, L.w_gu), 2 * F, d, at(c, L.act_d), gu);
+        rc = gemm(EPI_SWIGLU, layer_w(c, l, L.w_gu), layer_w(c, l, L.s_gu), 2 * F, d, at(c, L.act_d), gu);
         if (rc) return rc;
         GemmArgs dn = o;
         dn.gain = (l + 1 < g.n_layers) ? layer_w(c, l + 1, L.g_attn) : at(c, L.g_final);
-        rc = gemm(EPI_RESID, layer_w(c, l, L.w_d), d, F, at(c, L.act_f), dn);
+        rc = gemm(EPI_RESID, layer_w(c, l, L.w_d), layer_w(c, l, L.s_d), d, F, at(c, L.act_f), dn);
         if (rc) return rc;
     }
     if (logits != nullptr) {
@@ -423,7 +433,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.ld_out = V;
         a.ssq_in = ssq;
         a.NT_in = d / 16;
-        rc = gemm(EPI_STORE, at(c, L.lm), V, d, at(c, L.act_d), a);
+        rc = gemm(EPI_STORE, at(c, L.lm), at(c, L.s_lm), V, d, at(c, L.act_d), a);
         if (rc) return rc;
     }
     return SEED_OK;
@@ -518,6 +528,16 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
             return SEED_E_NULL_PTR;
         }
     }
+    if (cfg->dtype == SEED_DTYPE_BF16_W8) {
+        if (!w->lm_head_scale) { set_error("weights: lm_head_scale is NULL"); return SEED_E_NULL_PTR; }
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            const seed_layer_w &lw = w->layers[l];
+            if (!lw.sq || !lw.sk || !lw.sv || !lw.so || !lw.sgate || !lw.sup || !lw.sdown) {
+                set_error("weights: layer %d has a NULL scale array", l);
+                return SEED_E_NULL_PTR;
+            }
+        }
+    }
     if (((uintptr_t)workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return SEED_E_INVALID_ARG; }
     Layout L = make_layout(*cfg);
     if (workspace_bytes < L.total) {
@@ -530,7 +550,8 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     c->L = L;
     c->ws = (char *)workspace;
     c->stream = (hipStream_t)hip_stream;
-    c->bf16 = cfg->dtype == SEED_DTYPE_BF16;
+    c->bf16 = cfg->dtype != SEED_DTYPE_F32;
+    c->w8 = cfg->dtype == SEED_DTYPE_BF16_W8;
     hipStream_t st = c->stream;
     const size_t es = L.es, d = cfg->d_model, F = cfg->d_ff, V = cfg->vocab, HD = L.HD;
     auto copy = [&](void *dst, const void *src, size_t bytes) {
@@ -539,7 +560,17 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
 #define SEEDV_TRY(expr) do { rc = (expr); if (rc) { delete c; return rc; } } while (0)
     for (int l = 0; l < cfg->n_layers; ++l) {
         const seed_layer_w &lw = w->layers[l];
-        if (c->bf16) {
+        if (c->w8) {
+            const int qt = (int)(HD / 16);
+            float *sqkv = (float *)layer_w(c, l, L.s_qkv), *sgu = (float *)layer_w(c, l, L.s_gu);
+            SEEDV_TRY(launch_pack_weight8(lw.wq, lw.sq, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wk, lw.sk, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, qt, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wv, lw.sv, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 2 * qt, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wo, lw.so, layer_w(c, l, L.w_o), (float *)layer_w(c, l, L.s_o), (int)d, (int)HD, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wgate, lw.sgate, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 0, 2, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wup, lw.sup, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 1, 2, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wdown, lw.sdown, layer_w(c, l, L.w_d), (float *)layer_w(c, l, L.s_d), (int)d, (int)F, 0, 1, st));
+        } else if (c->bf16) {
             const int qt = (int)(HD / 16);
             SEEDV_TRY(launch_pack_weight(lw.wq, layer_w(c, l, L.w_qkv), (int)HD, (int)d, 0, 1, st));
             SEEDV_TRY(launch_pack_weight(lw.wk, layer_w(c, l, L.w_qkv), (int)HD, (int)d, qt, 1, st));
@@ -564,7 +595,8 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     }
     SEEDV_TRY(copy(at(c, L.emb), w->tok_emb, V * d * es));
     SEEDV_TRY(copy(at(c, L.g_final), w->norm_final, d * es));
-    if (c->bf16) SEEDV_TRY(launch_pack_weight(w->lm_head, at(c, L.lm), (int)V, (int)d, 0, 1, st));
+    if (c->w8) SEEDV_TRY(launch_pack_weight8(w->lm_head, w->lm_head_scale, at(c, L.lm), (float *)at(c, L.s_lm), (int)V, (int)d, 0, 1, st));
+    else if (c->bf16) SEEDV_TRY(launch_pack_weight(w->lm_head, at(c, L.lm), (int)V, (int)d, 0, 1, st));
     else SEEDV_TRY(copy(at(c, L.lm), w->lm_head, V * d * es));
     // KV caches and scratch start at zero: chunked key loops may touch (masked) entries past the valid length
     SEEDV_TRY(hip_fail(hipMemsetAsync(at(c, L.ks), 0, L.total - L.ks, st), "workspace clear"));

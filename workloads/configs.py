@@ -16,7 +16,8 @@ class ModelCfg:
     head_dim: int
     d_ff: int
     vocab: int
-    dtype: str            # "fp32" or "bf16": storage type of weights and KV cache
+    dtype: str            # "fp32" or "bf16": storage type of weights and KV cache; "bf16w8": bf16 with the
+                          # projection matrices as one-byte e4m3 codes + per-row scales
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
 

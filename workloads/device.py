@@ -7,7 +7,23 @@ from .gen import Weights
 
 
 def torch_dtype(model):
-    return torch.bfloat16 if model.dtype == "bf16" else torch.float32
+    return torch.float32 if model.dtype == "fp32" else torch.bfloat16
+
+
+_MATRICES = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+def _quantized(w, model, device, on_device=False):
+    """One-byte weights ("bf16w8"): (device codes uint8, device scales float32, dequantised float32 host copy).
+    on_device: timing runs only -- the same rule evaluated by torch on the GPU (no host copy, nothing to compare)."""
+    if on_device:
+        t = torch.from_numpy(np.ascontiguousarray(w)).to(device)
+        scale = (t.abs().amax(dim=1) / 448.0).clamp_min(1e-30)
+        codes = (t / scale[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+        return codes, scale.float(), None
+    from .fp8 import quantize_rows
+    codes, scale, deq = quantize_rows(w)
+    return torch.from_numpy(codes).to(device), torch.from_numpy(scale).to(device), deq
 
 
 def to_device(arr, model, device="cuda:0"):
@@ -20,7 +36,8 @@ class UploadingWeights:
     """Wraps a Weights generator: every tensor handed out (e.g. to the oracle) is also uploaded once to the
     GPU, so a large model is generated a single time for both sides."""
 
-    def __init__(self, model, seed, device="cuda:0", reuse_buffers=True):
+    def __init__(self, model, seed, device="cuda:0", reuse_buffers=True, device_quantize=False):
+        self.device_quantize = device_quantize
         self.inner = Weights(model, seed, reuse_buffers=reuse_buffers)
         self.model = model
         self.device = device
@@ -38,11 +55,26 @@ class UploadingWeights:
 
     def lm_head(self):
         a = self.inner.lm_head()
+        if self.model.dtype == "bf16w8":
+            # (the oracle gets the dequantised values: what the library's codes and scales stand for)
+            if "lm_head_deq" not in self.dev:
+                self.dev["lm_head"], self.dev["lm_head_scale"], self.dev["lm_head_deq"] = _quantized(a, self.model, self.device, self.device_quantize)
+            return self.dev["lm_head_deq"]
         self.dev.setdefault("lm_head", to_device(a, self.model, self.device))
         return a
 
     def layer(self, l):
         w = self.inner.layer(l)
+        if self.model.dtype == "bf16w8":
+            out, dev = {}, {}
+            for k, v in w.items():
+                if k in _MATRICES:
+                    dev[k], dev["s" + k[1:]], out[k] = _quantized(v, self.model, self.device, self.device_quantize)
+                else:
+                    dev[k], out[k] = to_device(v, self.model, self.device), v
+            if self.dev["layers"][l] is None:
+                self.dev["layers"][l] = dev
+            return out
         if self.dev["layers"][l] is None:
             self.dev["layers"][l] = {k: to_device(v, self.model, self.device) for k, v in w.items()}
         return w

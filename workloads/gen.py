@@ -79,7 +79,7 @@ class Weights:
         (saves the page-fault cost of fresh allocations when streaming a large model)."""
         self.model = model
         self.seed = seed
-        self.bf16 = model.dtype == "bf16"
+        self.bf16 = model.dtype != "fp32"
         self._bufs = {} if reuse_buffers else None
 
     def _mat(self, tid, shape, name=None):
@@ -148,7 +148,7 @@ def synthetic_kv(wl, layer):
     """Synthetic-KV protocol: post-RoPE K and V ~ N(0,1) for the shared prefix [H][S][dh] and the
     private contexts [N][H][R][dh] of one layer, on the storage grid of the model dtype."""
     m = wl.model
-    bf16 = m.dtype == "bf16"
+    bf16 = m.dtype != "fp32"
     H, dh = m.n_heads, m.head_dim
     base = 1000 + 4 * layer
     ks = normal_tensor(wl.seed + 1, base + 0, (H, wl.S, dh), 1.0, 0.0, bf16) if wl.S else \
