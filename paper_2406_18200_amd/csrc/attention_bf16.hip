@@ -67,6 +67,7 @@ struct AttnParams {
     int wave_tasks;           // several row groups: shared tasks are attn_task_lds workgroups
     int gpw, n_quads;         // row groups per such workgroup (<= 4), workgroups per (head, key range)
     int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
+    int pair_xcd;             // shared tasks of one (head, key range) on ids L, L+8, ...: one XCD, one L2
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
     int prefill_shared;       // rows additionally see shared keys S .. S+j (their own chunk, causal)
@@ -152,13 +153,22 @@ __device__ __forceinline__ void rotate_q(const AttnParams &P, int r, int g, cons
 }
 
 // One 32-key chunk for the RT row tiles of a task: S^T = K.Q^T, online softmax, O^T += V^T.P^T.
-// kf / vf are the chunk's A operands (any source), c its first key.
+// kf / vf are the chunk's A operands (any source), c its first key.  full (uniform over the wavefront): every
+// key of the chunk is visible to every row of the task, no mask.
+// The loop around this runs on two wavefronts per SIMD and is bound by instruction issue and latency, not by
+// the MFMAs or by memory, so the softmax is kept short (about half the vector instructions of the textbook
+// form): the running maximum is a REFERENCE, not the exact maximum -- it moves (and O and the sum are rescaled)
+// only when a chunk's maximum exceeds it by more than kRescaleStep in the exponent, so p <= 2^kRescaleStep and
+// most chunks skip the rescale altogether (the partial (m, l, O) stays self-consistent, the merge divides by
+// l); scores are scaled inside the fused multiply-add that feeds exp2; the hi/lo split uses the hardware
+// bf16 conversion.
+constexpr float kRescaleStep = 8.f;
 template <int DH>
 __device__ __forceinline__ void chunk_update(const bf16x8 (&kf)[2][DH / 32], const bf16x8 (&vf)[DH / 16],
                                              const bf16x8 (&qf)[kRowTiles][DH / 32][2],
                                              f32x4 (&o)[DH / 16][kRowTiles], float (&m_run)[kRowTiles],
                                              float (&l_run)[kRowTiles], const int (&limit)[kRowTiles], int c,
-                                             int kend, float scale_log2e) {
+                                             int kend, float scale_log2e, bool full) {
     constexpr int RT = kRowTiles, KS = DH / 32, DT = DH / 16;
     const int g = (threadIdx.x & 63) >> 4;
     f32x4 s[2][RT];                             // [key tile][row tile]
@@ -181,38 +191,47 @@ __device__ __forceinline__ void chunk_update(const bf16x8 (&kf)[2][DH / 32], con
         // lane holds keys c + 8g + {0..3} (tile 0) and c + 8g + {4..7} (tile 1) of query row `col`
         float sv[8];
         float mx = -INFINITY;
+        if (full) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int key = c + 8 * g + i;
-            float v = s[i >> 2][t][i & 3] * scale_log2e;
-            v = (key < limit[t] && key < kend) ? v : -INFINITY;
-            sv[i] = v;
-            mx = fmaxf(mx, v);
+            for (int i = 0; i < 8; ++i) {
+                sv[i] = s[i >> 2][t][i & 3];
+                mx = fmaxf(mx, sv[i]);
+            }
+        } else {
+            const int lim = min(limit[t], kend) - (c + 8 * g);      // keys 0 .. lim-1 of this lane's eight
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                sv[i] = i < lim ? s[i >> 2][t][i & 3] : -INFINITY;
+                mx = fmaxf(mx, sv[i]);
+            }
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[t], mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
+        mx *= scale_log2e;                                           // (the scale is positive)
+        const bool need = mx > m_run[t] + kRescaleStep;              // also the first visible key: m_run = -inf
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            const float alpha = need ? __builtin_amdgcn_exp2f(m_run[t] - mx) : 1.f;
+            m_run[t] = need ? mx : m_run[t];
+            l_run[t] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;
+        }
+        const float neg_m = (m_run[t] == -INFINITY) ? 0.f : -m_run[t];
         float psum = 0.f;
         float pv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            pv[i] = __builtin_amdgcn_exp2f(sv[i] - m_use);
+            pv[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], scale_log2e, neg_m));
             psum += pv[i];
         }
-        l_run[t] = l_run[t] * alpha + psum;      // per-lane partial sum; groups are combined at the end
-        m_run[t] = m_new;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt][t] *= alpha;
+        l_run[t] += psum;                        // per-lane partial sum; groups are combined at the end
         u32x4 wh, wl;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            uint16_t h0, l0, h1, l1;
-            split_bf16(pv[2 * i], h0, l0);
-            split_bf16(pv[2 * i + 1], h1, l1);
-            wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            uint32_t h2, l2;
+            split_bf16_x2(pv[2 * i], pv[2 * i + 1], h2, l2);
+            wh[i] = h2;
+            wl[i] = l2;
         }
         pf[t][0] = *reinterpret_cast<bf16x8 *>(&wh);
         pf[t][1] = *reinterpret_cast<bf16x8 *>(&wl);
@@ -228,7 +247,9 @@ __device__ __forceinline__ void chunk_update(const bf16x8 (&kf)[2][DH / 32], con
 }
 
 // A wavefront's own partial, straight from the accumulators: lane (col, g) holds dims dt*16 + 4g .. +4 of row
-// t*16 + col.  (Plain stores: the merge is a later launch whenever this is used.)
+// t*16 + col.  (Plain stores: the merge is a later launch whenever this is used.  Merging in this launch, by
+// the workgroup that completes a (head, 16-row group), was measured slower: the last arrivals queue a 75 KB
+// read of partials behind their own task, +6 us against a 5.9 us merge launch at full occupancy.)
 template <int DH>
 __device__ __forceinline__ void store_partial_direct(const AttnParams &P, int h, int row0, int rows_hi, int part,
                                                      const f32x4 (&o)[DH / 16][kRowTiles],
@@ -335,12 +356,15 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         m_run[t] = -INFINITY;
         l_run[t] = 0.f;
     }
+    // chunks that end at or below lim_full need no mask: the smallest limit among the task's rows (rows past
+    // rows_hi are never stored)
+    const int lim_full = min(kend, lim0 + inc * (row0 - row_ref));
     for (int c = c0; c < kend; c += CSTEP) {
         // the next chunk is requested while this one is computed
         bf16x8 kf_next[2][KS], vf_next[DT];
         const bool more = c + CSTEP < kend;           // (uniform)
         if (more) load_kv(c + CSTEP, kf_next, vf_next);
-        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e);
+        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e, __builtin_amdgcn_readfirstlane(c + 32 <= lim_full) != 0);
         if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -442,17 +466,19 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
     // this thread's pieces: where they come from in the chunk and which fragment slot they fill.
     // K chunk [32 keys][DH]: piece (key, dp) is lane (col, g) of fragment (kt, ks) with key = 8*(col/4) + col%4
     // + 4*kt, dp = 4*ks + g.  V chunk [DH][32 keys] (chunk-tiled cache): piece (d, kp) is lane (d%16, kp) of
-    // fragment dt = d/16.
+    // fragment dt = d/16.  Within its 16-lane group a piece sits at col ^ dp (K) or col ^ 4*kp (V): the threads
+    // that store one key's (one dim's) pieces would otherwise all hit the same four LDS banks (the counters
+    // showed 61 % of the LDS cycles of this kernel as bank conflicts); the reads undo the same exchange.
     int k_src[PPT], k_dst[PPT], v_src[PPT], v_dst[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const int j = tid + 256 * i;
         const int key = j / (DH / 8), dp = j % (DH / 8);
         k_src[i] = key * DH + dp * 8;
-        k_dst[i] = ((((key >> 2) & 1) * KS + (dp >> 2)) * 64) + (dp & 3) * 16 + (((key >> 3) << 2) | (key & 3));
+        k_dst[i] = ((((key >> 2) & 1) * KS + (dp >> 2)) * 64) + (dp & 3) * 16 + ((((key >> 3) << 2) | (key & 3)) ^ (dp & 15));
         const int d = j >> 2, kp = j & 3;
         v_src[i] = d * 32 + kp * 8;
-        v_dst[i] = (d >> 4) * 64 + kp * 16 + (d & 15);
+        v_dst[i] = (d >> 4) * 64 + kp * 16 + ((d & 15) ^ (4 * kp));
     }
     const int nch = (kend - kbeg + 31) >> 5;        // chunks of the range
     auto gload = [&](int i, bf16x8 (&kr)[PPT], bf16x8 (&vr)[PPT]) {
@@ -498,15 +524,16 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
     for (int dt = 0; dt < DT; ++dt) o[dt][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m_run[RT] = {-INFINITY}, l_run[RT] = {0.f};
 
+    const int lim_full = min(kend, lim0 + inc * row0);     // (see attn_task)
     auto compute = [&](int stage, int c) {
         bf16x8 kf[2][KS], vf[DT];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kst[stage][(kt * KS + ks) * 64 + lane];
+            for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kst[stage][(kt * KS + ks) * 64 + (lane & 48) + (col ^ ((4 * ks + g) & 15))];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = vst[stage][dt * 64 + lane];
-        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e);
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = vst[stage][dt * 64 + (lane & 48) + (col ^ (4 * g))];
+        chunk_update<DH>(kf, vf, qf, o, m_run, l_run, limit, c, kend, P.scale_log2e, __builtin_amdgcn_readfirstlane(c + 32 <= lim_full) != 0);
     };
 
     lstore(0, kr0, vr0);
@@ -532,11 +559,17 @@ __device__ void attn_task_lds(const AttnParams &P, int h, int grp0, int n_grp, c
 // fly from the fp32 QKV output, and the wavefront of row r appends that row's rotated key and its value to
 // the private cache.
 template <int DH, bool TREE>
-__device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
+__device__ void inflight_task_fused(const AttnParams &P, int h, int r, int r2) {
+    // r2: a second, later row of the same branch handled by this wavefront (-1: none).  Its keys are a
+    // superset of row r's, so every key is loaded and rotated once and scored against both rows: a branch of up
+    // to eight rows is one pass of the workgroup's four wavefronts, not two.
     constexpr int PER = DH / 64, HALF = DH / 2;
     const int lane = threadIdx.x & 63;
     if (r >= P.M) return;
-    const int b = r / P.T, j = r - b * P.T;
+    const bool two = r2 >= 0 && r2 < P.M;              // (uniform)
+    const int b = r / P.T;
+    const int jr[2] = {r - b * P.T, two ? r2 - b * P.T : r - b * P.T};
+    const int jmax = jr[1];
     const int HD = P.H * DH;
     const int sb = slot_of(P, b);
     if (P.slot != nullptr && P.slot[b] != sb && lane == 0 && h == 0) atomicOr(P.status, 2);   // slot out of range
@@ -564,43 +597,56 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
     const float *tb0 = P.rope + (size_t)(P.S + pl) * DH;
     // candidate trees (Section 2.2 "Tree Attention"; appendix): row j sees, among the rows of its branch, only
     // itself and its ancestors, and every row sits at the position of its depth
-    const unsigned long long anc = TREE ? P.row_anc[j] : ~0ull;
+    unsigned long long anc[2];
     auto depth_of = [&](int jj) { return TREE ? P.row_depth[jj] : jj; };
-    float qv[PER], o[PER];
+    float qv[2][PER], o[2][PER], m[2], l[2];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        qv[i] = rotated(P.qkv + (size_t)r * 3 * HD + h * DH, tb0 + (size_t)depth_of(j) * DH, i);
-        o[i] = 0.f;
+    for (int w = 0; w < 2; ++w) {
+        anc[w] = TREE ? P.row_anc[jr[w]] : ~0ull;
+        const int rw = b * P.T + jr[w];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            qv[w][i] = rotated(P.qkv + (size_t)rw * 3 * HD + h * DH, tb0 + (size_t)depth_of(jr[w]) * DH, i);
+            o[w][i] = 0.f;
+        }
+        m[w] = -INFINITY;
+        l[w] = 0.f;
     }
-    float m = -INFINITY, l = 0.f;
     constexpr int kB = 8;
-    for (int j0 = 0; j0 <= j; j0 += kB) {               // kB keys per pass: their loads overlap
-        float kk[kB][PER], vv[kB][PER], sc[kB];
+    for (int j0 = 0; j0 <= jmax; j0 += kB) {            // kB keys per pass: their loads overlap
+        float kk[kB][PER], vv[kB][PER], sc[2][kB];
 #pragma unroll
         for (int u = 0; u < kB; ++u) {
-            const int jj = min(j0 + u, j);
+            const int jj = min(j0 + u, jmax);
             const float *krow = P.qkv + (size_t)(b * P.T + jj) * 3 * HD + HD + h * DH;
-            sc[u] = 0.f;
+            sc[0][u] = sc[1][u] = 0.f;
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
                 kk[u][i] = rotated(krow, tb0 + (size_t)depth_of(jj) * DH, i);
                 vv[u][i] = krow[HD + lane * PER + i];
-                sc[u] = fmaf(qv[i], kk[u][i], sc[u]);
+                sc[0][u] = fmaf(qv[0][i], kk[u][i], sc[0][u]);
+                sc[1][u] = fmaf(qv[1][i], kk[u][i], sc[1][u]);
             }
         }
 #pragma unroll
         for (int u = 0; u < kB; ++u) {
-            if (j0 + u > j || (TREE && !((anc >> ((j0 + u) & 63)) & 1ull))) continue;    // (uniform over the wavefront)
-            const float s = wave_reduce_sum_dpp(sc[u]) * P.scale_log2e;   // (DPP: the keys of a row are a dependent chain)
-            const float m_new = fmaxf(m, s);
-            const float alpha = exp2f(m - m_new), p = exp2f(s - m_new);
-            l = l * alpha + p;
+            const int jj = j0 + u;
+            if (jj > jmax) continue;                                               // (uniform over the wavefront)
 #pragma unroll
-            for (int i = 0; i < PER; ++i) o[i] = o[i] * alpha + p * vv[u][i];
-            m = m_new;
-            if (j0 + u == j && store_kv) {              // this row's own key / value: append to the cache
+            for (int w = 0; w < 2; ++w) {
+                if (w == 1 && !two) continue;
+                if (jj > jr[w] || (TREE && !((anc[w] >> (jj & 63)) & 1ull))) continue;
+                const float s = wave_reduce_sum_dpp(sc[w][u]) * P.scale_log2e;   // (DPP: the keys of a row are a dependent chain)
+                const float m_new = fmaxf(m[w], s);
+                const float alpha = exp2f(m[w] - m_new), p = exp2f(s - m_new);
+                l[w] = l[w] * alpha + p;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) o[w][i] = o[w][i] * alpha + p * vv[u][i];
+                m[w] = m_new;
+            }
+            if ((jj == jr[0] || (two && jj == jr[1])) && store_kv) {   // a row's own key / value: append to the cache
                 const size_t head = (size_t)sb * P.H + h;
-                const int idx = pl + j;
+                const int idx = pl + jj;
 #pragma unroll
                 for (int i = 0; i < PER; ++i) {
                     const int d = lane * PER + i;
@@ -611,14 +657,19 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r) {
         }
     }
     const int part = P.ks_shared + P.ks_priv;
-    float *op = P.o_part + (((size_t)part * P.Mq + r) * P.H + h) * DH + lane * PER;
-    if (PER == 2) {
-        store2_agent(op, o[0], o[PER - 1]);
-    } else {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
+    for (int w = 0; w < 2; ++w) {
+        if (w == 1 && !two) continue;
+        const int rw = b * P.T + jr[w];
+        float *op = P.o_part + (((size_t)part * P.Mq + rw) * P.H + h) * DH + lane * PER;
+        if (PER == 2) {
+            store2_agent(op, o[w][0], o[w][PER - 1]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) store_agent(op + i, o[w][i]);
+        }
+        if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + rw) * P.H + h) * 2, m[w], l[w]);
     }
-    if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + r) * P.H + h) * 2, m, l);
 }
 
 // Combine the np partials of head h for the RB rows r0, r0 + rstep, ... by log-sum-exp and write the hi/lo bf16
@@ -726,9 +777,20 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     const int n_shared = P.wave_tasks ? P.H * P.ks_shared * P.n_quads : P.H * P.n_groups * P.ks_shared;
     int h;
     if (task < n_shared && P.wave_tasks) {
-        const int quad = task % P.n_quads;
-        const int ks = (task / P.n_quads) % P.ks_shared;
-        h = task / (P.n_quads * P.ks_shared);
+        // consecutive workgroup ids go round the 8 XCDs: the workgroups of one (head, key range) take ids
+        // 8 apart, so they run on one XCD at about the same time and the second reads the keys from its L2
+        int unit, quad;
+        const int paired = P.pair_xcd ? (P.H * P.ks_shared / 8) * 8 * P.n_quads : 0;
+        if (task < paired) {
+            const int rem = task % (8 * P.n_quads);
+            quad = rem >> 3;
+            unit = (task / (8 * P.n_quads)) * 8 + (rem & 7);
+        } else {
+            quad = (task - paired) % P.n_quads;
+            unit = paired / P.n_quads + (task - paired) / P.n_quads;
+        }
+        const int ks = unit % P.ks_shared;
+        h = unit / P.ks_shared;
         const int total = P.prefill_shared ? P.S + P.M : P.S;
         const int kbeg = ks * P.keys_per_range;
         const int kend = min(total, kbeg + P.keys_per_range);
@@ -770,7 +832,8 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
                                  pl, b * P.T, 0, P.ks_shared + ks, smem);
         }
         if (FUSED && ks == 0)
-            for (int r = row_first + wv; r < row_end; r += 4) inflight_task_fused<DH, TREE>(P, h, r);
+            for (int r = row_first + wv; r < row_end; r += 8)
+                inflight_task_fused<DH, TREE>(P, h, r, r + 4 < row_end ? r + 4 : -1);
     }
     if (FUSED && P.merge_in_launch) {
         // every task of head h has left its partial: the workgroup that arrives last merges the head's rows
@@ -798,22 +861,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *o_part, co
 // One row group (M <= 16): workgroup tasks whose four wavefronts interleave 32-key chunks: ranges of whole
 // 128-key rounds, about 512 workgroups.  Several row groups: workgroups that walk a range for up to four row
 // groups (attn_task_lds): ranges of an even number of 32-key chunks (chunks are processed in pairs), about 450
-// workgroups (flat between 256 and 640 in a sweep at the 7B / 13B shapes).  Private ranges are always of the first kind.
+// workgroups, fewer when the branch tasks are many.  Private ranges are always of the first kind.
 void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_keys, int prefill_shared,
                     int *ks_shared, int *keys_per_range, int *ks_priv, int *keys_per_range_priv) {
     const int n_groups = (M + 15) / 16;
     const bool lds_tasks = n_groups > 1;
-    const int unit = lds_tasks ? 64 : 128;
-    int units = (total_shared_keys + unit - 1) / unit;
-    if (units < 1) units = 1;
-    const int base_tasks = lds_tasks ? H * ((n_groups + 3) / 4) : H;
-    const int want = ((lds_tasks ? 448 : 512) + base_tasks - 1) / base_tasks;
-    int ks = want < units ? want : units;
-    if (ks < 1) ks = 1;
-    if (ks > 32) ks = 32;
-    const int per_units = (units + ks - 1) / ks;
-    *ks_shared = (units + per_units - 1) / per_units;
-    *keys_per_range = per_units * unit;
     if (prefill_shared || cap_priv_keys <= 0) {
         *ks_priv = 0;
         *keys_per_range_priv = 128;
@@ -830,6 +882,22 @@ void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_key
         *ks_priv = (rounds + per_rounds - 1) / per_rounds;
         *keys_per_range_priv = per_rounds * 128;
     }
+    const int unit = lds_tasks ? 64 : 128;
+    int units = (total_shared_keys + unit - 1) / unit;
+    if (units < 1) units = 1;
+    const int base_tasks = lds_tasks ? H * ((n_groups + 3) / 4) : H;
+    // workgroups of the shared pass.  Two fit on a CU (512 at once) and every one pays ~3.5 us of prologue and
+    // partial store, so when the branch tasks alone fill the chip the shared pass gets fewer, longer ranges
+    // (16 branches x 32 heads: 192 against 448 workgroups, -2 us; flat with 8 x 40)
+    const int branch_tasks = prefill_shared ? 0 : N * H * ((M / (N > 0 ? N : 1) + 15) / 16) * (*ks_priv > 0 ? *ks_priv : 1);
+    const int target = !lds_tasks ? 512 : branch_tasks >= 256 ? 192 : 448;
+    const int want = (target + base_tasks - 1) / base_tasks;
+    int ks = want < units ? want : units;
+    if (ks < 1) ks = 1;
+    if (ks > 32) ks = 32;
+    const int per_units = (units + ks - 1) / ks;
+    *ks_shared = (units + per_units - 1) / per_units;
+    *keys_per_range = per_units * unit;
 }
 
 int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
@@ -878,6 +946,7 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     // up to 16 rows the last workgroup of a head merges them in one pass; more rows would queue up behind its
     // four wavefronts, so they get a merge launch with a wavefront per (row, head)
     P.merge_in_launch = fused && !P.wave_tasks;
+    P.pair_xcd = P.n_quads > 1;
     const int np = fused ? a.ks_shared + a.ks_priv + 1 : a.ks_shared;   // prefill: shared partials only
     const bool tree = fused && a.row_depth != nullptr && a.row_anc != nullptr;
 #define SEEDV_ATTN(DHv, FUSEDv, TREEv) \

@@ -37,6 +37,18 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) 
     lo = f2bf(x - bf2f(hi));
 }
 
+// The same split for two values with the hardware conversion (v_cvt_pk_bf16_f32, round to nearest even):
+// half the instructions of the integer form.  hi2 / lo2 hold x0's part in the low half.
+__device__ __forceinline__ void split_bf16_x2(float x0, float x1, uint32_t &hi2, uint32_t &lo2) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const bf16x2_t h = __builtin_convertvector((f32x2_t){x0, x1}, bf16x2_t);
+    hi2 = *reinterpret_cast<const uint32_t *>(&h);
+    const bf16x2_t l = __builtin_convertvector(
+        (f32x2_t){x0 - __uint_as_float(hi2 << 16), x1 - __uint_as_float(hi2 & 0xFFFF0000u)}, bf16x2_t);
+    lo2 = *reinterpret_cast<const uint32_t *>(&l);
+}
+
 // bf16 V cache of one head, "chunk-tiled transposed": [cap/32][dh][32 keys].  The attention kernel reads V^T
 // fragments (16 dims x 32 keys, 16 bytes per lane); with this order the 32-key chunk it works on is one
 // contiguous dh*64-byte block, like the matching K chunk ([cap][dh] row-major), instead of dh pieces of 64
