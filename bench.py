@@ -368,7 +368,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c6"],
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c6", "c7", "c8"],
                     help="the headline workload (default c4: the largest verify batch)")
     ap.add_argument("--no-others", action="store_true", help="measure the headline workload only (profiling runs)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; "

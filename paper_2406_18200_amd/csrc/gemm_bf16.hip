@@ -124,17 +124,18 @@ __device__ __forceinline__ void store_act4(uint16_t *act, int row, int col0, int
 // takes rows w, w + kWaves, ...; a row of up to 512 sums is two 16-byte loads per lane, and the loads of eight
 // rows are in flight together (row after row would pay a memory latency each: twelve of them at 96 rows).
 template <int kWaves>
-__device__ __forceinline__ void rows_rinv(const GemmArgs &a, float *s_rinv, int w, int lane) {
+__device__ __forceinline__ void rows_rinv(const GemmArgs &a, float *s_rinv, int w, int lane, int r_lo, int r_hi) {
+    // rows r_lo .. r_hi - 1 (this workgroup's share); s_rinv is indexed from r_lo
     constexpr int kRowsAtOnce = 8;
     const int nt_in = a.NT_in;
     if (nt_in <= 512 && (nt_in & 3) == 0) {
-        for (int row0 = w; row0 < a.M; row0 += kRowsAtOnce * kWaves) {
+        for (int row0 = r_lo + w; row0 < r_hi; row0 += kRowsAtOnce * kWaves) {
             f32x4 v[kRowsAtOnce][2];
 #pragma unroll
             for (int r = 0; r < kRowsAtOnce; ++r)
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const int row = min(row0 + r * kWaves, a.M - 1), t = 4 * lane + 256 * i;
+                    const int row = min(row0 + r * kWaves, r_hi - 1), t = 4 * lane + 256 * i;
                     // (the load itself is unconditional, its value masked: a select on the value lets the compiler
                     // put the load under a branch, and a branch around a load drains the load queue at the join)
                     const u32x4 x = *reinterpret_cast<const u32x4 *>(a.ssq_in + (size_t)row * nt_in + (t < nt_in ? t : 0));
@@ -146,15 +147,15 @@ __device__ __forceinline__ void rows_rinv(const GemmArgs &a, float *s_rinv, int 
                 const f32x4 q = v[r][0] + v[r][1];
                 const float ssum = wave_reduce_sum_dpp((q[0] + q[1]) + (q[2] + q[3]));
                 // (no branch: every lane writes the one value; a row past the end repeats the last row's)
-                s_rinv[min(row0 + r * kWaves, a.M - 1)] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
+                s_rinv[min(row0 + r * kWaves, r_hi - 1) - r_lo] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
             }
         }
     } else {
-        for (int row = w; row < a.M; row += kWaves) {
+        for (int row = r_lo + w; row < r_hi; row += kWaves) {
             float ssum = 0.f;
             for (int t = lane; t < nt_in; t += 64) ssum += a.ssq_in[(size_t)row * nt_in + t];
             ssum = wave_reduce_sum(ssum);
-            if (lane == 0) s_rinv[row] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
+            if (lane == 0) s_rinv[row - r_lo] = 1.0f / sqrtf(ssum / (float)(nt_in * 16) + a.eps);
         }
     }
 }
@@ -177,7 +178,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
     const int nt_last = a.NT - 1;
     if (EPI != EPI_RESID && a.ssq_in != nullptr && !ssq_early) {
         // (after the k loop: a wait for these loads inside it would also wait for the weight prefetch)
-        rows_rinv<kWaves>(a, s_rinv, w, lane);
+        rows_rinv<kWaves>(a, s_rinv, w, lane, mh * TM * 16, min(a.M, (mh + 1) * TM * 16));
     }
     __syncthreads();                                      // s_rinv visible; xs no longer read
 
@@ -238,7 +239,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
             // and the next norm's gains)
             auto finish_one = [&](int nt, int row, int col, bool valid, const f32x4 &s, const f32x4 &x_in, const uint2 &gw) {
                 if (EPI == EPI_STORE) {
-                    const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
+                    const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[max(row - rbase, 0)] : 1.f;
                     if (valid) *reinterpret_cast<f32x4 *>(a.out + (size_t)row * a.ld_out + col) = s * sc;
                 } else {
                     float ss = 0.f;
@@ -363,7 +364,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
         const int row = rbase + tm * 16 + rlow;
         const bool valid = row < a.M;
         if (EPI == EPI_STORE) {
-            const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row] : 1.f;
+            const float sc = (valid && a.ssq_in != nullptr) ? s_rinv[row - rbase] : 1.f;
             if (valid) {
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
@@ -398,7 +399,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
             }
         } else {   // EPI_SWIGLU: tiles (nt0 + 2p, nt0 + 2p + 1) = (gate, up) of feature block nt0 / 2 + p
             if (valid) {
-                const float sc = s_rinv[row];
+                const float sc = s_rinv[row - rbase];
 #pragma unroll
                 for (int p = 0; p < TN / 2; ++p) {
                     if (nt0 + 2 * p + 1 > nt_last) continue;          // ragged last group: no such feature block
@@ -775,7 +776,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     for (int dd = 0; dd < D; ++dd) load_a(ring[dd], dd);
     // the input rows' 1/rms while the first weights are on their way (its loads come back after them, so the
     // wait inside is the prologue's wait)
-    if (EPI != EPI_RESID && a.ssq_in != nullptr) rows_rinv<kWaves>(a, s_rinv, w, lane);
+    if (EPI != EPI_RESID && a.ssq_in != nullptr) rows_rinv<kWaves>(a, s_rinv, w, lane, mt0 * 16, min(a.M, (mt0 + TM) * 16));
 #pragma unroll
     for (int dd = 0; dd < D; ++dd)
 #pragma unroll
@@ -1078,6 +1079,8 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
 // workgroup (WK), over all eight wavefronts when that gives one workgroup per CU without a split across
 // workgroups (no partials to exchange), else over four with two workgroups along K.
 // Row-split launches (65..128 rows): can be switched off for A/B measurements with SEED_GEMM_ROW_SPLIT=0.
+void gemm_bf16_pick_share(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
+                          int w8);
 static bool row_split_enabled() {
     static const bool on = [] {
         const char *e = getenv("SEED_GEMM_ROW_SPLIT");
@@ -1088,6 +1091,49 @@ static bool row_split_enabled() {
 
 void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
                     int w8) {
+    *sk = 1;
+    *wide = 0;
+    *ms = 1;
+    if (m_tiles > 8) {
+        // More than 128 rows: blocks of at most six row tiles, each run in the shape (and with the row shares)
+        // picked for a step of that many rows; no split of K (the shares alone are several workgroups per CU).
+        // All shares of a column group run on one XCD at about the same time (see wg_coords), so the weights
+        // still come from memory once.
+        if (NT % 4 == 0 && KT >= 64 && !w8) {
+            // Past 128 rows the launch is bound by MFMA issue and LDS reads, not by memory, so the big register
+            // tiles of the wide form: up to eight row tiles x four n-tiles per wavefront (a weight fragment feeds
+            // up to 16 MFMAs, an activation fragment read from LDS four); 4 x 2 wavefronts for wide outputs, 2 x 4
+            // (eight n-tiles per workgroup, K split four ways inside it) for narrow ones.  One such workgroup
+            // fills a CU, so the launch runs in whole rounds of 256: the row tiles per workgroup are chosen for
+            // the least rounds x (tiles + 2) (the 2: what a workgroup costs besides its MFMAs, in tiles).
+            // Measured at the 7B shapes, 384 rows: gate/up 166 us (three-tile shares of the 96-row shape) -> 147,
+            // QKV 109 -> 76.
+            const int swn = NT >= 600 ? 4 : 2, swk = 8 / swn;
+            const int groups = ((NT + 4 * swn - 1) / (4 * swn) + 7) / 8 * 8;
+            int best_tm = 0, best_cost = 1 << 30;
+            for (int t : {8, 6, 5, 4, 3}) {
+                const int shares = (m_tiles + t - 1) / t, tm = (m_tiles + shares - 1) / shares;   // tm <= t
+                if (tm < 3 || !wide_params(tm, 4, swn, swk).valid) continue;
+                const int cost = ((groups * shares + 255) / 256) * (tm + 2);
+                if (cost < best_cost) { best_cost = cost; best_tm = tm; }
+            }
+            if (best_tm > 0) {
+                *wn = swn; *wk = swk; *tn = 4; *wide = 1; *ms = (m_tiles + best_tm - 1) / best_tm;
+                return;
+            }
+        }
+        const int blocks = (m_tiles + 5) / 6;
+        int sk1, ms1;
+        gemm_bf16_pick_share(NT, KT, epi, (m_tiles + blocks - 1) / blocks, wn, wk, tn, &sk1, wide, &ms1, w8);
+        *ms = blocks * ms1;
+        return;
+    }
+    gemm_bf16_pick_share(NT, KT, epi, m_tiles, wn, wk, tn, sk, wide, ms, w8);
+}
+
+// (at most eight row tiles; splits them into two shares itself where that was measured faster)
+void gemm_bf16_pick_share(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
+                          int w8) {
     *sk = 1;
     *wide = 0;
     *ms = 1;

@@ -113,8 +113,8 @@ int validate_cfg(const seed_model_cfg *c) {
             set_error("bf16 path supports at most %d heads", kMaxHeads);
             return SEED_E_CAPACITY;
         }
-        if ((long)c->max_branches * c->max_rows_per_branch > 128) {
-            set_error("bf16 path supports at most 128 rows per step (max_branches * max_rows_per_branch)");
+        if ((long)c->max_branches * c->max_rows_per_branch > kMaxStepRows) {
+            set_error("bf16 path supports at most %d rows per step (max_branches * max_rows_per_branch)", kMaxStepRows);
             return SEED_E_CAPACITY;
         }
     } else {

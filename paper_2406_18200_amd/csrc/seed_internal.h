@@ -27,6 +27,10 @@ struct TreeInfo {                              // host-side expansion of a seed_
 };
 int expand_tree(const seed_tree *t, TreeInfo *out);   // validates; SEED_OK or an error code (message set)
 
+// Most rows (branches x rows per branch) of one bf16 step: 48 row tiles, run as row shares of three or four
+// tiles that share a weight pass.
+constexpr int kMaxStepRows = 768;
+
 // ---- accept.hip ------------------------------------------------------------------------------
 size_t accept_scratch_bytes(int max_rows);
 constexpr int kStaticAcceptRows = 4096;        // most target rows of a seed_accept_resample_static call

@@ -43,7 +43,7 @@ def test_workspace_size_and_config_validation(lib):
     n = lib.seed_verify_workspace_bytes(C.byref(big))
     assert 13.2e9 < n < 20e9            # packed 7B weights + caches + scratch
     for kw, code in ((dict(head_dim=96), -2), (dict(d_model=4100), -2), (dict(dtype_code=7), -5),
-                     (dict(max_branches=40, max_rows_per_branch=8), -3), (dict(n_layers=0), -1)):
+                     (dict(max_branches=100, max_rows_per_branch=8), -3), (dict(n_layers=0), -1)):
         c = B.ModelShape(32, 4096, 32, 128, 11008, 32000, "bf16").to_c()
         for k, v in kw.items():
             setattr(c, "dtype" if k == "dtype_code" else k, v)

@@ -73,6 +73,20 @@ def test_wide_projection_form_ragged_k(N, gamma, vocab):
     Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
 
 
+@pytest.mark.parametrize("N,gamma,vocab", [(24, 6, 20800),      # 144 rows: nine row tiles, two blocks of five
+                                           (64, 6, 10400),      # 384 rows: 24 tiles, four blocks x two shares
+                                           (50, 5, 20800),      # 250 rows: ragged last tile and last share
+                                           (96, 8, 2000)])      # 768 rows: the most a step takes
+def test_more_than_128_rows(N, gamma, vocab):
+    """Steps past 128 rows (batch sweep toward the matrix-core ridge): the projections run as row shares of
+    three or four tiles that reuse one pass over the weights, the shared attention segment as several
+    workgroups per key range.  Same small model as the wide-form cases; a sample of branches on the oracle
+    side (first, middle, last)."""
+    w = wl.get_workload("c4").scaled(n_layers=2, d_model=576, n_heads=9, head_dim=64, d_ff=4800, vocab=vocab,
+                                     N=N, gamma=gamma, S=100, R=20, seed=577 + gamma)
+    Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
+
+
 @pytest.mark.parametrize("N,gamma", [(16, 6), (3, 4)])
 def test_small_bf16_greedy_verification(N, gamma):
     """Greedy verification (accept while the draft equals the target's argmax) through the bf16 kernels; the

@@ -31,6 +31,13 @@ def test_w8_wide_shapes_ragged_k():
         Case(w, branches=[0, N // 2, N - 1]).run_oracle().run_gpu().compare()
 
 
+def test_w8_more_than_128_rows():
+    """250 rows (16 row tiles: blocks of six, each as two shares) with one-byte weights."""
+    w = wl.get_workload("c4").scaled(n_layers=2, d_model=576, n_heads=9, head_dim=64, d_ff=4800, vocab=10400, N=50,
+                                     gamma=5, S=100, R=20, seed=877, dtype="bf16w8")
+    Case(w, branches=[0, 25, 49]).run_oracle().run_gpu().compare()
+
+
 def test_w8_13b_widths_two_layers_and_error_of_the_format():
     """13B widths (d = 5120, F = 13824) at two layers, N = 8 x gamma = 5 over 4096 shared tokens.  Also prints how
     far the one-byte weights move the logits away from those of the bf16 weights they were made from."""

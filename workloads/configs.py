@@ -1,6 +1,7 @@
 """Workload shapes.  Names c1..c5 follow the order of the benchmark configurations:
 c1 tiny fp32 plumbing case, c2 draft-model batched decode, c3 7B verify (N=3, gamma=4, S=512),
-c4 wide 7B verify (N=16, gamma=6, S=2048, R=128), c5 13B verify (N=8, gamma=5, S=4096).
+c4 wide 7B verify (N=16, gamma=6, S=2048, R=128), c5 13B verify (N=8, gamma=5, S=4096); c6 state-evaluator
+shape, c7 / c8 the batch sweep past 128 rows.
 
 Notation: N branches (the paper's n), gamma draft tokens per branch (the paper's k), S shared-prefix
 tokens, R branch-private context tokens.
@@ -72,6 +73,12 @@ WORKLOADS = {
     # shared prefix at all, every branch brings its own context of a different length.
     "c6": Workload("c6", _7B, N=8, gamma=4, S=0, R=1024, temperature=0.7, q_kind="random", q_temp=1.0,
                    q_noise_std=0.0, kv_protocol="synthetic", seed=6001, R_min=384),
+    # Batch sweep past the matrix-core ridge (more branches than any search of the paper uses; the shapes of c4
+    # otherwise): 384 and 768 rows per step.
+    "c7": Workload("c7", _7B, N=64, gamma=6, S=2048, R=128, temperature=1.0, q_kind="random", q_temp=1.0,
+                   q_noise_std=0.0, kv_protocol="synthetic", seed=7001),
+    "c8": Workload("c8", _7B, N=128, gamma=6, S=2048, R=128, temperature=1.0, q_kind="random", q_temp=1.0,
+                   q_noise_std=0.0, kv_protocol="synthetic", seed=8001),
 }
 
 
