@@ -12,14 +12,15 @@ branches x 6 drafts = 96 rows, 2048-token shared prefix + 128 private tokens per
   step           -- whole-step figures: algorithmic bytes / time against the 8 TB/s HBM peak, useful flops
   roofline       -- the dominant kernel, the weight-streaming projection: algorithmic weight bytes per launch /
                     its launch duration (HIP events around every launch on the library's stream, in a pass of
-                    its own; the cost of an event pair, calibrated on an empty kernel, is subtracted and both
+                    its own; the cost of an event pair, calibrated on a kernel of known duration, is subtracted and both
                     figures are given), `achievable` = a pure streaming read measured in the same run
   other_workloads -- the same measurement for c5 (13B, 40 rows) and c3 (7B, 12 rows)
   draft_step     -- workload c2: gamma batched autoregressive steps of the small draft model (draft tokens/s)
   cpu_baseline   -- the float64 numpy oracle timed on this host's cores on a bounded sample of the headline
                     workload: three of its sixteen branches at full depth (branches are independent), nothing
                     extrapolated.
-`--workload X --no-others` measures X alone (the form the profiles under profiles/ are taken with).
+`--workload X --no-others` measures X alone (the form the profiles under profiles/ are taken with); c7 and c8
+(64 and 128 branches x 6 drafts: 384 and 768 rows) are the batch sweep past the matrix-core ridge.
 """
 import argparse
 import json
@@ -35,8 +36,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 # HBM bytes per projection launch from rocprofv3 --pmc runs of this file (FETCH_SIZE, WRITE_SIZE scaled by a
 # copy kernel of known size): the figures of the summaries under profiles/, not measured in this run.
-PROFILED_TRAFFIC_BYTES = {"c3": (106.3e6, "profiles/gemm_kernel_c3.md"),
-                          "c4": (135.7e6, "profiles/verify_step_c4_c5.md"),
+PROFILED_TRAFFIC_BYTES = {"c3": (106.4e6, "profiles/gemm_kernel_c3.md"),
+                          "c4": (132.5e6, "profiles/verify_step_c4_c5.md"),
                           "c5": (177.7e6, "profiles/verify_step_c4_c5.md"),
                           "c6": (112.0e6, "profiles/verify_step_c6.md")}
 
