@@ -68,6 +68,8 @@ struct AttnParams {
     int gpw, n_quads;         // row groups per such workgroup (<= 4), workgroups per (head, key range)
     int merge_in_launch;      // the last workgroup of a head merges its rows (few rows); else a second launch
     int pair_xcd;             // shared tasks of one (head, key range) on ids L, L+8, ...: one XCD, one L2
+    int solo_branch;          // branch tasks: a wavefront per (branch, head), four heads per workgroup,
+    int n_solo;               // ... which are the first n_solo workgroups of the launch
     int M, Mq, N, T, H;
     int S;                    // shared keys visible to every row (prefill: keys before the chunk)
     int prefill_shared;       // rows additionally see shared keys S .. S+j (their own chunk, causal)
@@ -279,7 +281,9 @@ __device__ __forceinline__ void store_partial_direct(const AttnParams &P, int h,
 // The four wavefronts of the workgroup interleave the 32-key chunks of the range and merge through LDS into one
 // partial (every barrier is reached by all four).  Used for every task of a step with one row group and for
 // the private segment; the shared segment of steps with several row groups goes through attn_task_lds.
-template <int DH, bool FUSED, bool TREE>
+// SOLO: the wavefront walks the whole range alone, chunk after chunk, and stores its own partial (no LDS, no
+// barrier): four such tasks, one per head, share a workgroup (branch tasks of steps with several row groups).
+template <int DH, bool FUSED, bool TREE, bool SOLO = false>
 __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, const uint16_t *kbase,
                           const uint16_t *vtbase, int cap, int kbeg, int kend, int lim0, int row_ref,
                           int inc, int part, char *smem) {
@@ -304,8 +308,8 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
         for (int dt = 0; dt < DT; ++dt)
             vf[dt] = *reinterpret_cast<const bf16x8 *>(vtbase + vt_offset(dt * 16 + col, c + 8 * g, DH));
     };
-    const int c0 = kbeg + 32 * wv;
-    constexpr int CSTEP = 128;
+    const int c0 = SOLO ? kbeg : kbeg + 32 * wv;
+    constexpr int CSTEP = SOLO ? 32 : 128;
     // Issue order: the private lengths (oldest, so they can be waited for alone), the K / V chunk, the raw q
     // values; straight-line code, or the compiler drains the load queue at the join of a branch.  Rows past the
     // task's rows are clamped to a valid row and masked later.
@@ -373,6 +377,10 @@ __device__ void attn_task(const AttnParams &P, int h, int row0, int rows_hi, con
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) vf[dt] = vf_next[dt];
         }
+    }
+    if (SOLO) {
+        store_partial_direct<DH>(P, h, row0, rows_hi, part, o, m_run, l_run);
+        return;
     }
     // ---- merge the four wavefronts' partial results through LDS, write ONE partial per workgroup ----
     // (fixed order: deterministic; cuts the partial traffic to global memory fourfold)
@@ -672,6 +680,119 @@ __device__ void inflight_task_fused(const AttnParams &P, int h, int r, int r2) {
     }
 }
 
+// The in-flight segment of ALL rows (at most eight) of branch b, head h in ONE wavefront (branch tasks that give a
+// wavefront a whole head).  Row after row on the whole wavefront would be a chain of 21 dependent 64-lane
+// reductions for six rows (measured 9.4 us); here the rotated q and k rows go through this wavefront's corner of
+// LDS (rows padded by four floats: eight rows on distinct banks), lane (r, u) forms the one score q_r . k_u, a
+// row's softmax is three xor-shuffles inside its eight lanes, and lanes go back to owning dims for P . V with the
+// weights read lane by lane.  Also appends the rows' rotated keys and their values to the private cache.
+template <int DH, bool TREE>
+__device__ void inflight_solo(const AttnParams &P, int h, int b, float *lds) {
+    constexpr int PER = DH / 64, HALF = DH / 2, R = 8, LD = DH + 4;
+    const int lane = threadIdx.x & 63;
+    const int n = P.T;                                   // 1 .. R rows
+    const int HD = P.H * DH;
+    const int sb = slot_of(P, b);
+    if (P.slot != nullptr && P.slot[b] != sb && lane == 0 && h == 0) atomicOr(P.status, 2);   // slot out of range
+    int pl = P.private_len[sb];
+    bool store_kv = true;
+    if (pl < 0 || pl > P.max_private) {              // capacity overflow: drop the append, flag it
+        if (lane == 0 && h == 0) atomicOr(P.status, 1);
+        pl = min(max(pl, 0), P.max_private);
+        store_kv = false;
+    }
+    const int r = lane >> 3, u = lane & 7;              // this lane's (row, key) pair
+    const unsigned long long anc = TREE ? P.row_anc[min(r, n - 1)] : ~0ull;
+    int dl[PER];
+    bool upper[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int d = lane * PER + i;
+        dl[i] = d & (HALF - 1);
+        upper[i] = d >= HALF;
+    }
+    auto rotated = [&](const float *vec, const float *tb, int i) {
+        const int d = lane * PER + i;
+        const float x = vec[d], y = vec[d ^ HALF], c = tb[2 * dl[i]], s_ = tb[2 * dl[i] + 1];
+        return upper[i] ? x * c + y * s_ : x * c - y * s_;
+    };
+    const float *tb0 = P.rope + (size_t)(P.S + pl) * DH;
+    float kr[R][PER], vv[R][PER];
+    float *Qs = lds, *Ks = lds + R * LD;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int jj = min(j, n - 1);                    // (rows past the last repeat it; masked below)
+        const float *row = P.qkv + (size_t)(b * P.T + jj) * 3 * HD + h * DH;
+        const float *tb = tb0 + (size_t)(TREE ? P.row_depth[jj] : jj) * DH;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            Qs[j * LD + lane * PER + i] = rotated(row, tb, i);
+            kr[j][i] = rotated(row + HD, tb, i);
+            vv[j][i] = row[2 * HD + lane * PER + i];
+            Ks[j * LD + lane * PER + i] = kr[j][i];
+        }
+    }
+    // (LDS operations of one wavefront execute in program order: the reads below see the rows)
+    float sc = 0.f;
+#pragma unroll
+    for (int d4 = 0; d4 < DH / 4; ++d4) {
+        const f32x4 qa = *reinterpret_cast<const f32x4 *>(Qs + r * LD + 4 * d4);
+        const f32x4 kb = *reinterpret_cast<const f32x4 *>(Ks + u * LD + 4 * d4);
+        sc = fmaf(qa[0], kb[0], sc);
+        sc = fmaf(qa[1], kb[1], sc);
+        sc = fmaf(qa[2], kb[2], sc);
+        sc = fmaf(qa[3], kb[3], sc);
+    }
+    // row r sees rows 0 .. r of its branch (candidate trees: itself and its ancestors)
+    const bool vis = r < n && u <= r && ((anc >> u) & 1ull);
+    const float s = vis ? sc * P.scale_log2e : -INFINITY;
+    float m = s;
+    m = fmaxf(m, __shfl_xor(m, 1));
+    m = fmaxf(m, __shfl_xor(m, 2));
+    m = fmaxf(m, __shfl_xor(m, 4));
+    const float p = __builtin_amdgcn_exp2f(s - (m == -INFINITY ? 0.f : m));      // 0 where masked
+    float l = p;
+    l += __shfl_xor(l, 1);
+    l += __shfl_xor(l, 2);
+    l += __shfl_xor(l, 4);
+    const int pbits = __builtin_bit_cast(int, p), mbits = __builtin_bit_cast(int, m), lbits = __builtin_bit_cast(int, l);
+    const int part = P.ks_shared + P.ks_priv;
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        if (rr >= n) break;                              // (uniform)
+        float o[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) o[i] = 0.f;
+#pragma unroll
+        for (int uu = 0; uu <= rr; ++uu) {
+            const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(pbits, rr * 8 + uu));
+#pragma unroll
+            for (int i = 0; i < PER; ++i) o[i] = fmaf(w, vv[uu][i], o[i]);
+        }
+        const int rw = b * P.T + rr;
+        float *op = P.o_part + (((size_t)part * P.Mq + rw) * P.H + h) * DH + lane * PER;
+        if (PER == 2) {
+            store2_agent(op, o[0], o[PER - 1]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) store_agent(op + i, o[i]);
+        }
+        const float mr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(mbits, rr * 8));
+        const float lr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(lbits, rr * 8));
+        if (lane == 0) store2_agent(P.ml_part + (((size_t)part * P.Mq + rw) * P.H + h) * 2, mr, lr);
+        if (store_kv) {                                  // the row's own key / value: append to the cache
+            const size_t head = (size_t)sb * P.H + h;
+            const int idx = pl + rr;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int d = lane * PER + i;
+                P.k_priv_w[(head * P.cap_p + idx) * DH + d] = f2bf(kr[rr][i]);
+                P.vt_priv_w[head * DH * P.cap_p + vt_offset(d, idx, DH)] = f2bf(vv[rr][i]);
+            }
+        }
+    }
+}
+
 // Combine the np partials of head h for the RB rows r0, r0 + rstep, ... by log-sum-exp and write the hi/lo bf16
 // activation (fragment-packed, K = H*DH) that feeds the O projection; rows >= M of the tile are zero.  One
 // wavefront; the loads of all RB rows and of up to eight partials are issued before the first is used (a
@@ -770,8 +891,33 @@ __global__ __launch_bounds__(256, 2) void attn_partial_kernel(AttnParams P) {
     constexpr int kMergeBytes = 2 * 4 * 16 * RT * 4 + 4 * 16 * RT * (DH + 4) * 4;
     constexpr int kStageBytes = 2 * (2 * (DH / 32) + DH / 16) * 64 * 16;
     __shared__ __attribute__((aligned(16))) char smem[kMergeBytes > kStageBytes ? kMergeBytes : kStageBytes];
-    const int task = blockIdx.x;
+    const int task = (int)blockIdx.x - P.n_solo;          // (n_solo = 0 unless the branch tasks go first)
     const int wv = threadIdx.x >> 6;
+    // steps with several row groups and short private contexts: a branch task is one WAVEFRONT -- the private
+    // keys of (branch, head) walked chunk by chunk, then all in-flight rows of that head -- and a workgroup holds
+    // four heads.  These workgroups come first in launch order and the shared pass gets the remaining slots of
+    // the chip, so that every task of the launch is resident from the start: the launch is bound by the sum of
+    // workgroup latencies over the slots (two workgroups per CU), not by throughput.
+    if (FUSED && P.solo_branch && blockIdx.x < P.n_solo) {
+        const int nr = max(P.ks_priv, 1);
+        const int hq_n = (P.H + 3) >> 2;
+        const int ks = (int)blockIdx.x % nr;
+        const int hq = ((int)blockIdx.x / nr) % hq_n;
+        const int b = (int)blockIdx.x / (nr * hq_n);
+        const int h = hq * 4 + wv;
+        if (h >= P.H) return;                              // (uniform over the wavefront; no barriers below)
+        if (P.ks_priv > 0) {
+            const int pl = clamped_private_len(P, b);
+            const int kbeg = ks * P.keys_per_range_priv;
+            const int kend = min(pl, kbeg + P.keys_per_range_priv);
+            const size_t sb = (size_t)slot_of(P, b);
+            attn_task<DH, FUSED, TREE, true>(P, h, b * P.T, (b + 1) * P.T, P.k_priv + (sb * P.H + h) * P.cap_p * DH,
+                                             P.vt_priv + (sb * P.H + h) * DH * P.cap_p, P.cap_p, kbeg, max(kbeg, kend),
+                                             pl, b * P.T, 0, P.ks_shared + ks, smem);
+        }
+        if (ks == 0) inflight_solo<DH, TREE>(P, h, b, reinterpret_cast<float *>(smem) + wv * (2 * 8 * (DH + 4)));
+        return;                                            // (the merge is a launch of its own in this mode)
+    }
     // shared segment: (head, row group, key range) tasks, or, when the step has several row groups,
     // (head, key range, up to four row groups) tasks that share the key range through LDS
     const int n_shared = P.wave_tasks ? P.H * P.ks_shared * P.n_quads : P.H * P.n_groups * P.ks_shared;
@@ -889,10 +1035,16 @@ void attn_bf16_plan(int M, int H, int N, int total_shared_keys, int cap_priv_key
     // workgroups of the shared pass.  Two fit on a CU (512 at once) and every one pays ~3.5 us of prologue and
     // partial store, so when the branch tasks alone fill the chip the shared pass gets fewer, longer ranges
     // (16 branches x 32 heads: 192 against 448 workgroups, -2 us; flat with 8 x 40)
-    const int branch_tasks = prefill_shared ? 0 : N * H * ((M / (N > 0 ? N : 1) + 15) / 16) * (*ks_priv > 0 ? *ks_priv : 1);
-    const int target = !lds_tasks ? 512 : branch_tasks >= 256 ? 192 : 448;
-    const int want = (target + base_tasks - 1) / base_tasks;
+    const int T = M / (N > 0 ? N : 1);
+    const bool solo = lds_tasks && !prefill_shared && T <= 8 && *keys_per_range_priv <= 256;   // (as in the launcher)
+    const int branch_tasks = prefill_shared ? 0 : (solo ? N * ((H + 3) / 4) : N * H * ((T + 15) / 16)) * (*ks_priv > 0 ? *ks_priv : 1);
+    // (branch tasks of one wavefront per head go first and the shared pass takes the slots they leave, so that
+    // the whole launch is resident at once)
+    const int left = 512 - branch_tasks > 192 ? 512 - branch_tasks : 192;
+    const int target = !lds_tasks ? 512 : solo ? left : branch_tasks >= 256 ? 192 : 448;
+    const int want = solo ? (target / base_tasks > 0 ? target / base_tasks : 1) : (target + base_tasks - 1) / base_tasks;
     int ks = want < units ? want : units;
+    if (lds_tasks && ks < (units + 15) / 16) ks = (units + 15) / 16;    // at most 32 chunks per workgroup
     if (ks < 1) ks = 1;
     if (ks > 32) ks = 32;
     const int per_units = (units + ks - 1) / ks;
@@ -937,8 +1089,11 @@ int launch_attn_bf16(const AttnBf16Args &a, hipStream_t st) {
     P.groups_priv = (a.T + 16 * rt - 1) / (16 * rt);
     P.scale_log2e = 1.4426950408889634f / sqrtf((float)a.dh);
     const bool fused = !a.prefill_shared;
-    const int blocks = (P.wave_tasks ? a.H * a.ks_shared * P.n_quads : a.H * P.n_groups * a.ks_shared) +
-                       (fused ? a.N * a.H * P.groups_priv * (a.ks_priv > 0 ? a.ks_priv : 1) : 0);
+    P.solo_branch = fused && P.wave_tasks && a.T <= 8 && a.keys_per_range_priv <= 256;
+    const int branch_units = P.solo_branch ? a.N * ((a.H + 3) / 4) : a.N * a.H * P.groups_priv;
+    const int n_branch = fused ? branch_units * (a.ks_priv > 0 ? a.ks_priv : 1) : 0;
+    P.n_solo = P.solo_branch ? n_branch : 0;
+    const int blocks = (P.wave_tasks ? a.H * a.ks_shared * P.n_quads : a.H * P.n_groups * a.ks_shared) + n_branch;
     if (a.dh != 128 && a.dh != 64) {
         set_error("bf16 attention supports head_dim 64 or 128, got %d", a.dh);
         return SEED_E_SHAPE;
