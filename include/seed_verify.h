@@ -63,10 +63,10 @@ typedef struct seed_ctx seed_ctx; /* opaque; one per model instance */
 
 typedef struct {
     int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
-    int32_t dtype;      /* SEED_DTYPE_F32 or SEED_DTYPE_BF16 */
+    int32_t dtype;      /* SEED_DTYPE_F32, SEED_DTYPE_BF16 or SEED_DTYPE_BF16_W8 */
     float rms_eps;      /* RMSNorm epsilon                    */
     float rope_theta;   /* rotary base; rotate-half pairing (i, i + head_dim/2) */
-    int32_t max_branches;        /* largest N of any step                                  */
+    int32_t max_branches;        /* largest N of any step (bf16: N * T <= 768 rows per step)  */
     int32_t max_rows_per_branch; /* largest T (= gamma, or gamma+1 with a bonus row)        */
     int32_t max_shared;          /* capacity of the shared-prefix KV cache, tokens          */
     int32_t max_private;         /* capacity of each branch's private context, tokens       */
@@ -194,8 +194,8 @@ typedef struct {
     int32_t *private_len;     /* [N] in (out if accept / COMMIT_ALL)              */
     float *logits_out;        /* [N][T][V] out, may be NULL                       */
     const seed_accept_args *accept; /* host pointer, may be NULL                  */
-    const int32_t *branch_slot; /* [N] device, may be NULL: see below              */
-    const seed_tree *tree;      /* HOST, may be NULL: see below                    */
+    const int32_t *branch_slot; /* [N] device, may be NULL: see above              */
+    const seed_tree *tree;      /* HOST, may be NULL: see above                    */
 } seed_step_args;
 
 /*
