@@ -518,6 +518,136 @@ __global__ __launch_bounds__(kBlock) void softmax_sample_kernel(
     }
 }
 
+// The same over the whole chip: grid (rows, slices), behind row_stats_kernel.  One workgroup per row is a chain of
+// memory round trips on 32000 logits (16 us for eight rows); here a workgroup combines the row's slice statistics
+// itself (the same arithmetic in every workgroup, so all agree on max and sum), writes its slice of q and leaves
+// the slice's fixed-point weight sum; the workgroup that arrives last for a row (arrival counter, zero on entry and
+// left zero) picks the slice that holds the target from those integer sums and scans it.  Same token as the
+// one-workgroup form: the sums are integers.
+__global__ __launch_bounds__(256) void softmax_sample_slices_kernel(
+        const float *logits, int V, int per, float temperature, int greedy, const float *u, float *q_out,
+        int64_t q_stride, int32_t *tok_out, int64_t tok_stride, int32_t *private_len, const SliceStats *stats,
+        unsigned long long *slice_sums, int *counters, const int32_t *slot, int n_slots) {
+    __shared__ unsigned long long s_tot[4];
+    __shared__ int s_last, s_tok;
+    const int row = blockIdx.x, sl = blockIdx.y, n_slices = gridDim.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float *src = logits + (size_t)row * V;
+    TargetRow r{src, 1, 0.f, 1.f, 1.f / temperature};
+    // the row's statistics from its slices (as in softmax_sample_kernel)
+    float lm = -INFINITY, ls = 0.f;
+    int li = 0x7fffffff;
+    if (lane < n_slices) {
+        const SliceStats e = stats[(size_t)row * n_slices + lane];
+        lm = e.mx;
+        li = e.idx;
+        ls = e.sum;
+    }
+    float mv = lm;
+    int mi = li;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(mv, off);
+        const int oi = __shfl_xor(mi, off);
+        if (ov > mv || (ov == mv && oi < mi)) { mv = ov; mi = oi; }
+    }
+    ls = lane < n_slices ? ls * exp_scaled(lm, mv, r.inv_temp) : 0.f;
+    float tot = 0.f;
+    for (int i = 0; i < n_slices; ++i) tot += __shfl(ls, i);          // fixed order
+    r.mx = mv;
+    r.inv_sum = 1.0f / tot;
+    // this slice: q values out, fixed-point weights summed
+    const int base = sl * per, end = min(V, base + per);
+    float *dst = q_out != nullptr ? q_out + (size_t)row * q_stride : nullptr;
+    unsigned long long local = 0;
+#pragma unroll 4
+    for (int v = base + threadIdx.x; v < end; v += 256) {
+        const float p = r.p(v);
+        if (dst != nullptr) dst[v] = p;
+        local += to_fixed(p);
+    }
+    local = wave_sum_u64(local);
+    if (lane == 0) s_tot[wave] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long sum = (s_tot[0] + s_tot[1]) + (s_tot[2] + s_tot[3]);
+        __hip_atomic_store(slice_sums + (size_t)row * n_slices + sl, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0);
+        const int old = __hip_atomic_fetch_add(counters + row, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = old == n_slices - 1;
+        if (s_last) __hip_atomic_store(counters + row, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // re-arm
+        s_tok = -1;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    int tok = mi;                                         // greedy: the argmax (lowest index on ties)
+    if (!greedy) {
+        // slice sums of the row: lane i takes slice i
+        unsigned long long mine = 0;
+        if (lane < n_slices)
+            mine = __hip_atomic_load(slice_sums + (size_t)row * n_slices + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned long long o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        const unsigned long long Z = __shfl(incl, 63);
+        if (Z != 0) {
+            const unsigned long long m24 = (unsigned long long)(__fmul_rn(u[row], 16777216.0f));
+            const unsigned long long t = (m24 * Z) >> 24;
+            const unsigned long long hit = __ballot(incl > t);           // (t < Z: some lane passes)
+            const int target = __ffsll((long long)hit) - 1;
+            unsigned long long run = __shfl(incl, target) - __shfl(mine, target);
+            // wavefront 0 walks the target slice in blocks of 2048 tokens, 32 consecutive tokens per lane (as in
+            // draw_fixed; a slice of the draft shapes is one block)
+            const int tb = target * per, te = min(V, tb + per);
+            constexpr int kPerLane = 32;
+            if (wave == 0) {
+                for (int blk = tb; blk < te; blk += 64 * kPerLane) {
+                    const int v0 = blk + lane * kPerLane;
+                    unsigned long long k[kPerLane];
+                    unsigned long long acc = 0;
+#pragma unroll
+                    for (int e = 0; e < kPerLane; ++e) {
+                        const int v = v0 + e;
+                        k[e] = v < te ? to_fixed(r.p(min(v, te - 1))) : 0ull;
+                        acc += k[e];
+                    }
+                    unsigned long long inc2 = acc;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const unsigned long long o = __shfl_up(inc2, off);
+                        if (lane >= off) inc2 += o;
+                    }
+                    const unsigned long long h2 = __ballot(run + inc2 > t);
+                    if (h2) {
+                        const int srcl = __ffsll((long long)h2) - 1;
+                        if (lane == srcl) {
+                            unsigned long long c = run + inc2 - acc;
+                            int tk = v0;
+#pragma unroll
+                            for (int e = 0; e < kPerLane; ++e) {
+                                c += k[e];
+                                if (c > t) { tk = v0 + e; break; }
+                            }
+                            s_tok = tk;
+                        }
+                        break;
+                    }
+                    run += __shfl(inc2, 63);
+                }
+            }
+        }
+        __syncthreads();
+        tok = s_tok;
+    }
+    if (threadIdx.x == 0) {
+        tok_out[(size_t)row * tok_stride] = tok;
+        if (private_len != nullptr) private_len[slot != nullptr ? min(max(slot[row], 0), n_slots - 1) : row] += 1;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Candidate trees (Section 2.2 "Tree Attention"; Section 4.1: k_config; appendix "Details of Tree Attention").
 // Nodes are numbered in level order, node 0 the root (the pending token); at position j every node of position
@@ -818,7 +948,8 @@ static int stats_slices(int rows, int vocab, int *per) {
     return (vocab + *per - 1) / *per;
 }
 
-size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices * sizeof(SliceStats); }
+// (slice statistics, then -- draft side -- the slices' 64-bit weight sums)
+size_t accept_scratch_bytes(int max_rows) { return (size_t)max_rows * kMaxSlices * (sizeof(SliceStats) + 8); }
 
 // The row statistics of the entry point that allocates nothing (seed_accept_resample_static): one copy of this
 // array per GPU, held until the process ends.  1 MiB: kStaticAcceptRows rows x 16 slices x 16 bytes.
@@ -897,20 +1028,27 @@ int launch_accept_tree(const seed_accept_args &a, const TreeInfo &ti, void *scra
 }
 
 // scratch (optional, accept_scratch_bytes(n_rows) bytes, rows contiguous: logits_stride == vocab): as in
-// launch_accept.
+// launch_accept, followed by the rows' slice sums.  counters (optional, one int per row, zero on entry, left zero):
+// with scratch and counters the draw runs over (rows, slices) workgroups, else one workgroup per row.
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
-                          const int32_t *branch_slot, int n_slots, hipStream_t st) {
+                          int *counters, const int32_t *branch_slot, int n_slots, hipStream_t st) {
     if (n_rows == 0) return SEED_OK;
     SliceStats *stats = nullptr;
-    int n_slices = 0;
+    int n_slices = 0, per = 0;
     if (scratch != nullptr && logits_stride == vocab) {
-        int per;
         n_slices = stats_slices(n_rows, vocab, &per);
         stats = (SliceStats *)scratch;
         hipLaunchKernelGGL(row_stats_kernel, dim3(n_rows, n_slices), dim3(256), 0, st, logits, vocab, per,
                            1.0f / temperature, stats);
+    }
+    if (stats != nullptr && counters != nullptr) {
+        unsigned long long *sums = (unsigned long long *)((char *)scratch + (size_t)n_rows * kMaxSlices * sizeof(SliceStats));
+        hipLaunchKernelGGL(softmax_sample_slices_kernel, dim3(n_rows, n_slices), dim3(256), 0, st, logits, vocab, per,
+                           temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, stats, sums,
+                           counters, branch_slot, n_slots);
+        return hip_fail(hipGetLastError(), "softmax_sample launch");
     }
     hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_rows), dim3(kBlock), 0, st, logits, logits_stride,
                        temperature, greedy, u, q_out, q_stride, tok_out, tok_stride, private_len, vocab, stats,

@@ -76,7 +76,7 @@ struct Layout {
     // KV caches (per-layer strides)
     size_t ks, vs, kp, vp, ks_stride, kp_stride;
     // activations
-    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, o_part, ml_part, logits, acc_stats, status,
+    size_t x, act_d, act_hd, act_f, part, qkv, rinv, ssq, counters, attn_counters, rope, q, o_part, ml_part, logits, acc_stats, draft_counters, status,
         tree_depth, tree_anc, commit_rows;
     int n_pos;
     size_t part_floats;
@@ -199,6 +199,7 @@ Layout make_layout(const seed_model_cfg &c) {
     L.ml_part = take(bf ? (size_t)kMaxAttnSlots * L.Mq_cap * H * 2 * 4 : 256);
     L.logits = take((size_t)L.M_cap * V * 4);
     L.acc_stats = take(accept_scratch_bytes(L.M_cap));
+    L.draft_counters = take((size_t)L.M_cap * 4);
     L.status = take(256);
     L.tree_depth = take(kMaxTreeNodes * 4);
     L.tree_anc = take(kMaxTreeNodes * 8);
@@ -827,8 +828,8 @@ int seed_draft_step(seed_ctx *c, const seed_draft_args *a) {
     int rc = run_forward(c, N, 1, a->shared_len, 0, a->row_tok, a->private_len, a->branch_slot, nullptr, logits);
     if (rc) return rc;
     return launch_softmax_sample(logits, g.vocab, a->temperature, greedy, a->u, a->q_out, a->q_stride, a->tok_out,
-                                 a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats), a->branch_slot,
-                                 g.max_branches, c->stream);
+                                 a->tok_stride, a->private_len, N, g.vocab, at(c, c->L.acc_stats),
+                                 (int *)at(c, c->L.draft_counters), a->branch_slot, g.max_branches, c->stream);
 }
 
 int seed_kv_load(seed_ctx *c, int32_t layer, const void *k_shared, const void *v_shared, int32_t shared_len,

@@ -44,7 +44,7 @@ int launch_accept_tree(const seed_accept_args &a, const TreeInfo &t, void *scrat
 int launch_softmax_sample(const float *logits, int64_t logits_stride, float temperature, int greedy,
                           const float *u, float *q_out, int64_t q_stride, int32_t *tok_out,
                           int64_t tok_stride, int32_t *private_len, int n_rows, int vocab, void *scratch,
-                          const int32_t *branch_slot, int n_slots, hipStream_t st);   // scratch, slot may be NULL
+                          int *counters, const int32_t *branch_slot, int n_slots, hipStream_t st);   // scratch, counters, slot may be NULL
 int launch_sample_probs(const float *probs, int64_t row_stride, const float *u, int32_t *tok_out,
                         int n_rows, int vocab, hipStream_t st);
 
