@@ -16,6 +16,7 @@ branches x 6 drafts = 96 rows, 2048-token shared prefix + 128 private tokens per
                     figures are given), `achievable` = a pure streaming read measured in the same run
   other_workloads -- the same measurement for c5 (13B, 40 rows) and c3 (7B, 12 rows)
   draft_step     -- workload c2: gamma batched autoregressive steps of the small draft model (draft tokens/s)
+  batch_sweep    -- c7 / c8: the headline shapes with 64 / 128 branches (384 / 768 rows), useful MFMA fraction
   cpu_baseline   -- the float64 numpy oracle timed on this host's cores on a bounded sample of the headline
                     workload: three of its sixteen branches at full depth (branches are independent), nothing
                     extrapolated.
@@ -428,6 +429,17 @@ def main():
             others[name] = r
         out["other_workloads"] = others
         out["draft_step"] = measure_draft(args, dev)
+        # batch sweep past 128 rows (64 and 128 branches): where the step turns from memory- to MFMA-bound
+        if w.name == "c4" and not args.layers:
+            sweep = {}
+            few = argparse.Namespace(**{**vars(args), "steps": max(5, args.steps // 5), "warmup": max(2, args.warmup // 5)})
+            for name in ("c7", "c8"):
+                r = measure_verify(wl.get_workload(name), few, dev)
+                sweep[name] = {"rows": r["config"]["global_batch"], "value": r["value"], "unit": "tokens/s",
+                               "ms_per_step": r["ms_per_step"], "steps": few.steps, "warmup": few.warmup,
+                               "useful_mfma_frac": r["step"]["mfma_frac"], "useful_tflops": r["step"]["useful_tflops"],
+                               "config": r["config"]}
+            out["batch_sweep"] = sweep
     if args.w8:
         out["fp8_weights"] = {}
         for name in ("c3", "c5"):
