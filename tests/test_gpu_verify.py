@@ -25,7 +25,10 @@ def test_c1_greedy():
 @pytest.mark.parametrize("N,gamma,S,R", [(3, 4, 100, 0), (5, 3, 70, 9), (16, 6, 257, 40), (1, 1, 33, 0),
                                          (2, 5, 1100, 300),   # <= 16 rows, 13 partials: in-launch merge in passes
                                          (1, 40, 64, 20),     # one branch of 40 rows: two row groups per branch
-                                         (3, 7, 200, 150)])   # 21 rows (two row tiles), two private key ranges
+                                         (3, 7, 200, 150),    # 21 rows (two row tiles), two private key ranges
+                                         (20, 1, 70, 9),      # 20 branches of ONE row: a head's in-flight segment is a single score
+                                         (3, 8, 100, 40),     # eight rows per branch: the most a wavefront-per-head branch task takes
+                                         (2, 9, 100, 40)])    # nine rows per branch: branch tasks in the workgroup-per-head form
 def test_small_bf16_synthetic_kv(N, gamma, S, R):
     """Small bf16 model (2 layers, d=256, 4 heads of 64): several MFMA tiles, ragged tails in rows and keys,
     and every shape of the attention launch (one / two row tiles, merge inside / after the launch, several
