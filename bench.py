@@ -52,7 +52,8 @@ def algorithmic_bytes(w):
     """Bytes one verify step must move: every weight once, the KV context once, logits and q once."""
     m = w.model
     es = 4 if m.dtype == "fp32" else 2
-    weights = m.params * (1 if m.dtype == "bf16w8" else es)      # one-byte weights: e4m3 codes (+ a scale per row)
+    # one-byte weights: e4m3 codes (+ a scale per row); four-bit weights: MXFP4 codes + a scale byte per 32
+    weights = int(m.params * {"bf16w8": 1.0, "bf16w4": 0.53125}.get(m.dtype, es))
     kv_tok = 2 * m.n_heads * m.head_dim * es * m.n_layers
     kv = (w.S + int(wl_private_lens(w).sum())) * kv_tok
     M = w.N * w.gamma
@@ -378,6 +379,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--w8", action="store_true", help="also time c3 and c5 with the projection matrices as one-byte "
                     "e4m3 codes + per-row scales (context dtype bf16w8): reported under fp8_weights, never as the headline")
+    ap.add_argument("--w4", action="store_true", help="the same with MXFP4 weights (E2M1 codes + a power-of-two scale per "
+                    "32 inputs, context dtype bf16w4): reported under fp4_weights")
     ap.add_argument("--greedy", action="store_true")
     ap.add_argument("--copy-probe-mb", type=int, default=0, help="also launch a plain device-to-device copy "
                     "of this many MiB (three times) before the timed region: the known-size kernel against "
@@ -447,6 +450,13 @@ def main():
             r.update(metric=out["metric"], unit="tokens/s", note="weights as e4m3 codes + per-row scales; a different "
                      "precision from the bf16 headline (see DESIGN.md for its error against the bf16 oracle)")
             out["fp8_weights"][name] = r
+    if args.w4:
+        out["fp4_weights"] = {}
+        for name in ("c3", "c5"):
+            r = measure_verify(wl.get_workload(name).scaled(dtype="bf16w4"), args, dev)
+            r.update(metric=out["metric"], unit="tokens/s", note="weights as MXFP4 codes + block scales; a different "
+                     "precision from the bf16 headline (see DESIGN.md for its error against the bf16 oracle)")
+            out["fp4_weights"][name] = r
     if not args.no_cpu_baseline:
         sample = [0, w.N // 2, w.N - 1] if w.N > 3 else list(range(w.N))
         out["cpu_baseline"] = cpu_baseline(w, inp, sorted(set(sample)))

@@ -49,6 +49,7 @@ extern "C" {
 #define SEED_DTYPE_F32 0
 #define SEED_DTYPE_BF16 1
 #define SEED_DTYPE_BF16_W8 2 /* as BF16, but the projection matrices are one byte per weight (see seed_layer_w) */
+#define SEED_DTYPE_BF16_W4 3 /* as BF16, but the projection matrices are four bits per weight (see seed_layer_w) */
 
 /* seed_accept_args.probs_kind */
 #define SEED_KIND_LOGITS 0 /* p_or_logits holds raw logits; the kernel applies softmax(logits / temperature) */
@@ -63,7 +64,7 @@ typedef struct seed_ctx seed_ctx; /* opaque; one per model instance */
 
 typedef struct {
     int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
-    int32_t dtype;      /* SEED_DTYPE_F32, SEED_DTYPE_BF16 or SEED_DTYPE_BF16_W8 */
+    int32_t dtype;      /* SEED_DTYPE_F32, SEED_DTYPE_BF16, SEED_DTYPE_BF16_W8 or SEED_DTYPE_BF16_W4 */
     float rms_eps;      /* RMSNorm epsilon                    */
     float rope_theta;   /* rotary base; rotate-half pairing (i, i + head_dim/2) */
     int32_t max_branches;        /* largest N of any step (bf16: N * T <= 768 rows per step)  */
@@ -76,8 +77,13 @@ typedef struct {
     const void *wq, *wk, *wv, *wo;      /* [H*dh][d], [H*dh][d], [H*dh][d], [d][H*dh] */
     const void *wgate, *wup, *wdown;    /* [F][d], [F][d], [d][F]                     */
     const void *norm_attn, *norm_ffn;   /* [d] RMSNorm gains                          */
-    /* dtype SEED_DTYPE_BF16_W8 only (else ignored, may be NULL): float32 scale per output row of each matrix */
-    const float *sq, *sk, *sv, *so, *sgate, *sup, *sdown;
+    /* The seven matrices by dtype (norm gains, embedding: bf16 in every BF16* dtype):
+     *   SEED_DTYPE_BF16_W8: uint8 [rows][cols], OCP e4m3 codes; s* = float32 [rows], the weight is code * s[row];
+     *   SEED_DTYPE_BF16_W4: uint8 [rows][cols/2], OCP MXFP4: E2M1 codes, column c in the low (c even) or high
+     *     nibble of byte c/2; s* = uint8 [rows][cols/32], E8M0 block scales: the weight is code * 2^(s - 127) with s
+     *     the byte of its row and of its block of 32 consecutive columns;
+     *   otherwise s* are ignored and may be NULL. */
+    const void *sq, *sk, *sv, *so, *sgate, *sup, *sdown;
 } seed_layer_w;
 
 typedef struct {
@@ -85,7 +91,7 @@ typedef struct {
     const void *norm_final;     /* [d]                                       */
     const void *lm_head;        /* [V][d] (untied)                           */
     const seed_layer_w *layers; /* HOST array of n_layers entries            */
-    const float *lm_head_scale; /* [V], dtype SEED_DTYPE_BF16_W8 only        */
+    const void *lm_head_scale;  /* as the s* of seed_layer_w, for lm_head     */
 } seed_weights;
 
 /*

@@ -164,7 +164,7 @@ class ModelShape:
     head_dim: int
     d_ff: int
     vocab: int
-    dtype: str                    # "fp32" | "bf16" | "bf16w8" (projection matrices as e4m3 codes + row scales)
+    dtype: str                    # "fp32" | "bf16" | "bf16w8" (projection matrices as e4m3 codes + row scales) | "bf16w4" (MXFP4 codes + block scales)
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     max_branches: int = 16
@@ -174,7 +174,7 @@ class ModelShape:
 
     def to_c(self):
         return ModelCfgC(self.n_layers, self.d_model, self.n_heads, self.head_dim, self.d_ff, self.vocab,
-                         {"fp32": 0, "bf16": 1, "bf16w8": 2}[self.dtype], self.rms_eps, self.rope_theta, self.max_branches,
+                         {"fp32": 0, "bf16": 1, "bf16w8": 2, "bf16w4": 3}[self.dtype], self.rms_eps, self.rope_theta, self.max_branches,
                          self.max_rows_per_branch, self.max_shared, self.max_private)
 
 

@@ -91,6 +91,28 @@ __device__ __forceinline__ bf16x8 widen_e4m3(u32x2 c) {
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// 4-bit weights (context dtype SEED_DTYPE_BF16_W4): the OCP microscaling format MXFP4 -- elements are E2M1 codes
+// (sign, two exponent bits, one mantissa bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6), every 32 consecutive inputs of an output
+// feature share a power-of-two scale stored as an E8M0 byte (2^(e - 127)).  A k-tile is exactly one such block per
+// row: tile (nt, kt) is 256 bytes of codes, lane l holding the 8 codes of W[nt*16 + l%16][kt*32 + 8*(l/16) .. +8]
+// (input k in the low nibble of byte k/2 for even k), plus 16 scale bytes in a separate array [nt][kt][16].
+// On the way into the MFMA a code pair becomes a bf16 pair with the hardware's scaled conversion (exact: one
+// mantissa bit times a power of two), so the kernel computes with exactly the values the codes stand for.
+__device__ __forceinline__ bf16x8 widen_mxfp4(uint32_t c, uint32_t e8m0) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const float scale = __uint_as_float(e8m0 << 23);
+    u32x4 r;
+    const bf16x2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 0);
+    const bf16x2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 1);
+    const bf16x2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 2);
+    const bf16x2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 3);
+    r[0] = __builtin_bit_cast(uint32_t, p0);
+    r[1] = __builtin_bit_cast(uint32_t, p1);
+    r[2] = __builtin_bit_cast(uint32_t, p2);
+    r[3] = __builtin_bit_cast(uint32_t, p3);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // Which column group and which share of the rows this workgroup works on.  With MS > 1 the rows of a step are
 // split over MS workgroups per column group (TM row tiles each): every workgroup then stages and re-reads only
 // its own rows' activations through LDS -- the saturated resource at 65..128 rows -- and takes MS times the columns
@@ -416,7 +438,7 @@ __device__ __forceinline__ void finish_tiles(const GemmArgs &a, f32x4 (&acc)[TN]
     }
 }
 
-template <int TM, int TN, int WN, int WK, int EPI, bool W8>
+template <int TM, int TN, int WN, int WK, int EPI, int WB>   // WB: bits per weight (16, 8 or 4)
 __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     using S = Shape<TM, TN, WN, WK>;
     constexpr int U = S::U, KC = S::KC, D = S::D, XG = S::XG, kWaves = S::kWaves;
@@ -476,16 +498,26 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
             }
         }
     };
-    using WFrag = std::conditional_t<W8, u32x2, bf16x8>;   // a lane's piece of a weight tile: 8 codes or 8 bf16
-    const WFrag *wbase_f = reinterpret_cast<const WFrag *>(a.Wp) + lane;
+    constexpr bool W8 = WB == 8, W4 = WB == 4;
+    // a lane's piece of a weight tile: 8 bf16, 8 one-byte codes or 8 four-bit codes (with their block's scale)
+    struct Frag4 { uint32_t c, e; };
+    using WFrag = std::conditional_t<W4, Frag4, std::conditional_t<W8, u32x2, bf16x8>>;
+    using WLoad = std::conditional_t<W4, uint32_t, std::conditional_t<W8, u32x2, bf16x8>>;
+    const WLoad *wbase_f = reinterpret_cast<const WLoad *>(a.Wp) + lane;
     WFrag ring[D][U][TN];                                 // weight fragments in flight: D chunks ahead
     auto load_a = [&](WFrag (&dst)[U][TN], int k) {       // this wavefront's U k-tiles of the chunk at k
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                dst[u][tn] = __builtin_nontemporal_load(
-                    wbase_f + ((size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1)) * 64);
+            for (int tn = 0; tn < TN; ++tn) {
+                const size_t tile = (size_t)min(nt0 + tn, nt_last) * KT + min(k + wk * U + u, KT - 1);
+                if constexpr (W4) {
+                    dst[u][tn].c = __builtin_nontemporal_load(wbase_f + tile * 64);
+                    dst[u][tn].e = a.w_mx[tile * 16 + (lane & 15)];
+                } else {
+                    dst[u][tn] = __builtin_nontemporal_load(wbase_f + tile * 64);
+                }
+            }
     };
     // Prologue order: the first weight groups and the first activation chunk are requested at once; the
     // epilogue operands that do not depend on this launch follow (vector loads complete in order, so they are
@@ -566,7 +598,8 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                 bf16x8 wa[TN];
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
-                    if constexpr (W8) wa[tn] = widen_e4m3(ring[dd][u][tn]);
+                    if constexpr (W4) wa[tn] = widen_mxfp4(ring[dd][u][tn].c, ring[dd][u][tn].e);
+                    else if constexpr (W8) wa[tn] = widen_e4m3(ring[dd][u][tn]);
                     else wa[tn] = ring[dd][u][tn];
                 }
 #pragma unroll
@@ -885,6 +918,28 @@ __global__ void pack_scale_kernel(const float *__restrict__ src, float *__restri
     if (r < n_rows) dst[(size_t)(dst_tile0 + (r >> 4) * dst_tile_step) * 16 + (r & 15)] = src[r];
 }
 
+// ... and for four-bit weights: row-major codes [n_rows][K/2] into 256-byte tiles, the E8M0 block scales
+// [n_rows][K/32] into [n-tile][k-tile][16].
+__global__ void pack_weight4_kernel(const uint8_t *__restrict__ W, uint32_t *__restrict__ dst, int n_tiles, int K, int KT,
+                                    int dst_tile0, int dst_tile_step) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 4-byte fragment each
+    const size_t total = (size_t)n_tiles * KT * 64;
+    if (idx >= total) return;
+    const int lane = idx & 63;
+    const size_t tile = idx >> 6;
+    const int kt = tile % KT;
+    const int nt = tile / KT;
+    const uint8_t *src = W + ((size_t)(nt * 16 + (lane & 15)) * K + kt * 32 + 8 * (lane >> 4)) / 2;
+    dst[(((size_t)(dst_tile0 + nt * dst_tile_step)) * KT + kt) * 64 + lane] = *reinterpret_cast<const uint32_t *>(src);
+}
+__global__ void pack_mx_scale_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst, int n_rows, int KT,
+                                     int dst_tile0, int dst_tile_step) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one (row, k-tile) each
+    if (idx >= (size_t)n_rows * KT) return;
+    const int r = idx / KT, kt = idx % KT;
+    dst[((size_t)(dst_tile0 + (r >> 4) * dst_tile_step) * KT + kt) * 16 + (r & 15)] = src[idx];
+}
+
 template <int TM, int TN, int WN, int WK>
 int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
     using S = Shape<TM, TN, WN, WK>;
@@ -906,19 +961,23 @@ int launch_shape(const GemmArgs &a, int epi, hipStream_t st) {
         const int groups = (a.NT + WN * TN - 1) / (WN * TN);
         if (b.MS < 1) b.MS = 1;
         dim3 grid(b.MS > 1 ? (groups + 7) / 8 * 8 * b.MS : groups, b.SK), block(WN * WK * 64);
-        const bool w8 = b.w_scale != nullptr;
+        const int wb = b.w_mx != nullptr ? 4 : (b.w_scale != nullptr ? 8 : 16);
+#define SEEDV_LAUNCH(EPIv)                                                                                  \
+        do {                                                                                                \
+            if (wb == 4) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPIv, 4>), grid, block, 0, st, b);      \
+            else if (wb == 8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPIv, 8>), grid, block, 0, st, b); \
+            else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPIv, 16>), grid, block, 0, st, b);             \
+        } while (0)
         if (epi == EPI_SWIGLU) {
             if constexpr (TN >= 2) {
-                if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU, true>), grid, block, 0, st, b);
-                else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_SWIGLU, false>), grid, block, 0, st, b);
+                SEEDV_LAUNCH(EPI_SWIGLU);
             } else { set_error("gemm: SwiGLU epilogue needs paired tiles"); return SEED_E_INVALID_ARG; }
         } else if (epi == EPI_RESID) {
-            if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID, true>), grid, block, 0, st, b);
-            else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_RESID, false>), grid, block, 0, st, b);
+            SEEDV_LAUNCH(EPI_RESID);
         } else {
-            if (w8) hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE, true>), grid, block, 0, st, b);
-            else hipLaunchKernelGGL((gemm_kernel<TM, TN, WN, WK, EPI_STORE, false>), grid, block, 0, st, b);
+            SEEDV_LAUNCH(EPI_STORE);
         }
+#undef SEEDV_LAUNCH
         return hip_fail(hipGetLastError(), "gemm launch");
     }
 }
@@ -958,7 +1017,7 @@ int launch_wide_shape(const GemmArgs &a, int epi, hipStream_t st) {
                       a.NT * 16, a.part_floats);
             return SEED_E_CAPACITY;
         }
-        if (a.w_scale != nullptr) { set_error("gemm: the wide form streams bf16 weights only"); return SEED_E_UNSUPPORTED_DTYPE; }
+        if (a.w_scale != nullptr || a.w_mx != nullptr) { set_error("gemm: the wide form streams bf16 weights only"); return SEED_E_UNSUPPORTED_DTYPE; }
         if ((size_t)a.NT * a.KT * 1024 >= ((size_t)1 << 32)) {
             set_error("gemm: the wide form addresses weights with 32-bit offsets (matrix of %d x %d tiles)", a.NT, a.KT);
             return SEED_E_CAPACITY;
@@ -1222,7 +1281,7 @@ void gemm_bf16_pick_share(int NT, int KT, int epi, int m_tiles, int *wn, int *wk
 
 int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
     int wn, wk, tn, sk, wide, ms;
-    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, a.w_scale != nullptr);
+    gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, a.w_scale != nullptr || a.w_mx != nullptr);
     a.MS = ms;
     if (a.SK < 1) a.SK = sk;
     return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
@@ -1236,6 +1295,17 @@ int launch_pack_weight8(const void *codes, const float *scale, void *dst, float 
                        (const uint8_t *)codes, (uint2 *)dst, n_tiles, K, KT, dst_tile0, dst_tile_step);
     hipLaunchKernelGGL(pack_scale_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, scale, scale_dst, n_rows,
                        dst_tile0, dst_tile_step);
+    return hip_fail(hipGetLastError(), "pack launch");
+}
+
+int launch_pack_weight4(const void *codes, const void *mx_scale, void *dst, void *scale_dst, int n_rows, int K,
+                        int dst_tile0, int dst_tile_step, hipStream_t st) {
+    const int n_tiles = n_rows / 16, KT = K / 32;
+    const size_t total = (size_t)n_tiles * KT * 64;
+    hipLaunchKernelGGL(pack_weight4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t *)codes, (uint32_t *)dst, n_tiles, K, KT, dst_tile0, dst_tile_step);
+    hipLaunchKernelGGL(pack_mx_scale_kernel, dim3((unsigned)(((size_t)n_rows * KT + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t *)mx_scale, (uint8_t *)scale_dst, n_rows, KT, dst_tile0, dst_tile_step);
     return hip_fail(hipGetLastError(), "pack launch");
 }
 

@@ -85,7 +85,7 @@ struct Layout {
 
 int validate_cfg(const seed_model_cfg *c) {
     if (c == nullptr) { set_error("cfg is NULL"); return SEED_E_NULL_PTR; }
-    if (c->dtype != SEED_DTYPE_F32 && c->dtype != SEED_DTYPE_BF16 && c->dtype != SEED_DTYPE_BF16_W8) {
+    if (c->dtype != SEED_DTYPE_F32 && c->dtype != SEED_DTYPE_BF16 && c->dtype != SEED_DTYPE_BF16_W8 && c->dtype != SEED_DTYPE_BF16_W4) {
         set_error("unsupported dtype %d", c->dtype);
         return SEED_E_UNSUPPORTED_DTYPE;
     }
@@ -138,9 +138,9 @@ int validate_cfg(const seed_model_cfg *c) {
 Layout make_layout(const seed_model_cfg &c) {
     Layout L{};
     const bool bf = c.dtype != SEED_DTYPE_F32;
-    const bool w8 = c.dtype == SEED_DTYPE_BF16_W8;
+    const bool w8 = c.dtype == SEED_DTYPE_BF16_W8, w4 = c.dtype == SEED_DTYPE_BF16_W4;
     L.es = bf ? 2 : 4;
-    const size_t ws = w8 ? 1 : L.es;                // bytes per projection weight
+    const size_t wbits = w4 ? 4 : w8 ? 8 : 8 * L.es;   // bits per projection weight
     const size_t d = c.d_model, F = c.d_ff, V = c.vocab, H = c.n_heads, dh = c.head_dim;
     L.HD = (int)(H * dh);
     const size_t HD = L.HD;
@@ -154,23 +154,24 @@ Layout make_layout(const seed_model_cfg &c) {
     // one layer's weights
     size_t lo = 0;
     auto ltake = [&](size_t bytes) { size_t o = lo; lo = align_up(lo + bytes, 256); return o; };
-    L.w_qkv = ltake(3 * HD * d * ws);
-    L.w_o = ltake(d * HD * ws);
-    L.w_gu = ltake(2 * F * d * ws);
-    L.w_d = ltake(d * F * ws);
-    // (one-byte weights: per-output-row scales, in the order of the packed tiles)
-    L.s_qkv = ltake(w8 ? 3 * HD * 4 : 0);
-    L.s_o = ltake(w8 ? d * 4 : 0);
-    L.s_gu = ltake(w8 ? 2 * F * 4 : 0);
-    L.s_d = ltake(w8 ? d * 4 : 0);
+    L.w_qkv = ltake(3 * HD * d * wbits / 8);
+    L.w_o = ltake(d * HD * wbits / 8);
+    L.w_gu = ltake(2 * F * d * wbits / 8);
+    L.w_d = ltake(d * F * wbits / 8);
+    // (one-byte weights: per-output-row scales, in the order of the packed tiles; four-bit weights: one scale
+    // byte per output row and 32 inputs)
+    L.s_qkv = ltake(w8 ? 3 * HD * 4 : w4 ? 3 * HD * d / 32 : 0);
+    L.s_o = ltake(w8 ? d * 4 : w4 ? d * HD / 32 : 0);
+    L.s_gu = ltake(w8 ? 2 * F * 4 : w4 ? 2 * F * d / 32 : 0);
+    L.s_d = ltake(w8 ? d * 4 : w4 ? d * F / 32 : 0);
     L.g_attn = ltake(d * L.es);
     L.g_ffn = ltake(d * L.es);
     L.layer_stride = lo;
     L.layers0 = take(L.layer_stride * c.n_layers);
     L.emb = take(V * d * L.es);
     L.g_final = take(d * L.es);
-    L.lm = take(V * d * ws);
-    L.s_lm = take(w8 ? V * 4 : 256);
+    L.lm = take(V * d * wbits / 8);
+    L.s_lm = take(w8 ? V * 4 : w4 ? V * d / 32 : 256);
     L.ks_stride = align_up(H * L.cap_s * dh * L.es, 256);
     L.kp_stride = align_up((size_t)c.max_branches * H * L.cap_p * dh * L.es, 256);
     L.ks = take(L.ks_stride * c.n_layers);
@@ -220,6 +221,7 @@ struct seed_ctx {
     hipStream_t stream;
     bool bf16;
     bool w8;                             // projection matrices as e4m3 codes + per-row scales
+    bool w4;                             // ... as MXFP4 codes + per-block scales
     // projection-kernel profiling (seed_verify_profile_*)
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;     // start/stop pairs, reused
@@ -334,6 +336,7 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
     auto gemm = [&](int epi, const void *W, const void *scale, int Nout, int K, const void *Xp, GemmArgs a) -> int {
         a.Wp = W;
         a.w_scale = c->w8 ? (const float *)scale : nullptr;
+        a.w_mx = c->w4 ? (const uint8_t *)scale : nullptr;
         a.Xp = Xp;
         a.NT = Nout / 16;
         a.KT = K / 32;
@@ -343,14 +346,14 @@ int run_forward_bf16(seed_ctx *c, int N, int T, int S, int prefill_shared, const
         a.counters = (int *)at(c, L.counters);
         a.eps = g.rms_eps;
         int wn, wk, tn, sk, wide, ms;
-        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, c->w8);
+        gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, c->w8 || c->w4);
         while (sk > 1 && (size_t)sk * M * Nout > L.part_floats) --sk;
         a.SK = sk;
         if (sk > 1 && (a.NT / (wn * tn) + 8) * ms + 2 > kMaxCounters) {
             set_error("projection with %d column groups exceeds the counter array", a.NT / (wn * tn));
             return SEED_E_CAPACITY;
         }
-        return profiled(c, (double)Nout * K * (c->w8 ? 1.0 : 2.0), [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
+        return profiled(c, (double)Nout * K * (c->w4 ? 0.53125 : c->w8 ? 1.0 : 2.0), [&]() { return launch_gemm_bf16(a, epi, m_tiles, st); });
     };
 
     int ks_shared = 1, keys_per_range = 32, ks_priv = 0, keys_per_range_priv = 128;
@@ -529,7 +532,7 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
             return SEED_E_NULL_PTR;
         }
     }
-    if (cfg->dtype == SEED_DTYPE_BF16_W8) {
+    if (cfg->dtype == SEED_DTYPE_BF16_W8 || cfg->dtype == SEED_DTYPE_BF16_W4) {
         if (!w->lm_head_scale) { set_error("weights: lm_head_scale is NULL"); return SEED_E_NULL_PTR; }
         for (int l = 0; l < cfg->n_layers; ++l) {
             const seed_layer_w &lw = w->layers[l];
@@ -553,6 +556,7 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     c->stream = (hipStream_t)hip_stream;
     c->bf16 = cfg->dtype != SEED_DTYPE_F32;
     c->w8 = cfg->dtype == SEED_DTYPE_BF16_W8;
+    c->w4 = cfg->dtype == SEED_DTYPE_BF16_W4;
     hipStream_t st = c->stream;
     const size_t es = L.es, d = cfg->d_model, F = cfg->d_ff, V = cfg->vocab, HD = L.HD;
     auto copy = [&](void *dst, const void *src, size_t bytes) {
@@ -564,13 +568,23 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
         if (c->w8) {
             const int qt = (int)(HD / 16);
             float *sqkv = (float *)layer_w(c, l, L.s_qkv), *sgu = (float *)layer_w(c, l, L.s_gu);
-            SEEDV_TRY(launch_pack_weight8(lw.wq, lw.sq, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 0, 1, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wk, lw.sk, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, qt, 1, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wv, lw.sv, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 2 * qt, 1, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wo, lw.so, layer_w(c, l, L.w_o), (float *)layer_w(c, l, L.s_o), (int)d, (int)HD, 0, 1, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wgate, lw.sgate, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 0, 2, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wup, lw.sup, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 1, 2, st));
-            SEEDV_TRY(launch_pack_weight8(lw.wdown, lw.sdown, layer_w(c, l, L.w_d), (float *)layer_w(c, l, L.s_d), (int)d, (int)F, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wq, (const float *)lw.sq, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wk, (const float *)lw.sk, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, qt, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wv, (const float *)lw.sv, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 2 * qt, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wo, (const float *)lw.so, layer_w(c, l, L.w_o), (float *)layer_w(c, l, L.s_o), (int)d, (int)HD, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wgate, (const float *)lw.sgate, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 0, 2, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wup, (const float *)lw.sup, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 1, 2, st));
+            SEEDV_TRY(launch_pack_weight8(lw.wdown, (const float *)lw.sdown, layer_w(c, l, L.w_d), (float *)layer_w(c, l, L.s_d), (int)d, (int)F, 0, 1, st));
+        } else if (c->w4) {
+            const int qt = (int)(HD / 16);
+            void *sqkv = layer_w(c, l, L.s_qkv), *sgu = layer_w(c, l, L.s_gu);
+            SEEDV_TRY(launch_pack_weight4(lw.wq, lw.sq, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wk, lw.sk, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, qt, 1, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wv, lw.sv, layer_w(c, l, L.w_qkv), sqkv, (int)HD, (int)d, 2 * qt, 1, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wo, lw.so, layer_w(c, l, L.w_o), layer_w(c, l, L.s_o), (int)d, (int)HD, 0, 1, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wgate, lw.sgate, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 0, 2, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wup, lw.sup, layer_w(c, l, L.w_gu), sgu, (int)F, (int)d, 1, 2, st));
+            SEEDV_TRY(launch_pack_weight4(lw.wdown, lw.sdown, layer_w(c, l, L.w_d), layer_w(c, l, L.s_d), (int)d, (int)F, 0, 1, st));
         } else if (c->bf16) {
             const int qt = (int)(HD / 16);
             SEEDV_TRY(launch_pack_weight(lw.wq, layer_w(c, l, L.w_qkv), (int)HD, (int)d, 0, 1, st));
@@ -596,7 +610,8 @@ int seed_verify_init(seed_ctx **out, const seed_model_cfg *cfg, const seed_weigh
     }
     SEEDV_TRY(copy(at(c, L.emb), w->tok_emb, V * d * es));
     SEEDV_TRY(copy(at(c, L.g_final), w->norm_final, d * es));
-    if (c->w8) SEEDV_TRY(launch_pack_weight8(w->lm_head, w->lm_head_scale, at(c, L.lm), (float *)at(c, L.s_lm), (int)V, (int)d, 0, 1, st));
+    if (c->w8) SEEDV_TRY(launch_pack_weight8(w->lm_head, (const float *)w->lm_head_scale, at(c, L.lm), (float *)at(c, L.s_lm), (int)V, (int)d, 0, 1, st));
+    else if (c->w4) SEEDV_TRY(launch_pack_weight4(w->lm_head, w->lm_head_scale, at(c, L.lm), at(c, L.s_lm), (int)V, (int)d, 0, 1, st));
     else if (c->bf16) SEEDV_TRY(launch_pack_weight(w->lm_head, at(c, L.lm), (int)V, (int)d, 0, 1, st));
     else SEEDV_TRY(copy(at(c, L.lm), w->lm_head, V * d * es));
     // KV caches and scratch start at zero: chunked key loops may touch (masked) entries past the valid length

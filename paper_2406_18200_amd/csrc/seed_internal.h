@@ -71,6 +71,7 @@ struct GemmArgs {
     float *ssq;            // RESID: [M][NT] per-tile sums of squares of the new residual stream (out)
     float eps;
     const float *w_scale;  // 8-bit weights: one float per output feature, in packed tile order (NULL: bf16 weights)
+    const uint8_t *w_mx;   // 4-bit weights: E8M0 block scales [n-tile][k-tile][16] (NULL otherwise)
     int MS;                // row splits: MS workgroups per column group, each with 1 / MS of the row tiles (0 or 1: none)
 };
 void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
@@ -80,6 +81,8 @@ int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st);   // a.S
 int launch_pack_weight(const void *W, void *dst, int n_rows, int K, int dst_tile0, int dst_tile_step,
                        hipStream_t st);
 int launch_pack_weight8(const void *codes, const float *scale, void *dst, float *scale_dst, int n_rows, int K,
+                        int dst_tile0, int dst_tile_step, hipStream_t st);
+int launch_pack_weight4(const void *codes, const void *mx_scale, void *dst, void *scale_dst, int n_rows, int K,
                         int dst_tile0, int dst_tile_step, hipStream_t st);
 // ---- rowops.hip ----------------------------------------------------------------------------------
 int launch_rownorm(bool bf16, float *x, const float *part, int SK, int64_t split_stride, const int32_t *tok,

@@ -11,7 +11,7 @@ from workloads import gen
 from workloads.device import UploadingWeights, make_context, to_device, f32, i32
 from paper_2406_18200_amd import binding as B
 
-TOL = {"fp32": (1e-5, 1e-4), "bf16": (2e-2, 1e-2), "bf16w8": (2e-2, 1e-2)}   # (absolute, relative): |got - ref| <= abs + rel * |ref|
+TOL = {"fp32": (1e-5, 1e-4), "bf16": (2e-2, 1e-2), "bf16w8": (2e-2, 1e-2), "bf16w4": (2e-2, 1e-2)}   # (absolute, relative): |got - ref| <= abs + rel * |ref|
 
 
 def check_logits(got, ref, dtype):

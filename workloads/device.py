@@ -14,8 +14,28 @@ _MATRICES = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
 
 
 def _quantized(w, model, device, on_device=False):
-    """One-byte weights ("bf16w8"): (device codes uint8, device scales float32, dequantised float32 host copy).
+    """Narrow weights: (device codes uint8, device scales, dequantised float32 host copy).  "bf16w8": e4m3 codes and
+    float32 row scales; "bf16w4": MXFP4 codes (two per byte) and E8M0 block scales.
     on_device: timing runs only -- the same rule evaluated by torch on the GPU (no host copy, nothing to compare)."""
+    if model.dtype == "bf16w4":
+        if on_device:
+            t = torch.from_numpy(np.ascontiguousarray(w)).to(device)
+            n, k = t.shape
+            blocks = t.view(n, k // 32, 32)
+            amax = blocks.abs().amax(dim=2)
+            exp = torch.where(amax > 0, torch.floor(torch.log2(amax.clamp_min(1e-38))) - 2.0, torch.zeros_like(amax)).clamp(-126, 127)
+            x = (blocks / torch.exp2(exp)[:, :, None]).abs()
+            mids = (0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0)
+            idx = torch.zeros_like(x, dtype=torch.uint8)
+            for i, mid in enumerate(mids):
+                idx += ((x > mid) if i % 2 == 0 else (x >= mid)).to(torch.uint8)
+            idx |= (blocks < 0).to(torch.uint8) << 3
+            flat = idx.view(n, k)
+            codes = (flat[:, 0::2] | (flat[:, 1::2] << 4)).contiguous()
+            return codes, (exp + 127).to(torch.uint8).contiguous(), None
+        from .fp4 import quantize_blocks
+        codes, scale, deq = quantize_blocks(w)
+        return torch.from_numpy(codes).to(device), torch.from_numpy(scale).to(device), deq
     if on_device:
         t = torch.from_numpy(np.ascontiguousarray(w)).to(device)
         scale = (t.abs().amax(dim=1) / 448.0).clamp_min(1e-30)
@@ -55,7 +75,7 @@ class UploadingWeights:
 
     def lm_head(self):
         a = self.inner.lm_head()
-        if self.model.dtype == "bf16w8":
+        if self.model.dtype in ("bf16w8", "bf16w4"):
             # (the oracle gets the dequantised values: what the library's codes and scales stand for)
             if "lm_head_deq" not in self.dev:
                 self.dev["lm_head"], self.dev["lm_head_scale"], self.dev["lm_head_deq"] = _quantized(a, self.model, self.device, self.device_quantize)
@@ -65,7 +85,7 @@ class UploadingWeights:
 
     def layer(self, l):
         w = self.inner.layer(l)
-        if self.model.dtype == "bf16w8":
+        if self.model.dtype in ("bf16w8", "bf16w4"):
             out, dev = {}, {}
             for k, v in w.items():
                 if k in _MATRICES:
