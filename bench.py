@@ -448,14 +448,14 @@ def main():
         for name in ("c3", "c5"):
             r = measure_verify(wl.get_workload(name).scaled(dtype="bf16w8"), args, dev)
             r.update(metric=out["metric"], unit="tokens/s", note="weights as e4m3 codes + per-row scales; a different "
-                     "precision from the bf16 headline (see DESIGN.md for its error against the bf16 oracle)")
+                     "precision from the bf16 headline (tests/test_gpu_w8.py and test_gpu_w4.py print the formats' error against the bf16 weights)")
             out["fp8_weights"][name] = r
     if args.w4:
         out["fp4_weights"] = {}
         for name in ("c3", "c5"):
             r = measure_verify(wl.get_workload(name).scaled(dtype="bf16w4"), args, dev)
             r.update(metric=out["metric"], unit="tokens/s", note="weights as MXFP4 codes + block scales; a different "
-                     "precision from the bf16 headline (see DESIGN.md for its error against the bf16 oracle)")
+                     "precision from the bf16 headline (tests/test_gpu_w8.py and test_gpu_w4.py print the formats' error against the bf16 weights)")
             out["fp4_weights"][name] = r
     if not args.no_cpu_baseline:
         sample = [0, w.N // 2, w.N - 1] if w.N > 3 else list(range(w.N))
