@@ -30,6 +30,11 @@
 // 16 rows the workgroup that finishes last for a head (a per-head arrival counter) merges that head's
 // partials, otherwise a merge launch follows.  The shared-prefix prefill keeps the three-launch form (rotary
 // + cache append, partials, merge): its rows read the keys of their own chunk from the cache.
+// Steps with several row groups, at most eight rows per branch and short private contexts (the paper's shapes:
+// many branches, a few draft tokens each) use a lighter form of the branch tasks: one WAVEFRONT per (branch,
+// head) -- attn_task<SOLO> over the private keys, then inflight_solo for all in-flight rows of the head -- four
+// heads per workgroup, dispatched ahead of the shared-segment workgroups, whose number is chosen so that the
+// whole launch is resident at once (two workgroups per CU).
 //
 // The two S^T tiles of a 32-key chunk use the key order key = 8*(i/4) + (i%4) (+4 for the second tile),
 // which makes lane group g hold exactly keys 8g..8g+7 -- the B-operand layout the P.V MFMA wants.
