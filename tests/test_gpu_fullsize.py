@@ -53,3 +53,10 @@ def test_c5_13b_as_configured_perturbed_target_q():
 def test_c6_7b_state_evaluator_shape_sampled_branches():
     """No shared prefix, eight private contexts of 384..1024 tokens: the shortest, the longest and one between."""
     Case(wl.get_workload("c6"), branches=[0, 3, 7]).run_oracle().run_gpu().compare()
+
+
+def test_c8_7b_batch_sweep_768_rows_sampled_branches():
+    """The largest step of the batch sweep at full size: 128 branches x 6 drafts = 768 rows on the 7B shapes, in the
+    launch configuration bench.py times (row shares of the projections, 1792 attention workgroups); the first and
+    the last branch against the oracle."""
+    Case(wl.get_workload("c8"), branches=[0, 127]).run_oracle().run_gpu().compare()
