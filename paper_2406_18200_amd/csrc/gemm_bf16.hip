@@ -465,6 +465,12 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     const bool active = nt0 < a.NT;
     const int KT = a.KT;
     const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
+    // every column group walks its k range from its own starting chunk (see gemm_wide_kernel): virtual k-tile
+    // position v in [k0, k1) -> the k-tile actually read; only where the range is whole chunks
+    const int krange = k1 - k0;
+    const bool rot_ok = a.rot != 0 && krange > 0 && krange % (S::OU * XKT) == 0;
+    const int rotk = rot_ok ? ((cg * a.rot) % (krange / XKT)) * XKT : 0;
+    auto kmap = [&](int v) { return v < k1 ? (v + rotk >= k1 ? v + rotk - krange : v + rotk) : v; };
 
     f32x4 acc[TN][TM];
 #pragma unroll
@@ -525,9 +531,9 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
     // residual rows and the next norm's gain (RESID, small M), the input rows' sums of squares.  All of it is
     // straight-line code with clamped addresses: a branch around a load makes the compiler drain the whole
     // load queue where the paths join, which would hold back everything issued after it by a memory latency.
-    load_x(k0);
+    load_x(kmap(k0));
 #pragma unroll
-    for (int dd = 0; dd < D; ++dd) load_a(ring[dd], k0 + dd * KC);
+    for (int dd = 0; dd < D; ++dd) load_a(ring[dd], kmap(k0 + dd * KC));
     constexpr bool kPre = EPI == EPI_RESID && TM <= 2;
     const int g = lane >> 4, rlow = lane & 15;
     f32x4 x_pre[TN][TM];
@@ -581,7 +587,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
         lds_barrier();                                    // the previous chunk is no longer read
         store_x(kx);
         lds_barrier();
-        if (!LAST) load_x(kx + XKT);
+        if (!LAST) load_x(kmap(kx + XKT));
 #pragma unroll
         for (int gq = 0; gq < XG; ++gq) {
             const int dd = (oc * XG + gq) % D;            // OU * XG is a multiple of D: the slot is static
@@ -610,7 +616,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_kernel(GemmArgs a) {
                         acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[tn], bh[tm], acc[tn][tm], 0, 0, 0);
                     }
             }
-            if (!LAST || gq + D < XG) load_a(ring[dd], kc + D * KC);   // refill this slot D groups ahead (clamped)
+            if (!LAST || gq + D < XG) load_a(ring[dd], kmap(kc + D * KC));   // refill this slot D groups ahead (clamped)
         }
     };
     if constexpr (OU == 1) {
@@ -765,6 +771,15 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     const int KT = a.KT;
     const int k0 = blockIdx.y * a.kt_per_split, k1 = min(KT, k0 + a.kt_per_split);
     const int n_groups = (k1 - k0 + GK - 1) / GK;
+    // Every column group walks the k range from its own starting group: the workgroups of a launch start together
+    // and run in step (a barrier per group), so without this all of them read the same k position at the same
+    // time -- and the weights of different n-tiles at one k position lie KT KiB apart, i.e. on few memory
+    // channels.  Measured at 96 rows on the 7B shapes: QKV 34.4 -> 32.5 us, gate/up 52.6 -> 50.8, LM head 71 -> 66
+    // (any odd multiplier does the same).  The sums come out in another order per column group, still a fixed
+    // one.  Only where the range is whole groups (no ragged tail to meet in mid-walk).
+    const bool rot_ok = a.rot != 0 && (k1 - k0) % GK == 0 && n_groups > 1;
+    const int rot = rot_ok ? (cg * a.rot) % n_groups : 0;
+    auto kgroup = [&](int g) { return g < n_groups ? (g + rot >= n_groups ? g + rot - n_groups : g + rot) : g; };
 
     f32x4 acc[TN][TM];
 #pragma unroll
@@ -787,7 +802,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
         for (int i = 0; i < P; ++i) {
             const int f = w + i * kWaves;
             const int kk = f / (2 * TM), r = f - kk * (2 * TM);
-            const int kt = min(k0 + g * GK + kk, KT - 1);
+            const int kt = min(k0 + kgroup(g) * GK + kk, KT - 1);
             const bf16x8 *src = xp + (((size_t)min(mt0 + (r >> 1), mt_last) * KT + kt) * 2 + (r & 1)) * 64;
             __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(smem + base + f * 1024), 16,
                                              0, 0);
@@ -797,7 +812,7 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_wide_kernel(GemmArgs a) {
     auto load_a = [&](bf16x8 (&dst)[U][TN], int g) {     // this wavefront's k-tiles of group g (clamped)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const char *base = reinterpret_cast<const char *>(a.Wp) + (size_t)min(k0 + g * GK + wk * U + u, k1 - 1) * 1024;
+            const char *base = reinterpret_cast<const char *>(a.Wp) + (size_t)min(k0 + kgroup(g) * GK + wk * U + u, k1 - 1) * 1024;
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) load_weight_nt(dst[u][tn], base, woff[tn]);
         }
@@ -1137,6 +1152,8 @@ int launch_gemm_bf16_cfg(const GemmArgs &a, int epi, int m_tiles, int wn, int wk
 // rows: wide outputs share activation fragments across wavefronts (WN); narrow outputs split K inside the
 // workgroup (WK), over all eight wavefronts when that gives one workgroup per CU without a split across
 // workgroups (no partials to exchange), else over four with two workgroups along K.
+// Multiplier of the per-column-group rotation of the k walk (see gemm_wide_kernel); 0 switches it off.
+constexpr int kRotation = 3;
 // Row-split launches (65..128 rows): can be switched off for A/B measurements with SEED_GEMM_ROW_SPLIT=0.
 void gemm_bf16_pick_share(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
                           int w8);
@@ -1283,6 +1300,7 @@ int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
     int wn, wk, tn, sk, wide, ms;
     gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, a.w_scale != nullptr || a.w_mx != nullptr);
     a.MS = ms;
+    a.rot = kRotation;
     if (a.SK < 1) a.SK = sk;
     return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
 }

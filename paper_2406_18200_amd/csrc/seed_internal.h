@@ -72,6 +72,7 @@ struct GemmArgs {
     float eps;
     const float *w_scale;  // 8-bit weights: one float per output feature, in packed tile order (NULL: bf16 weights)
     const uint8_t *w_mx;   // 4-bit weights: E8M0 block scales [n-tile][k-tile][16] (NULL otherwise)
+    int rot;               // multiplier of the per-column-group rotation of the k walk (0: none)
     int MS;                // row splits: MS workgroups per column group, each with 1 / MS of the row tiles (0 or 1: none)
 };
 void gemm_bf16_pick(int NT, int KT, int epi, int m_tiles, int *wn, int *wk, int *tn, int *sk, int *wide, int *ms,
