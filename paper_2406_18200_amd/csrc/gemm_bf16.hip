@@ -1300,7 +1300,10 @@ int launch_gemm_bf16(GemmArgs a, int epi, int m_tiles, hipStream_t st) {
     int wn, wk, tn, sk, wide, ms;
     gemm_bf16_pick(a.NT, a.KT, epi, m_tiles, &wn, &wk, &tn, &sk, &wide, &ms, a.w_scale != nullptr || a.w_mx != nullptr);
     a.MS = ms;
-    a.rot = kRotation;
+    // (only while the whole activation matrix -- hi and lo halves of every row -- stays in an XCD's 4 MiB L2 next to
+    // the weight stream: workgroups at different k positions read different parts of it; at 384 rows and more
+    // the rotation cost the narrow outputs 25-45 %)
+    a.rot = (size_t)m_tiles * 16 * a.KT * 32 * 4 <= ((size_t)2 << 20) ? kRotation : 0;
     if (a.SK < 1) a.SK = sk;
     return launch_gemm_bf16_cfg(a, epi, m_tiles, wn, wk, tn, wide, st);
 }
